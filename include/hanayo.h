@@ -1,0 +1,220 @@
+/*
+ * hanayo.h -- C ABI of the per-rank hot path of a Hanayo wave pipeline on one
+ * MI355X (gfx950).
+ *
+ * The paper's runtime section describes a scheduler that emits, per worker, an
+ * ordered "action list" whose compute actions carry the local module rank, and
+ * an interpreter on each worker that executes the list.  This library is that
+ * pair for ONE worker: it generates the worker's ordered forward/backward task
+ * list for a (P devices, W waves, M micro-batches) wave pipeline, sizes the
+ * activation stash from the list, and executes the list with hand-written HIP
+ * kernels, stage boundaries being buffers in HBM instead of sends to peers.
+ *
+ * Conventions for every function
+ *   - returns HANAYO_OK (0) or a negative error code; never throws or aborts;
+ *     hanayo_last_error() gives a thread-local detail string
+ *   - "host" / "device" on a pointer says where the memory lives
+ *   - the library allocates no device memory: all device buffers belong to the
+ *     caller, must be 256-byte aligned, and must stay alive until the stream
+ *     has passed the work enqueued by the call
+ *   - device work is enqueued on the given HIP stream (a hipStream_t passed as
+ *     void*, NULL = default stream) and the call returns without synchronising
+ */
+#ifndef HANAYO_H
+#define HANAYO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  HANAYO_OK = 0,
+  HANAYO_EINVAL = -1,       /* bad argument (range, shape, NULL, misalignment) */
+  HANAYO_EBUFSIZE = -2,     /* caller's output buffer too small; needed size reported */
+  HANAYO_ESTATE = -3,       /* list not executable: B before its F, repeated task, stash overflow */
+  HANAYO_EUNSUPPORTED = -4, /* shape or device outside what the kernels cover (not gfx950, ...) */
+  HANAYO_EHIP = -5          /* a HIP runtime call or kernel launch failed */
+};
+
+const char* hanayo_strerror(int code); /* static string */
+const char* hanayo_last_error(void);   /* thread-local, valid until the next call on this thread */
+
+/* ------------------------------------------------------------------------- *
+ * Wave schedule (Table 1: W = S / 2P; sections on wave-like pipelines and the
+ * theoretical analysis).  S = 2*W*P stages; stage s sits on device
+ *   rank(s) = s mod P           if floor(s / P) is even
+ *           = P - 1 - (s mod P) if floor(s / P) is odd
+ * so a micro-batch runs down the devices and back W times and the two stages
+ * at every turn share a device.  "chunk" = floor(s / P) is the local module
+ * rank of the stage on its device (0 .. 2W-1).
+ * ------------------------------------------------------------------------- */
+
+enum { HANAYO_F = 0, HANAYO_B = 1 };
+
+typedef struct hanayo_task {
+  uint8_t kind;   /* HANAYO_F or HANAYO_B */
+  uint8_t chunk;  /* local chunk 0 .. 2W-1 */
+  uint16_t rsvd;  /* 0 */
+  uint32_t mb;    /* micro-batch 0 .. M-1 */
+  uint32_t stage; /* global stage 0 .. 2WP-1 */
+} hanayo_task;    /* 12 bytes, no padding */
+
+int hanayo_stage_rank(int P, int W, int stage, int* rank /* host out */);
+int hanayo_rank_stage(int P, int W, int rank, int chunk, int* stage /* host out */);
+
+/*
+ * Ordered task list of one rank.  The paper draws the order only in figures;
+ * the order produced is the deterministic greedy list schedule of the whole
+ * P-rank pipeline under the cost model of the theoretical analysis (forward 1,
+ * backward 2, transfer 0): a free rank starts a ready task, backward before
+ * forward, lowest micro-batch first; the forward of micro-batch m >= P on
+ * stage 0 waits for the forward of micro-batch m-P on the last stage.
+ *
+ * out: host, caller-owned, capacity `cap` records.  *n (host, required)
+ * always receives the needed count 4*W*M, also on HANAYO_EBUFSIZE (out may be
+ * NULL with cap 0 to query).  Pure and thread-safe.
+ * HANAYO_EINVAL: P, W or M < 1, rank outside [0, P), 2W > 255, n NULL.
+ */
+int hanayo_schedule(int P, int W, int M, int rank, hanayo_task* out, size_t cap, size_t* n);
+
+/*
+ * Activation-stash accounting of a list (M_a of Table 1 counted per chunk):
+ * an entry lives from the F task of (mb, chunk) to its B task.
+ *   peak_total  host out, may be NULL: peak number of live entries
+ *   per_chunk   host out [2W], may be NULL: peak live entries of each chunk
+ *   slot        host out [n], may be NULL: for an F task the smallest slot id
+ *               of its chunk that is free at that point, for a B task the id
+ *               its F took; always < per_chunk[chunk]
+ * HANAYO_ESTATE: a B whose (mb, chunk) is not live, an F of a live one, or
+ * entries left live at the end.  HANAYO_EINVAL: chunk >= 2W, bad kind.
+ */
+int hanayo_stash_plan(const hanayo_task* list /* host */, size_t n, int W, int* peak_total, int* per_chunk,
+                      int32_t* slot);
+
+/* ------------------------------------------------------------------------- *
+ * Chunk = n_blocks transformer blocks (the paper's T_F / 2W and T_B / 2W unit
+ * of work; the evaluation section gives the model families by layer, head and
+ * hidden counts only, so the block is the standard one):
+ *   pre-LN   x1 = x + Attn(LN1(x)),  y = x1 + MLP(LN2(x1))
+ *   post-LN  x1 = LN1(x + Attn(x)),  y = LN2(x1 + MLP(x1))
+ *   Attn(u) = softmax(Q K^T / sqrt(d) with masked keys removed) V Wo + bo
+ *   MLP(v)  = GELU_erf(v W1 + b1) W2 + b2,   LN with biased variance and eps
+ * ------------------------------------------------------------------------- */
+
+enum { HANAYO_PRE_LN = 0, HANAYO_POST_LN = 1 };
+enum { HANAYO_MASK_NONE = 0, HANAYO_MASK_CAUSAL = 1 };
+enum { HANAYO_FP32 = 0, HANAYO_BF16 = 1 }; /* storage type; accumulation is always fp32 */
+
+typedef struct hanayo_chunk_desc {
+  int n_blocks;
+  int hidden; /* H; multiple of 64 */
+  int heads;  /* H / heads must be 64 or 128 (fp32 storage: any multiple of 16 up to 128) */
+  int ffn;    /* F; multiple of 64 */
+  int seq;    /* s; multiple of 64 */
+  int mb;     /* sequences per micro-batch b; tokens T = b * s */
+  int norm;   /* HANAYO_PRE_LN / HANAYO_POST_LN */
+  int mask;   /* HANAYO_MASK_NONE / HANAYO_MASK_CAUSAL; key padding comes from valid_len */
+  int dtype;  /* HANAYO_FP32 / HANAYO_BF16 */
+  float ln_eps;
+} hanayo_chunk_desc;
+
+/*
+ * Parameter layout.  Weights are one packed array of the storage type, grads
+ * one packed fp32 array with the same element offsets.  Per block, in order
+ * (ids for hanayo_param_span):
+ *   0 ln1_gamma[H] 1 ln1_beta[H] 2 Wqkv[H][3H] 3 bqkv[3H] 4 Wo[H][H] 5 bo[H]
+ *   6 ln2_gamma[H] 7 ln2_beta[H] 8 W1[H][F]    9 b1[F]   10 W2[F][H] 11 b2[H]
+ * Matrices are row-major [in][out] (y = x W + b); Wqkv columns are [Q | K | V]
+ * and head j owns columns j*d .. (j+1)*d-1 of each third.
+ */
+enum { HANAYO_N_PARAMS = 12 };
+int hanayo_param_span(const hanayo_chunk_desc* d, int block, int param, size_t* elem_offset, size_t* elem_count);
+
+size_t hanayo_weight_bytes(const hanayo_chunk_desc* d);    /* 0 on a bad descriptor */
+size_t hanayo_grad_bytes(const hanayo_chunk_desc* d);      /* fp32 */
+size_t hanayo_stash_bytes(const hanayo_chunk_desc* d);     /* one (micro-batch, chunk) entry, multiple of 256 */
+size_t hanayo_workspace_bytes(const hanayo_chunk_desc* d); /* scratch shared by forward and backward */
+size_t hanayo_act_bytes(const hanayo_chunk_desc* d);       /* one [b][s][H] boundary tensor */
+
+/*
+ * Forward of one micro-batch through one chunk.
+ *   weights      device, packed parameters (read)
+ *   x            device [b][s][H] storage type (read)
+ *   valid_len    device int32 [b] or NULL: keys j >= valid_len[n] of sequence n are
+ *                masked for every query row; each must be in [1, s]
+ *   y            device [b][s][H] (fully overwritten; may not alias x)
+ *   stash_entry  device, hanayo_stash_bytes(): written here, read-only in backward;
+ *                holds a copy of x, so x may be reused once the call's work is done
+ *   workspace    device, hanayo_workspace_bytes(); contents undefined afterwards
+ */
+int hanayo_chunk_forward(const hanayo_chunk_desc* d, const void* weights, const void* x, const int32_t* valid_len,
+                         void* y, void* stash_entry, void* workspace, void* hip_stream);
+
+/*
+ * Backward of one micro-batch through one chunk.
+ *   grads        device fp32, packed like weights; every parameter gradient is ADDED
+ *                (caller zeroes at the start of an iteration: the flush boundary
+ *                of synchronous pipeline training)
+ *   dy           device [b][s][H] storage type, gradient of the loss w.r.t. y (read)
+ *   stash_entry  what the matching forward wrote (read)
+ *   dx           device [b][s][H] (fully overwritten; may not alias dy)
+ */
+int hanayo_chunk_backward(const hanayo_chunk_desc* d, const void* weights, float* grads, const void* dy,
+                          const int32_t* valid_len, const void* stash_entry, void* dx, void* workspace,
+                          void* hip_stream);
+
+/* ------------------------------------------------------------------------- *
+ * Per-rank task executor (the worker-side interpreter of the runtime section,
+ * compute actions only).  Runs `list` in order on one stream.  All chunks of
+ * the rank share one descriptor.  Tables are host arrays of device pointers
+ * indexed [mb * 2W + chunk].
+ *
+ * Forward input of (mb, chunk): if the previous stage is on this rank (the
+ * local turn-around) it is act_out[mb][chunk-1], else act_in[mb][chunk], a
+ * buffer the caller filled ("received" activation, or the data for stage 0).
+ * Forward output goes to act_out[mb][chunk] ("sent" activation).
+ * Backward input of (mb, chunk): if the next stage is on this rank it is
+ * grad_out[mb][chunk+1], else grad_in[mb][chunk] ("received" gradient, or the
+ * loss gradient for the last stage).  Backward output goes to
+ * grad_out[mb][chunk].  act_in / grad_in entries that are never read may be NULL.
+ *
+ * The stash arena is carved by the plan of `list`: chunk c owns
+ * per_chunk[c] entries starting after those of the chunks before it.
+ * ------------------------------------------------------------------------- */
+typedef struct hanayo_exec_args {
+  const hanayo_chunk_desc* desc;
+  int P, W, M, rank;
+  const void* const* weights;      /* host [2W] -> device */
+  float* const* grads;             /* host [2W] -> device fp32 */
+  const void* const* act_in;       /* host [M*2W] -> device */
+  const void* const* grad_in;      /* host [M*2W] -> device */
+  void* const* act_out;            /* host [M*2W] -> device */
+  void* const* grad_out;           /* host [M*2W] -> device */
+  const int32_t* const* valid_len; /* host [M] -> device int32 [b], or NULL */
+  void* stash_arena;               /* device */
+  size_t stash_arena_bytes;        /* >= hanayo_stash_arena_bytes() */
+  void* workspace;                 /* device, hanayo_workspace_bytes() */
+  void* hip_stream;
+} hanayo_exec_args;
+
+/* Arena size the executor needs for `list`; 0 on error. */
+size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const hanayo_chunk_desc* d);
+
+/*
+ * HANAYO_ESTATE if the list is not exactly the rank's 4*W*M tasks, each once,
+ * every B after its F and after the task it depends on locally; nothing is
+ * enqueued in that case.  *peak_seen (host, may be NULL) receives the largest
+ * number of stash entries that were live at once.
+ */
+int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_args* args, int* peak_seen);
+
+/* Library / device facts for reports: writes a NUL-terminated description. */
+int hanayo_device_info(char* buf /* host */, size_t cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HANAYO_H */

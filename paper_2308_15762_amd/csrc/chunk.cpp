@@ -1,0 +1,264 @@
+// chunk_forward / chunk_backward: the fixed kernel sequence of n_blocks
+// transformer blocks for one micro-batch (the paper's T_F / 2W and T_B / 2W
+// units of work), plus the dispatch between the MFMA and the ALU kernels.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstring>
+
+#include "kernels.h"
+
+namespace hanayo {
+
+namespace {
+
+// gfx950 check, cached per device.
+int check_device() {
+  static thread_local int ok_device = -1;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return set_error(HANAYO_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (dev == ok_device) return HANAYO_OK;
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return set_error(HANAYO_EHIP, "hipGetDeviceProperties: %s", hipGetErrorString(e));
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return set_error(HANAYO_EUNSUPPORTED, "device %d is %s, this library is built for gfx950 only", dev, prop.gcnArchName);
+  ok_device = dev;
+  return HANAYO_OK;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) != 0; }
+
+struct BlockPtrs {
+  const char* w[HANAYO_N_PARAMS];
+  float* g[HANAYO_N_PARAMS];
+};
+
+BlockPtrs block_ptrs(const Shape& sh, const ParamOffsets& po, const void* weights, float* grads, int blk) {
+  BlockPtrs bp;
+  for (int i = 0; i < HANAYO_N_PARAMS; ++i) {
+    const size_t e = (size_t)blk * po.block_elems + po.off[i];
+    bp.w[i] = static_cast<const char*>(weights) + e * sh.esz;
+    bp.g[i] = grads ? grads + e : nullptr;
+  }
+  return bp;
+}
+
+enum { P_LN1G, P_LN1B, P_WQKV, P_BQKV, P_WO, P_BO, P_LN2G, P_LN2B, P_W1, P_B1, P_W2, P_B2 };
+
+#define TRY(expr)          \
+  do {                     \
+    const int rc_ = (expr); \
+    if (rc_) return rc_;   \
+  } while (0)
+
+// y[T][N] = x[T][K] W[K][N] (+ epilogue)
+int linear_fwd(const Shape& sh, const void* x, const void* W, const void* bias, void* y, int K, int N, k::Epilogue epi,
+               const void* aux, void* aux_out, hipStream_t st) {
+  k::GemmArgs g{};
+  g.A = x; g.B = W; g.C = y; g.bias = bias; g.aux = aux; g.aux_out = aux_out;
+  g.M = sh.T; g.N = N; g.K = K; g.lda = K; g.ldb = N; g.ldc = N;
+  g.a_t = false; g.b_t = true; g.epi = epi;
+  return k::gemm(sh.dtype, g, st);
+}
+
+// dx[T][K] = dy[T][N] W[K][N]^T (+ epilogue)
+int linear_bwd_input(const Shape& sh, const void* dy, const void* W, void* dx, int K, int N, k::Epilogue epi,
+                     const void* aux, hipStream_t st) {
+  k::GemmArgs g{};
+  g.A = dy; g.B = W; g.C = dx; g.aux = aux;
+  g.M = sh.T; g.N = K; g.K = N; g.lda = N; g.ldb = N; g.ldc = K;
+  g.a_t = false; g.b_t = false; g.epi = epi;
+  return k::gemm(sh.dtype, g, st);
+}
+
+// dW[K][N] += x[T][K]^T dy[T][N];  db[N] += column sums of dy
+int linear_bwd_params(const Shape& sh, const void* x, const void* dy, float* dW, float* db, int K, int N, float* partial,
+                      hipStream_t st) {
+  k::GemmArgs g{};
+  g.A = x; g.B = dy; g.C = dW;
+  g.M = K; g.N = N; g.K = sh.T; g.lda = K; g.ldb = N; g.ldc = N;
+  g.a_t = true; g.b_t = true; g.epi = k::EPI_ACCUM_F32;
+  TRY(k::gemm(sh.dtype, g, st));
+  return k::colsum_add(sh.dtype, dy, sh.T, N, db, partial, st);
+}
+
+}  // namespace
+
+namespace k {
+
+int gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
+  if (g.M < 1 || g.N < 1 || g.K < 1) return set_error(HANAYO_EINVAL, "gemm: empty problem");
+  if (dtype == HANAYO_BF16 && gemm_mfma_supported(g)) return gemm_mfma(g, stream);
+  return gemm_alu(dtype, g, stream);
+}
+
+int attn_forward(int dtype, const AttnArgs& a, hipStream_t stream) {
+  if (dtype == HANAYO_BF16 && attn_mfma_supported(a)) return attn_forward_mfma(a, stream);
+  return attn_forward_alu(dtype, a, stream);
+}
+
+int attn_backward(int dtype, const AttnArgs& a, hipStream_t stream) {
+  if (dtype == HANAYO_BF16 && attn_mfma_supported(a)) return attn_backward_mfma(a, stream);
+  return attn_backward_alu(dtype, a, stream);
+}
+
+}  // namespace k
+
+int chunk_forward(const Shape& sh, const void* weights, const void* x, const int32_t* valid_len, void* y, void* stash,
+                  hipStream_t st) {
+  const ParamOffsets po = param_offsets(sh);
+  const StashLayout L = stash_layout(sh);
+  const int T = sh.T, H = sh.H, F = sh.F;
+  const size_t act_bytes = (size_t)T * H * sh.esz;
+  for (int blk = 0; blk < sh.nb; ++blk) {
+    char* sb = static_cast<char*>(stash) + (size_t)blk * L.block_bytes;
+    const BlockPtrs p = block_ptrs(sh, po, weights, nullptr, blk);
+    // block input: the caller's x for the first block (copied into the stash), else what the block before wrote
+    const void* xin = blk == 0 ? x : sb + L.x;
+    void* yout = blk == sh.nb - 1 ? y : sb + L.block_bytes + L.x;
+    k::AttnArgs at{};
+    at.qkv = sb + L.qkv; at.valid_len = valid_len; at.ctx = sb + L.ctx; at.lse = reinterpret_cast<float*>(sb + L.lse);
+    at.b = sh.b; at.s = sh.s; at.heads = sh.heads; at.d = sh.d; at.causal = sh.mask == HANAYO_MASK_CAUSAL;
+    if (sh.norm == HANAYO_PRE_LN) {
+      TRY(k::ln_forward(sh.dtype, xin, p.w[P_LN1G], p.w[P_LN1B], sb + L.ln_a, reinterpret_cast<float2*>(sb + L.stats1),
+                        blk == 0 ? sb + L.x : nullptr, T, H, sh.eps, st));
+      TRY(linear_fwd(sh, sb + L.ln_a, p.w[P_WQKV], p.w[P_BQKV], sb + L.qkv, H, 3 * H, k::EPI_BIAS, nullptr, nullptr, st));
+      TRY(k::attn_forward(sh.dtype, at, st));
+      TRY(linear_fwd(sh, sb + L.ctx, p.w[P_WO], p.w[P_BO], sb + L.x1, H, H, k::EPI_BIAS_RES, xin, nullptr, st));
+      TRY(k::ln_forward(sh.dtype, sb + L.x1, p.w[P_LN2G], p.w[P_LN2B], sb + L.ln_b, reinterpret_cast<float2*>(sb + L.stats2),
+                        nullptr, T, H, sh.eps, st));
+      TRY(linear_fwd(sh, sb + L.ln_b, p.w[P_W1], p.w[P_B1], sb + L.act, H, F, k::EPI_BIAS_GELU, nullptr, sb + L.hpre, st));
+      TRY(linear_fwd(sh, sb + L.act, p.w[P_W2], p.w[P_B2], yout, F, H, k::EPI_BIAS_RES, sb + L.x1, nullptr, st));
+    } else {
+      if (blk == 0) TRY(k::copy_bytes(sb + L.x, x, act_bytes, st));
+      TRY(linear_fwd(sh, xin, p.w[P_WQKV], p.w[P_BQKV], sb + L.qkv, H, 3 * H, k::EPI_BIAS, nullptr, nullptr, st));
+      TRY(k::attn_forward(sh.dtype, at, st));
+      TRY(linear_fwd(sh, sb + L.ctx, p.w[P_WO], p.w[P_BO], sb + L.ln_a, H, H, k::EPI_BIAS_RES, xin, nullptr, st));
+      TRY(k::ln_forward(sh.dtype, sb + L.ln_a, p.w[P_LN1G], p.w[P_LN1B], sb + L.x1, reinterpret_cast<float2*>(sb + L.stats1),
+                        nullptr, T, H, sh.eps, st));
+      TRY(linear_fwd(sh, sb + L.x1, p.w[P_W1], p.w[P_B1], sb + L.act, H, F, k::EPI_BIAS_GELU, nullptr, sb + L.hpre, st));
+      TRY(linear_fwd(sh, sb + L.act, p.w[P_W2], p.w[P_B2], sb + L.ln_b, F, H, k::EPI_BIAS_RES, sb + L.x1, nullptr, st));
+      TRY(k::ln_forward(sh.dtype, sb + L.ln_b, p.w[P_LN2G], p.w[P_LN2B], yout, reinterpret_cast<float2*>(sb + L.stats2),
+                        nullptr, T, H, sh.eps, st));
+    }
+  }
+  return HANAYO_OK;
+}
+
+int chunk_backward(const Shape& sh, const void* weights, float* grads, const void* dy, const int32_t* valid_len,
+                   const void* stash, void* dx, void* workspace, hipStream_t st) {
+  const ParamOffsets po = param_offsets(sh);
+  const StashLayout L = stash_layout(sh);
+  const WorkLayout WL = work_layout(sh);
+  char* ws = static_cast<char*>(workspace);
+  const int T = sh.T, H = sh.H, F = sh.F;
+  float* partial = reinterpret_cast<float*>(ws + WL.partial);
+  const void* dy_blk = dy;
+  for (int blk = sh.nb - 1; blk >= 0; --blk) {
+    const char* sb = static_cast<const char*>(stash) + (size_t)blk * L.block_bytes;
+    const BlockPtrs p = block_ptrs(sh, po, weights, grads, blk);
+    // gradient w.r.t. this block's input: the caller's dx for block 0, else a ping-pong buffer
+    void* dx_blk = blk == 0 ? dx : ws + ((blk & 1) ? WL.d_ping : WL.d_pong);
+    k::AttnArgs at{};
+    at.qkv = sb + L.qkv; at.valid_len = valid_len; at.ctx = const_cast<char*>(sb + L.ctx);
+    at.lse = reinterpret_cast<float*>(const_cast<char*>(sb + L.lse));
+    at.dqkv = ws + WL.d_qkv; at.delta = reinterpret_cast<float*>(ws + WL.delta);
+    at.b = sh.b; at.s = sh.s; at.heads = sh.heads; at.d = sh.d; at.causal = sh.mask == HANAYO_MASK_CAUSAL;
+    if (sh.norm == HANAYO_PRE_LN) {
+      // y = x1 + W2 GELU(W1 LN2(x1))
+      TRY(linear_bwd_params(sh, sb + L.act, dy_blk, p.g[P_W2], p.g[P_B2], F, H, partial, st));
+      TRY(linear_bwd_input(sh, dy_blk, p.w[P_W2], ws + WL.d_act, F, H, k::EPI_MUL_DGELU, sb + L.hpre, st));
+      TRY(linear_bwd_params(sh, sb + L.ln_b, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial, st));
+      TRY(linear_bwd_input(sh, ws + WL.d_act, p.w[P_W1], ws + WL.d_h0, H, F, k::EPI_NONE, nullptr, st));
+      // dx1 = dy + LN2'(d_h0)
+      TRY(k::ln_backward(sh.dtype, ws + WL.d_h0, sb + L.x1, p.w[P_LN2G], reinterpret_cast<const float2*>(sb + L.stats2),
+                         dy_blk, ws + WL.d_h1, p.g[P_LN2G], p.g[P_LN2B], partial, T, H, st));
+      // x1 = x + Wo ctx
+      TRY(linear_bwd_params(sh, sb + L.ctx, ws + WL.d_h1, p.g[P_WO], p.g[P_BO], H, H, partial, st));
+      TRY(linear_bwd_input(sh, ws + WL.d_h1, p.w[P_WO], ws + WL.d_h0, H, H, k::EPI_NONE, nullptr, st));
+      at.dctx = ws + WL.d_h0;
+      TRY(k::attn_backward(sh.dtype, at, st));
+      TRY(linear_bwd_params(sh, sb + L.ln_a, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial, st));
+      TRY(linear_bwd_input(sh, ws + WL.d_qkv, p.w[P_WQKV], ws + WL.d_h2, H, 3 * H, k::EPI_NONE, nullptr, st));
+      // dx = dx1 + LN1'(d_h2)
+      TRY(k::ln_backward(sh.dtype, ws + WL.d_h2, sb + L.x, p.w[P_LN1G], reinterpret_cast<const float2*>(sb + L.stats1),
+                         ws + WL.d_h1, dx_blk, p.g[P_LN1G], p.g[P_LN1B], partial, T, H, st));
+    } else {
+      // y = LN2(f), f = x1 + W2 GELU(W1 x1)
+      TRY(k::ln_backward(sh.dtype, dy_blk, sb + L.ln_b, p.w[P_LN2G], reinterpret_cast<const float2*>(sb + L.stats2),
+                         nullptr, ws + WL.d_h0, p.g[P_LN2G], p.g[P_LN2B], partial, T, H, st));
+      TRY(linear_bwd_params(sh, sb + L.act, ws + WL.d_h0, p.g[P_W2], p.g[P_B2], F, H, partial, st));
+      TRY(linear_bwd_input(sh, ws + WL.d_h0, p.w[P_W2], ws + WL.d_act, F, H, k::EPI_MUL_DGELU, sb + L.hpre, st));
+      TRY(linear_bwd_params(sh, sb + L.x1, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial, st));
+      // dx1 = df + d_act W1^T
+      TRY(linear_bwd_input(sh, ws + WL.d_act, p.w[P_W1], ws + WL.d_h1, H, F, k::EPI_ADD, ws + WL.d_h0, st));
+      // x1 = LN1(a), a = x + Wo ctx
+      TRY(k::ln_backward(sh.dtype, ws + WL.d_h1, sb + L.ln_a, p.w[P_LN1G], reinterpret_cast<const float2*>(sb + L.stats1),
+                         nullptr, ws + WL.d_h2, p.g[P_LN1G], p.g[P_LN1B], partial, T, H, st));
+      TRY(linear_bwd_params(sh, sb + L.ctx, ws + WL.d_h2, p.g[P_WO], p.g[P_BO], H, H, partial, st));
+      TRY(linear_bwd_input(sh, ws + WL.d_h2, p.w[P_WO], ws + WL.d_h0, H, H, k::EPI_NONE, nullptr, st));
+      at.dctx = ws + WL.d_h0;
+      TRY(k::attn_backward(sh.dtype, at, st));
+      TRY(linear_bwd_params(sh, sb + L.x, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial, st));
+      // dx = da + dqkv Wqkv^T
+      TRY(linear_bwd_input(sh, ws + WL.d_qkv, p.w[P_WQKV], dx_blk, H, 3 * H, k::EPI_ADD, ws + WL.d_h2, st));
+    }
+    dy_blk = dx_blk;
+  }
+  return HANAYO_OK;
+}
+
+int prepare_call(const hanayo_chunk_desc* d, Shape& sh) {
+  TRY(make_shape(d, sh));
+  return check_device();
+}
+
+}  // namespace hanayo
+
+using namespace hanayo;
+
+extern "C" {
+
+int hanayo_chunk_forward(const hanayo_chunk_desc* d, const void* weights, const void* x, const int32_t* valid_len,
+                         void* y, void* stash_entry, void* workspace, void* hip_stream) {
+  Shape sh;
+  TRY(prepare_call(d, sh));
+  (void)workspace;
+  if (!weights || !x || !y || !stash_entry) return set_error(HANAYO_EINVAL, "chunk_forward: NULL pointer");
+  if (misaligned(weights) || misaligned(x) || misaligned(y) || misaligned(stash_entry))
+    return set_error(HANAYO_EINVAL, "chunk_forward: device pointers must be 256-byte aligned");
+  if (x == y) return set_error(HANAYO_EINVAL, "chunk_forward: y aliases x");
+  return chunk_forward(sh, weights, x, valid_len, y, stash_entry, static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_chunk_backward(const hanayo_chunk_desc* d, const void* weights, float* grads, const void* dy,
+                          const int32_t* valid_len, const void* stash_entry, void* dx, void* workspace,
+                          void* hip_stream) {
+  Shape sh;
+  TRY(prepare_call(d, sh));
+  if (!weights || !grads || !dy || !dx || !stash_entry || !workspace)
+    return set_error(HANAYO_EINVAL, "chunk_backward: NULL pointer");
+  if (misaligned(weights) || misaligned(grads) || misaligned(dy) || misaligned(dx) || misaligned(stash_entry) ||
+      misaligned(workspace))
+    return set_error(HANAYO_EINVAL, "chunk_backward: device pointers must be 256-byte aligned");
+  if (dx == dy) return set_error(HANAYO_EINVAL, "chunk_backward: dx aliases dy");
+  return chunk_backward(sh, weights, grads, dy, valid_len, stash_entry, dx, workspace,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_device_info(char* buf, size_t cap) {
+  if (!buf || !cap) return set_error(HANAYO_EINVAL, "device_info: no buffer");
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return set_error(HANAYO_EHIP, "device_info: no HIP device");
+  }
+  std::snprintf(buf, cap, "%s %s CUs=%d clock_khz=%d", prop.name, prop.gcnArchName, prop.multiProcessorCount,
+                prop.clockRate);
+  return HANAYO_OK;
+}
+
+}  // extern "C"

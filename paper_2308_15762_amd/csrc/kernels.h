@@ -1,0 +1,87 @@
+// Host-side launchers of the HIP kernels.  Every launcher validates what the
+// kernel and its grid assume, enqueues on `stream`, and returns HANAYO_OK or an
+// error code (nothing is enqueued on error).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+
+namespace hanayo {
+namespace k {
+
+// ---- LayerNorm (row-wise over H; wavefront reductions) ----------------------
+// out = LN(x) * gamma + beta; stats[t] = (mean, rstd); copy_out (optional) = x.
+int ln_forward(int dtype, const void* x, const void* gamma, const void* beta, void* out, float2* stats, void* copy_out,
+               int T, int H, float eps, hipStream_t stream);
+// dz = LN'(dout) (+ addend, optional); dgamma += sum_t dout*xhat; dbeta += sum_t dout.
+// `partial` is scratch of at least kMaxPartialRows * 2H floats.
+int ln_backward(int dtype, const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend,
+                void* dz, float* dgamma, float* dbeta, float* partial, int T, int H, hipStream_t stream);
+// out[n] += sum_t in[t][n]
+int colsum_add(int dtype, const void* in, int T, int N, float* out, float* partial, hipStream_t stream);
+
+// ---- GEMM ---------------------------------------------------------------------
+enum Epilogue {
+  EPI_NONE = 0,       // C = acc
+  EPI_BIAS,           // C = acc + bias[n]
+  EPI_BIAS_GELU,      // aux_out = acc + bias[n];  C = GELU(aux_out)
+  EPI_BIAS_RES,       // C = acc + bias[n] + aux[m][n]
+  EPI_MUL_DGELU,      // C = acc * GELU'(aux[m][n])
+  EPI_ADD,            // C = acc + aux[m][n]
+  EPI_ACCUM_F32       // C (fp32) += acc
+};
+
+// C[M][N] = A[M][K] * B[K][N] with fp32 accumulation.
+//   a_t = false: A stored [M][lda] (K contiguous);  true: stored [K][lda] (M contiguous)
+//   b_t = false: B stored [N][ldb] (K contiguous);  true: stored [K][ldb] (N contiguous)
+// C, aux, aux_out are row-major [M][ldc]; bias is the storage type, [N].
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  const void* bias;
+  const void* aux;
+  void* aux_out;
+  int M, N, K;
+  int lda, ldb, ldc;
+  bool a_t, b_t;
+  Epilogue epi;
+};
+int gemm(int dtype, const GemmArgs& g, hipStream_t stream);
+
+// ---- attention ------------------------------------------------------------------
+// qkv is [b*s][3H] (Q | K | V, head j in columns j*d..), ctx [b*s][H], lse [b][heads][s].
+struct AttnArgs {
+  const void* qkv;
+  const int32_t* valid_len;  // device [b] or nullptr
+  void* ctx;                 // forward: out; backward: in
+  float* lse;                // forward: out; backward: in
+  const void* dctx;          // backward in
+  void* dqkv;                // backward out [b*s][3H]
+  float* delta;              // backward scratch [b][heads][s]
+  int b, s, heads, d;
+  bool causal;
+};
+int attn_forward(int dtype, const AttnArgs& a, hipStream_t stream);
+int attn_backward(int dtype, const AttnArgs& a, hipStream_t stream);
+
+// Implementations behind the dispatchers above.
+int gemm_alu(int dtype, const GemmArgs& g, hipStream_t stream);
+int attn_forward_alu(int dtype, const AttnArgs& a, hipStream_t stream);
+int attn_backward_alu(int dtype, const AttnArgs& a, hipStream_t stream);
+int attn_delta(int dtype, const AttnArgs& a, hipStream_t stream);  // delta = rowsum(dctx * ctx)
+bool gemm_mfma_supported(const GemmArgs& g);
+int gemm_mfma(const GemmArgs& g, hipStream_t stream);  // bf16 only
+bool attn_mfma_supported(const AttnArgs& a);
+int attn_forward_mfma(const AttnArgs& a, hipStream_t stream);
+int attn_backward_mfma(const AttnArgs& a, hipStream_t stream);
+
+// ---- misc ------------------------------------------------------------------------
+int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream);
+
+// Checks the last launch; returns HANAYO_EHIP with the HIP message on failure.
+int check_launch(const char* what);
+
+}  // namespace k
+}  // namespace hanayo

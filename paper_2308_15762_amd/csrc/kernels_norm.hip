@@ -1,0 +1,280 @@
+// LayerNorm forward / backward, column sums (bias gradients) and the partial-sum
+// finaliser.  All of them stream [T][H]-shaped tensors once and are bound by HBM
+// bandwidth: one wavefront owns a whole row, lanes read 8-element vectors so
+// that a wavefront touches 1 KiB (bf16) of contiguous memory per load, row
+// statistics are wavefront butterfly reductions, and per-column sums live in
+// registers across the rows a wavefront visits.
+#include "device_util.h"
+#include "kernels.h"
+
+namespace hanayo {
+namespace k {
+
+namespace {
+
+constexpr int kRowsPerBlock = 4;  // wavefronts per 256-thread block
+
+// ------------------------------------------------------------------ LN forward
+// NV = vectors of 8 per lane kept in registers (H <= 64 * 8 * NV).
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ out,
+                                                     float2* __restrict__ stats, T* __restrict__ copy_out, int rows,
+                                                     int H, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * H;
+  float v[NV][8];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 8;
+    if (c < H) {
+      load8(xr + c, v[i]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += v[i][j];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)H;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 8;
+    if (c < H) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float dlt = v[i][j] - mean;
+        sq += dlt * dlt;
+      }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)H + eps);
+  if (lane == 0) stats[row] = make_float2(mean, rstd);
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 8;
+    if (c < H) {
+      if (copy_out) store8(copy_out + (size_t)row * H + c, v[i]);
+      float g[8], b[8], o[8];
+      load8(gamma + c, g);
+      load8(beta + c, b);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
+      store8(out + (size_t)row * H + c, o);
+    }
+  }
+}
+
+// ------------------------------------------------------------------ LN backward
+// Each wavefront walks rows row0, row0 + stride, ...; its lanes keep the column
+// sums of dout*xhat and dout for their columns in registers.  The four
+// wavefronts of a block are then combined through LDS into one partial row.
+template <typename T, int NV>
+__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ x,
+                                                     const T* __restrict__ gamma, const float2* __restrict__ stats,
+                                                     const T* __restrict__ addend, T* __restrict__ dz,
+                                                     float* __restrict__ partial, int rows, int H) {
+  extern __shared__ float red[];  // [kRowsPerBlock][H]
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  float acc_g[NV][8], acc_b[NV][8], gm[NV][8];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 8;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = gm[i][j] = 0.f;
+    if (c < H) load8(gamma + c, gm[i]);
+  }
+  for (int row = blockIdx.x * kRowsPerBlock + wave; row < rows; row += gridDim.x * kRowsPerBlock) {
+    const float2 st = stats[row];
+    const size_t base = (size_t)row * H;
+    float xh[NV][8], dy[NV][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 8;
+      if (c < H) {
+        load8(x + base + c, xh[i]);
+        load8(dout + base + c, dy[i]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          xh[i][j] = (xh[i][j] - st.x) * st.y;
+          acc_g[i][j] += dy[i][j] * xh[i][j];
+          acc_b[i][j] += dy[i][j];
+          const float dxh = dy[i][j] * gm[i][j];
+          s1 += dxh;
+          s2 += dxh * xh[i][j];
+        }
+      }
+    }
+    const float c1 = wave_sum(s1) / (float)H;
+    const float c2 = wave_sum(s2) / (float)H;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 8;
+      if (c < H) {
+        float o[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) o[j] = (dy[i][j] * gm[i][j] - c1 - xh[i][j] * c2) * st.y;
+        if (addend) {
+          float a[8];
+          load8(addend + base + c, a);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[j] += a[j];
+        }
+        store8(dz + base + c, o);
+      }
+    }
+  }
+  // combine the block's four wavefronts: first the gamma sums, then the beta sums
+  for (int pass = 0; pass < 2; ++pass) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = (i * 64 + lane) * 8;
+      if (c < H) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) red[wave * H + c + j] = pass == 0 ? acc_g[i][j] : acc_b[i][j];
+      }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < H; c += blockDim.x) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < kRowsPerBlock; ++w) t += red[w * H + c];
+      partial[(size_t)blockIdx.x * 2 * H + pass * H + c] = t;
+    }
+    __syncthreads();
+  }
+}
+
+// out[c] += sum_r partial[r][c]   (one thread per column, rows in fixed order)
+__global__ void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n, float* __restrict__ out) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float t = 0.f;
+  for (int r = 0; r < rows; ++r) t += partial[(size_t)r * ld + c];
+  out[c] += t;
+}
+
+// ------------------------------------------------------------------ column sums
+// Block = 8 row groups x 32 lanes, each lane owning 8 consecutive columns.
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const T* __restrict__ in, int rows, int N,
+                                                     float* __restrict__ partial) {
+  __shared__ float red[8][256 + 8];
+  const int cl = (threadIdx.x & 31) * 8;
+  const int rg = threadIdx.x >> 5;
+  const int c = blockIdx.x * 256 + cl;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c < N) {
+    for (int r = blockIdx.y * 8 + rg; r < rows; r += gridDim.y * 8) {
+      float v[8];
+      load8(in + (size_t)r * N + c, v);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[j] += v[j];
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) red[rg][cl + j] = acc[j];
+  __syncthreads();
+  const int cc = blockIdx.x * 256 + threadIdx.x;
+  if (cc < N) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) t += red[g][threadIdx.x];
+    partial[(size_t)blockIdx.y * N + cc] = t;
+  }
+}
+
+template <typename T>
+int ln_forward_t(const void* x, const void* gamma, const void* beta, void* out, float2* stats, void* copy_out, int T_,
+                 int H, float eps, hipStream_t stream) {
+  const dim3 grid((T_ + kRowsPerBlock - 1) / kRowsPerBlock), block(256);
+  const int nv = (H + 511) / 512;
+#define LAUNCH(NV)                                                                                                 \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, NV>), grid, block, 0, stream, (const T*)x, (const T*)gamma, (const T*)beta, \
+                     (T*)out, stats, (T*)copy_out, T_, H, eps)
+  if (nv <= 1) LAUNCH(1);
+  else if (nv <= 2) LAUNCH(2);
+  else if (nv <= 4) LAUNCH(4);
+  else LAUNCH(8);
+#undef LAUNCH
+  return check_launch("ln_forward");
+}
+
+template <typename T>
+int ln_backward_t(const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend, void* dz,
+                  float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
+  int blocks = (T_ + kRowsPerBlock - 1) / kRowsPerBlock;
+  // two rows per wavefront when there are enough rows; never more partial rows than the scratch holds
+  if (blocks > 256) blocks = (blocks + 1) / 2;
+  if (blocks > kMaxPartialRows) blocks = kMaxPartialRows;
+  const size_t lds = (size_t)kRowsPerBlock * H * sizeof(float);
+  const int nv = (H + 511) / 512;
+#define LAUNCH(NV)                                                                                            \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NV>), dim3(blocks), dim3(256), lds, stream, (const T*)dout, (const T*)x, \
+                     (const T*)gamma, stats, (const T*)addend, (T*)dz, partial, T_, H)
+  if (nv <= 1) LAUNCH(1);
+  else if (nv <= 2) LAUNCH(2);
+  else if (nv <= 4) LAUNCH(4);
+  else LAUNCH(8);
+#undef LAUNCH
+  int rc = check_launch("ln_backward");
+  if (rc) return rc;
+  const dim3 fgrid((H + 255) / 256);
+  hipLaunchKernelGGL(finalize_kernel, fgrid, dim3(256), 0, stream, partial, blocks, 2 * H, H, dgamma);
+  hipLaunchKernelGGL(finalize_kernel, fgrid, dim3(256), 0, stream, partial + H, blocks, 2 * H, H, dbeta);
+  return check_launch("ln_backward finalize");
+}
+
+template <typename T>
+int colsum_t(const void* in, int T_, int N, float* out, float* partial, hipStream_t stream) {
+  int gy = (T_ + 31) / 32;
+  if (gy > 64) gy = 64;
+  if (gy < 1) gy = 1;
+  const dim3 grid((N + 255) / 256, gy);
+  hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, stream, (const T*)in, T_, N, partial);
+  int rc = check_launch("colsum");
+  if (rc) return rc;
+  hipLaunchKernelGGL(finalize_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, partial, gy, N, N, out);
+  return check_launch("colsum finalize");
+}
+
+}  // namespace
+
+int check_launch(const char* what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_error(HANAYO_EHIP, "%s: %s", what, hipGetErrorString(e));
+  return HANAYO_OK;
+}
+
+int ln_forward(int dtype, const void* x, const void* gamma, const void* beta, void* out, float2* stats, void* copy_out,
+               int T_, int H, float eps, hipStream_t stream) {
+  if (T_ < 1 || H < 8 || H % 8 || H > 4096) return set_error(HANAYO_EUNSUPPORTED, "ln_forward: H=%d (need multiple of 8, <= 4096)", H);
+  return dtype == HANAYO_BF16 ? ln_forward_t<bf16>(x, gamma, beta, out, stats, copy_out, T_, H, eps, stream)
+                              : ln_forward_t<float>(x, gamma, beta, out, stats, copy_out, T_, H, eps, stream);
+}
+
+int ln_backward(int dtype, const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend,
+                void* dz, float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
+  if (T_ < 1 || H < 8 || H % 8 || H > 4096) return set_error(HANAYO_EUNSUPPORTED, "ln_backward: H=%d (need multiple of 8, <= 4096)", H);
+  return dtype == HANAYO_BF16
+             ? ln_backward_t<bf16>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream)
+             : ln_backward_t<float>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream);
+}
+
+int colsum_add(int dtype, const void* in, int T_, int N, float* out, float* partial, hipStream_t stream) {
+  if (T_ < 1 || N < 8 || N % 8) return set_error(HANAYO_EUNSUPPORTED, "colsum: N=%d (need multiple of 8)", N);
+  return dtype == HANAYO_BF16 ? colsum_t<bf16>(in, T_, N, out, partial, stream)
+                              : colsum_t<float>(in, T_, N, out, partial, stream);
+}
+
+int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+  const hipError_t e = hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, stream);
+  if (e != hipSuccess) return set_error(HANAYO_EHIP, "copy: %s", hipGetErrorString(e));
+  return HANAYO_OK;
+}
+
+}  // namespace k
+}  // namespace hanayo

@@ -1,0 +1,254 @@
+"""ctypes binding of libhanayo.so: same names as include/hanayo.h, marshalling only.
+
+Device buffers are torch tensors (torch is used for device memory and streams
+only); a tensor argument is passed as its data pointer.  Every call raises
+HanayoError on a non-zero return code.  There is no fallback: if the library is
+missing this module fails to import.
+"""
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhanayo.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libhanayo.so is not built: run `python -m paper_2308_15762_amd.build`")
+_lib = ctypes.CDLL(LIB_PATH)
+
+OK, EINVAL, EBUFSIZE, ESTATE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4, -5
+F, B = 0, 1
+PRE_LN, POST_LN = 0, 1
+MASK_NONE, MASK_CAUSAL = 0, 1
+FP32, BF16 = 0, 1
+N_PARAMS = 12
+PARAM_NAMES = ("ln1_g", "ln1_b", "wqkv", "bqkv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+TASK_DTYPE = np.dtype([("kind", np.uint8), ("chunk", np.uint8), ("rsvd", np.uint16),
+                       ("mb", np.uint32), ("stage", np.uint32)])
+assert TASK_DTYPE.itemsize == 12
+
+
+class ChunkDesc(ctypes.Structure):
+    _fields_ = [("n_blocks", ctypes.c_int), ("hidden", ctypes.c_int), ("heads", ctypes.c_int),
+                ("ffn", ctypes.c_int), ("seq", ctypes.c_int), ("mb", ctypes.c_int),
+                ("norm", ctypes.c_int), ("mask", ctypes.c_int), ("dtype", ctypes.c_int),
+                ("ln_eps", ctypes.c_float)]
+
+
+class ExecArgs(ctypes.Structure):
+    _fields_ = [("desc", ctypes.POINTER(ChunkDesc)),
+                ("P", ctypes.c_int), ("W", ctypes.c_int), ("M", ctypes.c_int), ("rank", ctypes.c_int),
+                ("weights", ctypes.POINTER(ctypes.c_void_p)), ("grads", ctypes.POINTER(ctypes.c_void_p)),
+                ("act_in", ctypes.POINTER(ctypes.c_void_p)), ("grad_in", ctypes.POINTER(ctypes.c_void_p)),
+                ("act_out", ctypes.POINTER(ctypes.c_void_p)), ("grad_out", ctypes.POINTER(ctypes.c_void_p)),
+                ("valid_len", ctypes.POINTER(ctypes.c_void_p)),
+                ("stash_arena", ctypes.c_void_p), ("stash_arena_bytes", ctypes.c_size_t),
+                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p)]
+
+
+class HanayoError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        detail = _lib.hanayo_last_error().decode()
+        super().__init__("%s (%d): %s" % (_lib.hanayo_strerror(code).decode(), code, detail))
+
+
+EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
+           "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
+           "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_device_info")
+
+_vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+_descp = ctypes.POINTER(ChunkDesc)
+_lib.hanayo_strerror.restype = ctypes.c_char_p
+_lib.hanayo_strerror.argtypes = [_int]
+_lib.hanayo_last_error.restype = ctypes.c_char_p
+_lib.hanayo_last_error.argtypes = []
+_lib.hanayo_stage_rank.argtypes = [_int, _int, _int, ctypes.POINTER(_int)]
+_lib.hanayo_rank_stage.argtypes = [_int, _int, _int, _int, ctypes.POINTER(_int)]
+_lib.hanayo_schedule.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
+_lib.hanayo_stash_plan.argtypes = [_vp, _sz, _int, ctypes.POINTER(_int), _vp, _vp]
+_lib.hanayo_param_span.argtypes = [_descp, _int, _int, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
+for _n in ("hanayo_weight_bytes", "hanayo_grad_bytes", "hanayo_stash_bytes", "hanayo_workspace_bytes",
+           "hanayo_act_bytes"):
+    getattr(_lib, _n).restype = _sz
+    getattr(_lib, _n).argtypes = [_descp]
+_lib.hanayo_chunk_forward.argtypes = [_descp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.hanayo_chunk_backward.argtypes = [_descp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.hanayo_stash_arena_bytes.restype = _sz
+_lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
+_lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
+_lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
+
+
+def _check(rc):
+    if rc != OK:
+        raise HanayoError(rc)
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def make_desc(n_blocks, hidden, heads, ffn, seq, mb, norm, mask, dtype, ln_eps=1e-5):
+    return ChunkDesc(n_blocks, hidden, heads, ffn, seq, mb, norm, mask, dtype, ln_eps)
+
+
+def desc_for(wl):
+    """Descriptor of a synth.Workload."""
+    return make_desc(wl.n_blocks, wl.hidden, wl.heads, wl.ffn, wl.seq, wl.mb,
+                     PRE_LN if wl.norm == "pre" else POST_LN,
+                     MASK_CAUSAL if wl.causal else MASK_NONE,
+                     BF16 if wl.dtype == "bf16" else FP32)
+
+
+# ------------------------------------------------------------------ schedule
+
+def hanayo_stage_rank(P, W, stage):
+    out = _int()
+    _check(_lib.hanayo_stage_rank(P, W, stage, ctypes.byref(out)))
+    return out.value
+
+
+def hanayo_rank_stage(P, W, rank, chunk):
+    out = _int()
+    _check(_lib.hanayo_rank_stage(P, W, rank, chunk, ctypes.byref(out)))
+    return out.value
+
+
+def hanayo_schedule(P, W, M, rank):
+    """Ordered task list of one rank as a structured array (kind, chunk, rsvd, mb, stage)."""
+    n = _sz()
+    rc = _lib.hanayo_schedule(P, W, M, rank, None, 0, ctypes.byref(n))
+    if rc != EBUFSIZE:
+        _check(rc)
+    out = np.zeros(n.value, dtype=TASK_DTYPE)
+    _check(_lib.hanayo_schedule(P, W, M, rank, out.ctypes.data, out.size, ctypes.byref(n)))
+    return out
+
+
+def hanayo_stash_plan(tasks, W):
+    """Returns (peak_total, per_chunk[2W], slot[n])."""
+    tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
+    peak = _int()
+    per_chunk = np.zeros(2 * W, dtype=np.int32)
+    slot = np.zeros(tasks.size, dtype=np.int32)
+    _check(_lib.hanayo_stash_plan(tasks.ctypes.data, tasks.size, W, ctypes.byref(peak),
+                                  per_chunk.ctypes.data, slot.ctypes.data))
+    return peak.value, per_chunk, slot
+
+
+# ------------------------------------------------------------------ sizes / layout
+
+def hanayo_param_span(desc, block, param):
+    off, cnt = _sz(), _sz()
+    _check(_lib.hanayo_param_span(ctypes.byref(desc), block, param, ctypes.byref(off), ctypes.byref(cnt)))
+    return off.value, cnt.value
+
+
+def _size(fn, desc):
+    v = fn(ctypes.byref(desc))
+    if v == 0:
+        raise HanayoError(EINVAL)
+    return v
+
+
+def hanayo_weight_bytes(desc):
+    return _size(_lib.hanayo_weight_bytes, desc)
+
+
+def hanayo_grad_bytes(desc):
+    return _size(_lib.hanayo_grad_bytes, desc)
+
+
+def hanayo_stash_bytes(desc):
+    return _size(_lib.hanayo_stash_bytes, desc)
+
+
+def hanayo_workspace_bytes(desc):
+    return _size(_lib.hanayo_workspace_bytes, desc)
+
+
+def hanayo_act_bytes(desc):
+    return _size(_lib.hanayo_act_bytes, desc)
+
+
+def hanayo_stash_arena_bytes(tasks, W, desc):
+    tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
+    v = _lib.hanayo_stash_arena_bytes(tasks.ctypes.data, tasks.size, W, ctypes.byref(desc))
+    if v == 0:
+        raise HanayoError(ESTATE)
+    return v
+
+
+def hanayo_device_info():
+    buf = ctypes.create_string_buffer(256)
+    _check(_lib.hanayo_device_info(buf, 256))
+    return buf.value.decode()
+
+
+# ------------------------------------------------------------------ compute
+
+def hanayo_chunk_forward(desc, weights, x, valid_len, y, stash_entry, workspace, stream=None):
+    _check(_lib.hanayo_chunk_forward(ctypes.byref(desc), _ptr(weights), _ptr(x), _ptr(valid_len), _ptr(y),
+                                     _ptr(stash_entry), _ptr(workspace), stream))
+
+
+def hanayo_chunk_backward(desc, weights, grads, dy, valid_len, stash_entry, dx, workspace, stream=None):
+    _check(_lib.hanayo_chunk_backward(ctypes.byref(desc), _ptr(weights), _ptr(grads), _ptr(dy), _ptr(valid_len),
+                                      _ptr(stash_entry), _ptr(dx), _ptr(workspace), stream))
+
+
+def _table(items):
+    arr = (ctypes.c_void_p * len(items))()
+    for i, t in enumerate(items):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def hanayo_executor_run(tasks, desc, P, W, M, rank, weights, grads, act_in, grad_in, act_out, grad_out,
+                        valid_len, stash_arena, stash_arena_bytes, workspace, stream=None):
+    """Tables are Python lists of tensors / None: weights, grads [2W]; act_*, grad_* [M*2W]
+    indexed mb*2W+chunk; valid_len [M] or None.  Returns the stash peak seen."""
+    tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
+    tabs = [_table(t) for t in (weights, grads, act_in, grad_in, act_out, grad_out)]
+    vl = _table(valid_len) if valid_len is not None else None
+    args = ExecArgs(ctypes.pointer(desc), P, W, M, rank, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5],
+                    vl, _ptr(stash_arena), stash_arena_bytes, _ptr(workspace), stream)
+    peak = _int()
+    _check(_lib.hanayo_executor_run(tasks.ctypes.data, tasks.size, ctypes.byref(args), ctypes.byref(peak)))
+    return peak.value
+
+
+# ------------------------------------------------------------------ packing (layout marshalling only)
+
+def pack_params(desc, blocks):
+    """list of per-block dicts of float32 arrays -> flat float32 array in the packed order."""
+    total = hanayo_param_span(desc, desc.n_blocks - 1, N_PARAMS - 1)
+    flat = np.zeros(total[0] + total[1], dtype=np.float32)
+    for b, blk in enumerate(blocks):
+        for i, name in enumerate(PARAM_NAMES):
+            off, cnt = hanayo_param_span(desc, b, i)
+            flat[off:off + cnt] = np.asarray(blk[name], dtype=np.float32).reshape(-1)
+    return flat
+
+
+def unpack_params(desc, flat, like):
+    """flat array in the packed order -> list of per-block dicts shaped like `like`."""
+    out = []
+    for b, blk in enumerate(like):
+        d = {}
+        for i, name in enumerate(PARAM_NAMES):
+            off, cnt = hanayo_param_span(desc, b, i)
+            d[name] = np.asarray(flat[off:off + cnt]).reshape(np.shape(blk[name]))
+        out.append(d)
+    return out
