@@ -211,6 +211,56 @@ size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const 
  */
 int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_args* args, int* peak_seen);
 
+
+/* ------------------------------------------------------------------------- *
+ * Single kernels of the chunk path, exported so that each can be checked and
+ * timed on its own (per-kernel parity tests and roofline measurements).  Same
+ * conventions as above; `dtype` is HANAYO_FP32 / HANAYO_BF16.
+ * ------------------------------------------------------------------------- */
+
+enum {
+  HANAYO_EPI_NONE = 0,      /* C = acc */
+  HANAYO_EPI_BIAS = 1,      /* C = acc + bias[n] */
+  HANAYO_EPI_BIAS_GELU = 2, /* aux_out = acc + bias[n]; C = GELU(aux_out) */
+  HANAYO_EPI_BIAS_RES = 3,  /* C = acc + bias[n] + aux[m][n] */
+  HANAYO_EPI_MUL_DGELU = 4, /* C = acc * GELU'(aux[m][n]) */
+  HANAYO_EPI_ADD = 5,       /* C = acc + aux[m][n] */
+  HANAYO_EPI_ACCUM_F32 = 6  /* C is fp32 and is accumulated into: C += acc */
+};
+
+/*
+ * C[M][N] = A[M][K] B[K][N] with fp32 accumulation, then the epilogue.
+ *   a_t = 0: A stored [M][lda], K contiguous;  1: stored [K][lda], M contiguous
+ *   b_t = 0: B stored [N][ldb], K contiguous;  1: stored [K][ldb], N contiguous
+ * C, aux, aux_out are row-major with leading dimension ldc; bias has N entries.
+ * The forward linears use (a_t, b_t) = (0, 1), the input gradients (0, 0), the
+ * weight gradients (1, 1) with HANAYO_EPI_ACCUM_F32.
+ */
+int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
+                   int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out,
+                   void* hip_stream);
+
+/* out = LN(x) over the last dimension; stats[t] = (mean, rstd) as two floats;
+   copy_out (may be NULL) receives a copy of x. */
+int hanayo_op_layernorm_forward(int dtype, const void* x, const void* gamma, const void* beta, void* out,
+                                float* stats, void* copy_out, int rows, int hidden, float eps, void* hip_stream);
+/* dz = dLN(dout) (+ addend if not NULL); dgamma, dbeta (fp32, [hidden]) are added to.
+   scratch: device, at least 1024 * hidden floats. */
+int hanayo_op_layernorm_backward(int dtype, const void* dout, const void* x, const void* gamma, const float* stats,
+                                 const void* addend, void* dz, float* dgamma, float* dbeta, float* scratch, int rows,
+                                 int hidden, void* hip_stream);
+/* out[n] (fp32) += sum over rows of in[row][n].  scratch: at least 64 * n floats. */
+int hanayo_op_colsum_add(int dtype, const void* in, int rows, int n, float* out, float* scratch, void* hip_stream);
+
+/* qkv [b*s][3H] (Q | K | V), ctx [b*s][H], lse [b][heads][s] fp32 (log-sum-exp of the
+   scaled, masked scores).  Backward reads qkv, ctx, lse, dctx and writes all of
+   dqkv [b*s][3H]; delta is scratch [b][heads][s] fp32. */
+int hanayo_op_attention_forward(int dtype, const void* qkv, const int32_t* valid_len, void* ctx, float* lse, int b,
+                                int s, int heads, int head_dim, int causal, void* hip_stream);
+int hanayo_op_attention_backward(int dtype, const void* qkv, const int32_t* valid_len, const void* ctx,
+                                 const float* lse, const void* dctx, void* dqkv, float* delta, int b, int s,
+                                 int heads, int head_dim, int causal, void* hip_stream);
+
 /* Library / device facts for reports: writes a NUL-terminated description. */
 int hanayo_device_info(char* buf /* host */, size_t cap);
 

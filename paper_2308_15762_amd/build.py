@@ -9,8 +9,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhanayo.so")
 
 SOURCES = [
-    "schedule.cpp", "layout.cpp", "chunk.cpp", "executor.cpp",
-    "kernels_norm.hip", "kernels_generic.hip", "kernels_mfma_stub.hip",
+    "schedule.cpp", "layout.cpp", "chunk.cpp", "executor.cpp", "ops.cpp",
+    "kernels_norm.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_attn_mfma.hip",
 ]
 
 FLAGS = [

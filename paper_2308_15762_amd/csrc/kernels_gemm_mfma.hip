@@ -302,11 +302,11 @@ int gemm_mfma(const GemmArgs& g, hipStream_t stream) {
   const long tiles128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
   const bool big = tiles256 >= 256;
   int splits = 1;
-  if (g.epi == EPI_ACCUM_F32) {
-    // few output tiles, long reduction: split K so that about 512 workgroups exist
-    const long tiles = big ? tiles256 : tiles128;
+  if (g.epi == EPI_ACCUM_F32 && tiles128 < 64) {
+    // A handful of output tiles with a long reduction: split K (fp32 atomics are slow, so
+    // only when the machine would otherwise sit almost empty).
     const int ksteps = (g.K + BK - 1) / BK;
-    splits = (int)((512 + tiles - 1) / tiles);
+    splits = (int)((128 + tiles128 - 1) / tiles128);
     if (splits > ksteps) splits = ksteps;
     if (splits < 1) splits = 1;
   }

@@ -1,0 +1,91 @@
+// C entry points for the single kernels of the chunk path.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+using namespace hanayo;
+
+namespace hanayo {
+int prepare_call(const hanayo_chunk_desc* d, Shape& sh);
+}
+
+namespace {
+int check_dtype(int dtype) {
+  if (dtype != HANAYO_FP32 && dtype != HANAYO_BF16) return set_error(HANAYO_EINVAL, "dtype must be HANAYO_FP32 or HANAYO_BF16");
+  return HANAYO_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
+                   int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!A || !B || !C || M < 1 || N < 1 || K < 1) return set_error(HANAYO_EINVAL, "op_gemm: NULL operand or empty problem");
+  if (epilogue < HANAYO_EPI_NONE || epilogue > HANAYO_EPI_ACCUM_F32) return set_error(HANAYO_EINVAL, "op_gemm: epilogue");
+  if (lda < (a_t ? M : K) || ldb < (b_t ? N : K) || ldc < N) return set_error(HANAYO_EINVAL, "op_gemm: leading dimension too small");
+  const bool need_bias = epilogue == HANAYO_EPI_BIAS || epilogue == HANAYO_EPI_BIAS_GELU || epilogue == HANAYO_EPI_BIAS_RES;
+  const bool need_aux = epilogue == HANAYO_EPI_BIAS_RES || epilogue == HANAYO_EPI_MUL_DGELU || epilogue == HANAYO_EPI_ADD;
+  if ((need_bias && !bias) || (need_aux && !aux) || (epilogue == HANAYO_EPI_BIAS_GELU && !aux_out))
+    return set_error(HANAYO_EINVAL, "op_gemm: epilogue operand missing");
+  k::GemmArgs g{};
+  g.A = A; g.B = B; g.C = C; g.bias = bias; g.aux = aux; g.aux_out = aux_out;
+  g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.a_t = a_t != 0; g.b_t = b_t != 0; g.epi = static_cast<k::Epilogue>(epilogue);
+  return k::gemm(dtype, g, static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_op_layernorm_forward(int dtype, const void* x, const void* gamma, const void* beta, void* out, float* stats,
+                                void* copy_out, int rows, int hidden, float eps, void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!x || !gamma || !beta || !out || !stats || rows < 1) return set_error(HANAYO_EINVAL, "op_layernorm_forward: bad argument");
+  return k::ln_forward(dtype, x, gamma, beta, out, reinterpret_cast<float2*>(stats), copy_out, rows, hidden, eps,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_op_layernorm_backward(int dtype, const void* dout, const void* x, const void* gamma, const float* stats,
+                                 const void* addend, void* dz, float* dgamma, float* dbeta, float* scratch, int rows,
+                                 int hidden, void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!dout || !x || !gamma || !stats || !dz || !dgamma || !dbeta || !scratch || rows < 1)
+    return set_error(HANAYO_EINVAL, "op_layernorm_backward: bad argument");
+  return k::ln_backward(dtype, dout, x, gamma, reinterpret_cast<const float2*>(stats), addend, dz, dgamma, dbeta, scratch,
+                        rows, hidden, static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_op_colsum_add(int dtype, const void* in, int rows, int n, float* out, float* scratch, void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!in || !out || !scratch) return set_error(HANAYO_EINVAL, "op_colsum_add: NULL pointer");
+  return k::colsum_add(dtype, in, rows, n, out, scratch, static_cast<hipStream_t>(hip_stream));
+}
+
+static int attn_args(k::AttnArgs& a, int b, int s, int heads, int head_dim, int causal) {
+  if (b < 1 || s < 1 || heads < 1 || head_dim < 8 || head_dim % 8 || head_dim > 128)
+    return set_error(HANAYO_EINVAL, "op_attention: bad shape");
+  a.b = b; a.s = s; a.heads = heads; a.d = head_dim; a.causal = causal != 0;
+  return HANAYO_OK;
+}
+
+int hanayo_op_attention_forward(int dtype, const void* qkv, const int32_t* valid_len, void* ctx, float* lse, int b, int s,
+                                int heads, int head_dim, int causal, void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!qkv || !ctx || !lse) return set_error(HANAYO_EINVAL, "op_attention_forward: NULL pointer");
+  k::AttnArgs a{};
+  if (int rc = attn_args(a, b, s, heads, head_dim, causal)) return rc;
+  a.qkv = qkv; a.valid_len = valid_len; a.ctx = ctx; a.lse = lse;
+  return k::attn_forward(dtype, a, static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_op_attention_backward(int dtype, const void* qkv, const int32_t* valid_len, const void* ctx, const float* lse,
+                                 const void* dctx, void* dqkv, float* delta, int b, int s, int heads, int head_dim,
+                                 int causal, void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!qkv || !ctx || !lse || !dctx || !dqkv || !delta) return set_error(HANAYO_EINVAL, "op_attention_backward: NULL pointer");
+  k::AttnArgs a{};
+  if (int rc = attn_args(a, b, s, heads, head_dim, causal)) return rc;
+  a.qkv = qkv; a.valid_len = valid_len; a.ctx = const_cast<void*>(ctx); a.lse = const_cast<float*>(lse);
+  a.dctx = dctx; a.dqkv = dqkv; a.delta = delta;
+  return k::attn_backward(dtype, a, static_cast<hipStream_t>(hip_stream));
+}
+
+}  // extern "C"

@@ -10,6 +10,10 @@ import ctypes
 import os
 
 import numpy as np
+# torch ships its own HIP runtime (libamdhip64.so.7).  It has to be in the process before
+# libhanayo.so is loaded so that the loader binds the library to that same runtime: two HIP
+# runtimes in one process cannot both open the GPU.
+import torch  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhanayo.so")
@@ -58,7 +62,9 @@ class HanayoError(RuntimeError):
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
-           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_device_info")
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_device_info",
+           "hanayo_op_gemm", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
+           "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 _descp = ctypes.POINTER(ChunkDesc)
@@ -81,6 +87,13 @@ _lib.hanayo_stash_arena_bytes.restype = _sz
 _lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
+_lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp]
+_lib.hanayo_op_layernorm_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _vp, _vp, _int, _int, ctypes.c_float, _vp]
+_lib.hanayo_op_layernorm_backward.argtypes = [_int] + [_vp] * 9 + [_int, _int, _vp]
+_lib.hanayo_op_colsum_add.argtypes = [_int, _vp, _int, _int, _vp, _vp, _vp]
+_lib.hanayo_op_attention_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _int, _int, _int, _int, _int, _vp]
+_lib.hanayo_op_attention_backward.argtypes = [_int] + [_vp] * 7 + [_int] * 5 + [_vp]
+EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RES, EPI_MUL_DGELU, EPI_ADD, EPI_ACCUM_F32 = range(7)
 
 
 def _check(rc):
@@ -206,6 +219,38 @@ def hanayo_chunk_forward(desc, weights, x, valid_len, y, stash_entry, workspace,
 def hanayo_chunk_backward(desc, weights, grads, dy, valid_len, stash_entry, dx, workspace, stream=None):
     _check(_lib.hanayo_chunk_backward(ctypes.byref(desc), _ptr(weights), _ptr(grads), _ptr(dy), _ptr(valid_len),
                                       _ptr(stash_entry), _ptr(dx), _ptr(workspace), stream))
+
+
+def hanayo_op_gemm(dtype, A, B, C, M, N, K, lda, ldb, ldc, a_t, b_t, epilogue, bias=None, aux=None, aux_out=None,
+                   stream=None):
+    _check(_lib.hanayo_op_gemm(dtype, _ptr(A), _ptr(B), _ptr(C), M, N, K, lda, ldb, ldc, int(a_t), int(b_t), epilogue,
+                               _ptr(bias), _ptr(aux), _ptr(aux_out), stream))
+
+
+def hanayo_op_layernorm_forward(dtype, x, gamma, beta, out, stats, copy_out, rows, hidden, eps, stream=None):
+    _check(_lib.hanayo_op_layernorm_forward(dtype, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(out), _ptr(stats),
+                                            _ptr(copy_out), rows, hidden, eps, stream))
+
+
+def hanayo_op_layernorm_backward(dtype, dout, x, gamma, stats, addend, dz, dgamma, dbeta, scratch, rows, hidden,
+                                 stream=None):
+    _check(_lib.hanayo_op_layernorm_backward(dtype, _ptr(dout), _ptr(x), _ptr(gamma), _ptr(stats), _ptr(addend),
+                                             _ptr(dz), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), rows, hidden, stream))
+
+
+def hanayo_op_colsum_add(dtype, inp, rows, n, out, scratch, stream=None):
+    _check(_lib.hanayo_op_colsum_add(dtype, _ptr(inp), rows, n, _ptr(out), _ptr(scratch), stream))
+
+
+def hanayo_op_attention_forward(dtype, qkv, valid_len, ctx, lse, b, s, heads, head_dim, causal, stream=None):
+    _check(_lib.hanayo_op_attention_forward(dtype, _ptr(qkv), _ptr(valid_len), _ptr(ctx), _ptr(lse), b, s, heads,
+                                            head_dim, int(causal), stream))
+
+
+def hanayo_op_attention_backward(dtype, qkv, valid_len, ctx, lse, dctx, dqkv, delta, b, s, heads, head_dim, causal,
+                                 stream=None):
+    _check(_lib.hanayo_op_attention_backward(dtype, _ptr(qkv), _ptr(valid_len), _ptr(ctx), _ptr(lse), _ptr(dctx),
+                                             _ptr(dqkv), _ptr(delta), b, s, heads, head_dim, int(causal), stream))
 
 
 def _table(items):

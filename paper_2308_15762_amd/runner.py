@@ -1,0 +1,111 @@
+"""Device-side plumbing for callers of the binding: moves seeded host arrays into
+torch device tensors, owns the buffers one chunk or one rank needs, and calls
+the library.  No arithmetic of the method happens here."""
+
+import numpy as np
+import torch
+
+from . import hanayo as hn
+from . import synth
+
+
+def dev(a, dtype):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.bfloat16() if dtype == "bf16" else t
+
+
+def host(t):
+    return t.float().cpu().numpy()
+
+
+def dev_bytes(n):
+    return torch.empty(int(n), dtype=torch.uint8, device="cuda")
+
+
+class GpuChunk:
+    """One chunk's device state: packed weights, fp32 grads, workspace."""
+
+    def __init__(self, wl, params):
+        self.wl = wl
+        self.desc = hn.desc_for(wl)
+        self.params = params
+        self.weights = dev(hn.pack_params(self.desc, params), wl.dtype)
+        assert self.weights.numel() * self.weights.element_size() <= hn.hanayo_weight_bytes(self.desc)
+        self.grads = torch.zeros(hn.hanayo_grad_bytes(self.desc) // 4, dtype=torch.float32, device="cuda")
+        self.work = dev_bytes(hn.hanayo_workspace_bytes(self.desc))
+
+    def new_stash(self):
+        return dev_bytes(hn.hanayo_stash_bytes(self.desc))
+
+    def forward(self, x, valid_len=None, stash=None):
+        wl = self.wl
+        xd = dev(x, wl.dtype)
+        y = torch.empty_like(xd)
+        stash = self.new_stash() if stash is None else stash
+        vl = None if valid_len is None else torch.from_numpy(np.asarray(valid_len, dtype=np.int32)).cuda()
+        hn.hanayo_chunk_forward(self.desc, self.weights, xd, vl, y, stash, self.work)
+        torch.cuda.synchronize()
+        return host(y), (stash, vl)
+
+    def backward(self, dy, stash):
+        wl = self.wl
+        st, vl = stash
+        dyd = dev(dy, wl.dtype)
+        dx = torch.empty_like(dyd)
+        hn.hanayo_chunk_backward(self.desc, self.weights, self.grads, dyd, vl, st, dx, self.work)
+        torch.cuda.synchronize()
+        return host(dx)
+
+    def grad_dicts(self):
+        return hn.unpack_params(self.desc, self.grads.cpu().numpy(), self.params)
+
+
+class GpuRank:
+    """Device state of one rank of a workload: per-chunk weights/grads, boundary
+    tables, stash arena, workspace; runs a task list through hanayo_executor_run."""
+
+    def __init__(self, wl, rank=0, tasks=None, unique_outputs=True):
+        self.wl, self.rank = wl, rank
+        self.desc = hn.desc_for(wl)
+        P, W, M = wl.P, wl.W, wl.M
+        self.nchunk = 2 * W
+        self.tasks = hn.hanayo_schedule(P, W, M, rank) if tasks is None else tasks
+        self.params = [synth.chunk_params(wl, c) for c in range(self.nchunk)]
+        self.weights = [dev(hn.pack_params(self.desc, p), wl.dtype) for p in self.params]
+        self.grads = [torch.zeros(hn.hanayo_grad_bytes(self.desc) // 4, dtype=torch.float32, device="cuda")
+                      for _ in range(self.nchunk)]
+        self.work = dev_bytes(hn.hanayo_workspace_bytes(self.desc))
+        self.arena_bytes = hn.hanayo_stash_arena_bytes(self.tasks, W, self.desc)
+        self.arena = dev_bytes(self.arena_bytes)
+        S = 2 * W * P
+        n = M * self.nchunk
+        self.act_in, self.grad_in = [None] * n, [None] * n
+        self.act_out, self.grad_out = [None] * n, [None] * n
+        tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        shape = (wl.mb, wl.seq, wl.hidden)
+        for m in range(M):
+            for c in range(self.nchunk):
+                stage = hn.hanayo_rank_stage(P, W, rank, c)
+                i = m * self.nchunk + c
+                if not (stage > 0 and hn.hanayo_stage_rank(P, W, stage - 1) == rank):
+                    self.act_in[i] = dev(synth.forward_input(wl, m, c), wl.dtype)
+                if not (stage < S - 1 and hn.hanayo_stage_rank(P, W, stage + 1) == rank):
+                    self.grad_in[i] = dev(synth.upstream_grad(wl, m, c), wl.dtype)
+                self.act_out[i] = torch.empty(shape, dtype=tdt, device="cuda")
+                self.grad_out[i] = torch.empty(shape, dtype=tdt, device="cuda")
+        self.valid_len = None
+        if wl.valid_len_range is not None:
+            self.valid_len = [torch.from_numpy(synth.valid_lengths(wl, m)).cuda() for m in range(M)]
+
+    def zero_grads(self):
+        for g in self.grads:
+            g.zero_()
+
+    def run(self, tasks=None, stream=None):
+        wl = self.wl
+        return hn.hanayo_executor_run(self.tasks if tasks is None else tasks, self.desc, wl.P, wl.W, wl.M, self.rank,
+                                      self.weights, self.grads, self.act_in, self.grad_in, self.act_out,
+                                      self.grad_out, self.valid_len, self.arena, self.arena_bytes, self.work, stream)
+
+    def grad_dicts(self, chunk):
+        return hn.unpack_params(self.desc, self.grads[chunk].cpu().numpy(), self.params[chunk])

@@ -1,12 +1,11 @@
-"""Shared plumbing of the GPU parity tests: moves seeded host arrays to the
-device, calls the library through its binding, brings results back."""
+"""Shared plumbing of the GPU parity tests."""
 
 import numpy as np
-import torch
 
 from oracle import block as OB
 from paper_2308_15762_amd import hanayo as hn
 from paper_2308_15762_amd import synth
+from paper_2308_15762_amd.runner import GpuChunk, GpuRank, dev, dev_bytes, host  # noqa: F401
 
 TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
@@ -17,59 +16,8 @@ def nerr(got, ref):
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def dev(a, dtype):
-    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-    return t.bfloat16() if dtype == "bf16" else t
-
-
-def host(t):
-    return t.float().cpu().numpy()
-
-
-def dev_bytes(n):
-    return torch.empty(int(n), dtype=torch.uint8, device="cuda")
-
-
 def oracle_cfg(wl):
     return OB.BlockCfg(wl.hidden, wl.heads, wl.ffn, norm=wl.norm, causal=wl.causal)
-
-
-class GpuChunk:
-    """One chunk's device state: packed weights, fp32 grads, workspace."""
-
-    def __init__(self, wl, params):
-        self.wl = wl
-        self.desc = hn.desc_for(wl)
-        self.params = params
-        self.weights = dev(hn.pack_params(self.desc, params), wl.dtype)
-        assert self.weights.numel() * self.weights.element_size() <= hn.hanayo_weight_bytes(self.desc)
-        self.grads = torch.zeros(hn.hanayo_grad_bytes(self.desc) // 4, dtype=torch.float32, device="cuda")
-        self.work = dev_bytes(hn.hanayo_workspace_bytes(self.desc))
-
-    def new_stash(self):
-        return dev_bytes(hn.hanayo_stash_bytes(self.desc))
-
-    def forward(self, x, valid_len=None, stash=None):
-        wl = self.wl
-        xd = dev(x, wl.dtype)
-        y = torch.empty_like(xd)
-        stash = self.new_stash() if stash is None else stash
-        vl = None if valid_len is None else torch.from_numpy(np.asarray(valid_len, dtype=np.int32)).cuda()
-        hn.hanayo_chunk_forward(self.desc, self.weights, xd, vl, y, stash, self.work)
-        torch.cuda.synchronize()
-        return host(y), (stash, vl)
-
-    def backward(self, dy, stash):
-        wl = self.wl
-        st, vl = stash
-        dyd = dev(dy, wl.dtype)
-        dx = torch.empty_like(dyd)
-        hn.hanayo_chunk_backward(self.desc, self.weights, self.grads, dyd, vl, st, dx, self.work)
-        torch.cuda.synchronize()
-        return host(dx)
-
-    def grad_dicts(self):
-        return hn.unpack_params(self.desc, self.grads.cpu().numpy(), self.params)
 
 
 def compare_grads(got, ref, tol, label=""):
@@ -80,3 +28,13 @@ def compare_grads(got, ref, tol, label=""):
             worst = max(worst, e)
             assert e <= tol, "%s block %d %s: normalised error %.3g > %.3g" % (label, bi, name, e, tol)
     return worst
+
+
+def oracle_rank(wl, rank, tasks):
+    """The oracle's execution of the same list on the same seeded inputs."""
+    from oracle import executor as OE
+    params = [synth.chunk_params(wl, c) for c in range(2 * wl.W)]
+    vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
+    lst = [(int(t["kind"]), int(t["mb"]), int(t["chunk"]), int(t["stage"])) for t in tasks]
+    return OE.run_rank(lst, wl.P, wl.W, rank, oracle_cfg(wl), params,
+                       lambda m, c: synth.forward_input(wl, m, c), lambda m, c: synth.upstream_grad(wl, m, c), vl)
