@@ -13,6 +13,8 @@
 // The MFMA is issued with the operands swapped (B fragment first), so a lane's
 // accumulator registers hold 4 consecutive columns of one row of C and the
 // epilogue moves 8-byte (bf16) or 16-byte (fp32) vectors.
+#include <type_traits>
+
 #include "device_util.h"
 #include "epilogue.h"
 #include "kernels.h"
@@ -50,14 +52,19 @@ struct TileMover {
   static constexpr int kPerThread = kVecs / 256;
   static_assert(kVecs % 256 == 0, "tile must split evenly over 256 threads");
 
+  template <bool EVEN>
   __device__ static void load(const bf16* __restrict__ g, int ld, int row0, int col0, int row_lim, int col_lim,
                               bf16x8 (&r)[kPerThread]) {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       const int v = threadIdx.x + i * 256;
       const int row = row0 + v / kVecPerRow, col = col0 + (v % kVecPerRow) * 8;
-      bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-      r[i] = (row < row_lim && col < col_lim) ? *reinterpret_cast<const bf16x8*>(g + (size_t)row * ld + col) : z;
+      if constexpr (EVEN) {
+        r[i] = *reinterpret_cast<const bf16x8*>(g + (size_t)row * ld + col);
+      } else {
+        bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        r[i] = (row < row_lim && col < col_lim) ? *reinterpret_cast<const bf16x8*>(g + (size_t)row * ld + col) : z;
+      }
     }
   }
   template <int PITCH>
@@ -96,7 +103,8 @@ __device__ __forceinline__ bf16x8 frag_transposed(const bf16* lds, int r0, int k
   return u.v;
 }
 
-template <int BM, int BN, int BK, bool A_T, bool B_T, int EPI>
+// EVEN: M, N and the K range are whole multiples of the tile, so no load or store is guarded.
+template <int BM, int BN, int BK, bool A_T, bool B_T, int EPI, bool EVEN>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDev p) {
   constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
   constexpr int PA = A_T ? BM + kPadT : BK + kPadK;  // LDS pitch (elements) of the A tile
@@ -128,10 +136,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDev p) {
   bf16x8 ra[MoveA::kPerThread], rb[MoveB::kPerThread];
   auto fetch = [&](int kt) {
     const int k0 = k_begin + kt * BK;
-    if (A_T) MoveA::load(p.A, p.lda, k0, m0, k_end, p.M, ra);
-    else MoveA::load(p.A, p.lda, m0, k0, p.M, k_end, ra);
-    if (B_T) MoveB::load(p.B, p.ldb, k0, n0, k_end, p.N, rb);
-    else MoveB::load(p.B, p.ldb, n0, k0, p.N, k_end, rb);
+    if (A_T) MoveA::template load<EVEN>(p.A, p.lda, k0, m0, k_end, p.M, ra);
+    else MoveA::template load<EVEN>(p.A, p.lda, m0, k0, p.M, k_end, ra);
+    if (B_T) MoveB::template load<EVEN>(p.B, p.ldb, k0, n0, k_end, p.N, rb);
+    else MoveB::template load<EVEN>(p.B, p.ldb, n0, k0, p.N, k_end, rb);
   };
   auto stage = [&](int buf) {
     bf16* a = lds + buf * (A_ELEMS + B_ELEMS);
@@ -144,43 +152,77 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDev p) {
     stage(0);
   }
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
+  // One K tile: prefetch the next tile into registers, run the MFMAs of this one from LDS,
+  // park the prefetched tile in the other LDS buffer.  `more` is a compile-time flag so that the
+  // last tile carries no branch inside the scheduled region.
+  auto k_tile = [&](int kt, auto more) {
+    constexpr bool kMore = decltype(more)::value;
     const bf16* a_lds = lds + (kt & 1) * (A_ELEMS + B_ELEMS);
     const bf16* b_lds = a_lds + A_ELEMS;
-    if (kt + 1 < nk) fetch(kt + 1);
-#pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+    if constexpr (kMore) fetch(kt + 1);
+    // fragments of step kk+1 are requested from LDS before the MFMAs of step kk are issued
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int kk, int slot) {
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        fa[i] = A_T ? frag_transposed<PA>(a_lds, wm * WM + i * 32, kk, lane)
-                    : frag_kcontig<PA>(a_lds, wm * WM + i * 32, kk, lane);
+        fa[slot][i] = A_T ? frag_transposed<PA>(a_lds, wm * WM + i * 32, kk, lane)
+                          : frag_kcontig<PA>(a_lds, wm * WM + i * 32, kk, lane);
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        fb[j] = B_T ? frag_transposed<PB>(b_lds, wn * WN + j * 32, kk, lane)
-                    : frag_kcontig<PB>(b_lds, wn * WN + j * 32, kk, lane);
+        fb[slot][j] = B_T ? frag_transposed<PB>(b_lds, wn * WN + j * 32, kk, lane)
+                          : frag_kcontig<PB>(b_lds, wn * WN + j * 32, kk, lane);
+    };
+    read_frags(0, 0);
+    __builtin_amdgcn_sched_barrier(0);  // step 0's own reads stay ahead of the interleaved region
+    constexpr int kDsPerStep = (A_T ? 2 : 1) * TM + (B_T ? 2 : 1) * TN;  // LDS reads of one kk step
+    constexpr int kMfmaPerStep = TM * TN;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      if (kk + 1 < BK / 16) read_frags(kk + 1, (kk + 1) & 1);
+      else if constexpr (kMore) stage((kt + 1) & 1);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      // Issue order inside the step: LDS traffic spread evenly between the MFMAs, so the
+      // reads for the next step (or the writes of the next tile) complete under this step's math.
+      if (kk + 1 < BK / 16) {
+        constexpr int kRatio = kMfmaPerStep >= kDsPerStep ? kMfmaPerStep / kDsPerStep : 1;
+        constexpr int kDsEach = kMfmaPerStep >= kDsPerStep ? 1 : (kDsPerStep + kMfmaPerStep - 1) / kMfmaPerStep;
+#pragma unroll
+        for (int g = 0; g < (kMfmaPerStep >= kDsPerStep ? kDsPerStep : kMfmaPerStep); ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x100, kDsEach, 0);  // DS read
+          __builtin_amdgcn_sched_group_barrier(0x008, kRatio, 0);   // MFMA
+        }
+      } else if constexpr (kMore) {
+        constexpr int kWrites = MoveA::kPerThread + MoveB::kPerThread;
+        constexpr int kRatio = kMfmaPerStep >= kWrites ? kMfmaPerStep / kWrites : 1;
+        constexpr int kWrEach = kMfmaPerStep >= kWrites ? 1 : (kWrites + kMfmaPerStep - 1) / kMfmaPerStep;
+#pragma unroll
+        for (int g = 0; g < (kMfmaPerStep >= kWrites ? kWrites : kMfmaPerStep); ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x200, kWrEach, 0);  // DS write
+          __builtin_amdgcn_sched_group_barrier(0x008, kRatio, 0);   // MFMA
+        }
+      }
     }
-    if (kt + 1 < nk) stage((kt + 1) & 1);
     __syncthreads();
-  }
+  };
+  for (int kt = 0; kt + 1 < nk; ++kt) k_tile(kt, std::true_type{});
+  if (nk > 0) k_tile(nk - 1, std::false_type{});
 
   // Epilogue.  Register group q of a tile holds columns n .. n+3 of row m with
   //   m = tile_m + lane % 32,  n = tile_n + 8 q + 4 (lane / 32).
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = m0 + wm * WM + i * 32 + (lane & 31);
-    if (m >= p.M) continue;
+    if (!EVEN && m >= p.M) continue;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * (lane >> 5);
-        if (n >= p.N) continue;
+        if (!EVEN && n >= p.N) continue;
         const size_t at = (size_t)m * p.ldc + n;
         float v[4];
 #pragma unroll
@@ -237,10 +279,10 @@ constexpr size_t lds_bytes() {
   return 2 * ((A_T ? BK : BM) * PA + (B_T ? BK : BN) * PB) * sizeof(bf16);
 }
 
-template <int BM, int BN, int BK, bool A_T, bool B_T, int EPI>
-int launch(const GemmDev& p, int splits, hipStream_t stream) {
+template <int BM, int BN, int BK, bool A_T, bool B_T, int EPI, bool EVEN>
+int launch_even(const GemmDev& p, int splits, hipStream_t stream) {
   constexpr size_t lds = lds_bytes<BM, BN, BK, A_T, B_T>();
-  auto kern = gemm_mfma_kernel<BM, BN, BK, A_T, B_T, EPI>;
+  auto kern = gemm_mfma_kernel<BM, BN, BK, A_T, B_T, EPI, EVEN>;
   if (lds > 64 * 1024) {
     static thread_local bool raised = false;
     if (!raised) {
@@ -253,6 +295,13 @@ int launch(const GemmDev& p, int splits, hipStream_t stream) {
   const dim3 grid((p.N + BN - 1) / BN, (p.M + BM - 1) / BM, splits);
   hipLaunchKernelGGL(kern, grid, dim3(256), lds, stream, p);
   return check_launch("gemm_mfma");
+}
+
+template <int BM, int BN, int BK, bool A_T, bool B_T, int EPI>
+int launch(const GemmDev& p, int splits, hipStream_t stream) {
+  const bool even = p.M % BM == 0 && p.N % BN == 0 && p.K % BK == 0 && p.k_per_split % BK == 0;
+  return even ? launch_even<BM, BN, BK, A_T, B_T, EPI, true>(p, splits, stream)
+              : launch_even<BM, BN, BK, A_T, B_T, EPI, false>(p, splits, stream);
 }
 
 template <int BM, int BN, int BK>

@@ -148,13 +148,25 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
   }
 }
 
-// out[c] += sum_r partial[r][c]   (one thread per column, rows in fixed order)
-__global__ void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n, float* __restrict__ out) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
+// out[c] += sum_r partial[r][c] for c in [0, n): a block owns 32 columns, its 8 row groups
+// split the rows, LDS combines them in a fixed order.  Columns >= split go to out1[c - split].
+__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n,
+                                                       float* __restrict__ out0, float* __restrict__ out1, int split) {
+  __shared__ float red[8][33];
+  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
   float t = 0.f;
-  for (int r = 0; r < rows; ++r) t += partial[(size_t)r * ld + c];
-  out[c] += t;
+  if (c < n)
+    for (int r = rg; r < rows; r += 8) t += partial[(size_t)r * ld + c];
+  red[rg][cl] = t;
+  __syncthreads();
+  if (rg == 0 && c < n) {
+    float sum = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; ++g) sum += red[g][cl];
+    float* dst = c < split ? out0 + c : out1 + (c - split);
+    *dst += sum;
+  }
 }
 
 // ------------------------------------------------------------------ column sums
@@ -207,9 +219,7 @@ template <typename T>
 int ln_backward_t(const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend, void* dz,
                   float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
   int blocks = (T_ + kRowsPerBlock - 1) / kRowsPerBlock;
-  // two rows per wavefront when there are enough rows; never more partial rows than the scratch holds
-  if (blocks > 256) blocks = (blocks + 1) / 2;
-  if (blocks > kMaxPartialRows) blocks = kMaxPartialRows;
+  if (blocks > 256) blocks = 256;  // a wavefront then walks several rows; 256 partial rows at most
   const size_t lds = (size_t)kRowsPerBlock * H * sizeof(float);
   const int nv = (H + 511) / 512;
 #define LAUNCH(NV)                                                                                            \
@@ -222,9 +232,8 @@ int ln_backward_t(const void* dout, const void* x, const void* gamma, const floa
 #undef LAUNCH
   int rc = check_launch("ln_backward");
   if (rc) return rc;
-  const dim3 fgrid((H + 255) / 256);
-  hipLaunchKernelGGL(finalize_kernel, fgrid, dim3(256), 0, stream, partial, blocks, 2 * H, H, dgamma);
-  hipLaunchKernelGGL(finalize_kernel, fgrid, dim3(256), 0, stream, partial + H, blocks, 2 * H, H, dbeta);
+  hipLaunchKernelGGL(finalize_kernel, dim3((2 * H + 31) / 32), dim3(256), 0, stream, partial, blocks, 2 * H, 2 * H,
+                     dgamma, dbeta, H);
   return check_launch("ln_backward finalize");
 }
 
@@ -237,7 +246,7 @@ int colsum_t(const void* in, int T_, int N, float* out, float* partial, hipStrea
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, stream, (const T*)in, T_, N, partial);
   int rc = check_launch("colsum");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((N + 255) / 256), dim3(256), 0, stream, partial, gy, N, N, out);
+  hipLaunchKernelGGL(finalize_kernel, dim3((N + 31) / 32), dim3(256), 0, stream, partial, gy, N, N, out, out, N);
   return check_launch("colsum finalize");
 }
 
