@@ -240,6 +240,12 @@ int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int 
                    int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out,
                    void* hip_stream);
 
+/* Tuning knob for measurements: which bf16 MFMA GEMM kernel hanayo_op_gemm and the chunk calls use.
+   -1 (default) = chosen from the shape; 0 / 1 / 2 = direct-to-LDS kernel with 256x256 / 128x128 /
+   256x128 tiles wherever the shape is a whole number of tiles; 3 = register-staged kernel only.
+   Process-wide, not thread-safe. */
+int hanayo_op_gemm_config(int config);
+
 /* out = LN(x) over the last dimension; stats[t] = (mean, rstd) as two floats;
    copy_out (may be NULL) receives a copy of x. */
 int hanayo_op_layernorm_forward(int dtype, const void* x, const void* gamma, const void* beta, void* out,

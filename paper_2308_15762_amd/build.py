@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "libhanayo.so")
 
 SOURCES = [
     "schedule.cpp", "layout.cpp", "chunk.cpp", "executor.cpp", "ops.cpp",
-    "kernels_norm.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_attn_mfma.hip",
+    "kernels_norm.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_gemm_dma.hip", "kernels_attn_mfma.hip",
 ]
 
 FLAGS = [

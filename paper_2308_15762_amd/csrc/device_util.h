@@ -70,4 +70,28 @@ __device__ __forceinline__ float gelu_grad_f(float h) {
   return cdf + h * pdf;
 }
 
+// The same two functions from one exponential and a rational erfc approximation
+// (Abramowitz & Stegun 7.1.26, absolute error of erf below 1.5e-7): used in the
+// bf16 MFMA epilogues, where the result is rounded to bf16 anyway.
+//   Phi(|h|) = 1 - 0.5 t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-h^2 / 2),  t = 1 / (1 + p |h| / sqrt 2)
+__device__ __forceinline__ void phi_fast(float h, float& cdf, float& pdf) {
+  const float ah = fabsf(h);
+  const float t = __frcp_rn(1.0f + 0.3275911f * 0.70710678118654752f * ah);
+  const float e = exp2f(-0.72134752044448170f * h * h);  // exp(-h^2 / 2)
+  const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+  const float tail = 0.5f * poly * e;  // 1 - Phi(|h|)
+  cdf = h >= 0.f ? 1.0f - tail : tail;
+  pdf = 0.39894228040143268f * e;
+}
+__device__ __forceinline__ float gelu_fast(float h) {
+  float cdf, pdf;
+  phi_fast(h, cdf, pdf);
+  return h * cdf;
+}
+__device__ __forceinline__ float gelu_grad_fast(float h) {
+  float cdf, pdf;
+  phi_fast(h, cdf, pdf);
+  return cdf + h * pdf;
+}
+
 }  // namespace hanayo

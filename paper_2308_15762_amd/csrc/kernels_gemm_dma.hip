@@ -1,0 +1,375 @@
+// bf16 GEMM for shapes that are whole multiples of the tile: operand tiles go from
+// global memory straight into LDS (global_load_lds_dwordx4, no VGPR staging and no
+// LDS write instructions), through a ring of NSTAGE LDS buffers, so that loads
+// for tile t+NSTAGE-1 are in flight while tile t is multiplied.  One workgroup
+// barrier per K tile (32 elements).
+//
+// LDS layouts are unpadded and XOR-swizzled in units of 16 bytes ("slots"); a
+// direct load writes 64 consecutive slots per wavefront instruction, so the
+// swizzle is applied by choosing which global vector each lane fetches:
+//   * contraction-contiguous operand, tile [rows][32]: 4 slots per row,
+//       slot' = slot ^ ((row >> 2) & 3)          (16-byte fragment reads of 16
+//       consecutive rows then cover all 64 banks)
+//   * contraction-strided operand, tile [32][cols]: cols/8 slots per row,
+//       slot' = slot ^ ((row & 3) << 2)          (the 4 rows x 4 slots one half
+//       wavefront touches in a transpose read cover all 64 banks)
+// MFMA, fragment orientation and epilogue are those of the staged kernel
+// (kernels_gemm_mfma.hip).
+#include <type_traits>
+
+#include "device_util.h"
+#include "epilogue.h"
+#include "kernels.h"
+
+namespace hanayo {
+namespace k {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+struct DmaGemm {
+  const bf16* A;
+  const bf16* B;
+  bf16* C;
+  float* Cf;
+  const bf16* bias;
+  const bf16* aux;
+  bf16* aux_out;
+  int M, N, K;
+  int lda, ldb, ldc;
+};
+
+constexpr int kBK = 32;
+
+// One wavefront-wide 16-byte-per-lane load from global memory into LDS: lane L's
+// vector lands at lds_byte_addr + 16 L.  `voff` is the lane's byte offset from `base`.
+// M0 carries the LDS address; it is written and consumed inside the statement, and nothing
+// else in these kernels lives in M0 (gfx950 LDS instructions do not use it).
+__device__ __forceinline__ void dma16(const void* base, unsigned voff, unsigned lds_byte_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(voff), "s"(base), "s"(lds_byte_addr)
+      : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Waits until at most `tiles_in_flight` tiles (LOADS instructions each) are still outstanding.
+template <int LOADS>
+__device__ __forceinline__ void wait_tiles(int tiles_in_flight) {
+  if (tiles_in_flight <= 0) wait_vmcnt<0>();
+  else if (tiles_in_flight == 1) wait_vmcnt<LOADS>();
+  else if (tiles_in_flight == 2) wait_vmcnt<2 * LOADS>();
+  else wait_vmcnt<3 * LOADS>();
+}
+
+// Operand tile description.  T = contraction strided in memory (tile is [32][EXT]).
+template <int EXT, bool T, int NW>
+struct Operand {
+  static constexpr int kSlotsPerRow = T ? EXT / 8 : 4;
+  static constexpr int kRows = T ? kBK : EXT;
+  static constexpr int kBytes = kRows * kSlotsPerRow * 16;
+  static constexpr int kInstr = kBytes / 1024;      // wavefront-wide loads per tile
+  static constexpr int kPerWave = kInstr / NW;      // issued by each wavefront
+  static constexpr int kRowsPerInstr = 64 / kSlotsPerRow == 0 ? 1 : 64 / kSlotsPerRow;
+  static_assert(kInstr % NW == 0, "tile loads must divide evenly over the wavefronts");
+  // row_base(q) is taken from the per-wavefront index i: valid when a wavefront's first
+  // instruction starts at a multiple of 4 rows
+  static_assert(!T || ((kPerWave * 64) / kSlotsPerRow) % 4 == 0, "wavefront's share must start on a 4-row boundary");
+
+  __device__ static int swizzle(int row, int slot) { return T ? slot ^ ((row & 3) << 2) : slot ^ ((row >> 2) & 3); }
+
+  // Byte offset, from the first element an instruction covers, of the vector that lane `lane`
+  // fetches.  `row_base` = (first tile row of the instruction) mod 4: the swizzle of a transposed
+  // tile depends on the absolute row, and an instruction may start at a row that is not a
+  // multiple of 4 (it covers 64 / slots-per-row rows).
+  __device__ static unsigned lane_offset(int lane, int ld, int row_base) {
+    if (T) {
+      const int row = lane / kSlotsPerRow, sp = lane % kSlotsPerRow;
+      return (unsigned)((row * ld + swizzle(row_base + row, sp) * 8) * 2);
+    }
+    const int row = lane >> 2, sp = lane & 3;
+    return (unsigned)((row * ld + swizzle(row, sp) * 8) * 2);
+  }
+  // row_base of instruction q
+  __device__ static constexpr int row_base(int q) { return T ? ((q * 64) / kSlotsPerRow) & 3 : 0; }
+};
+
+template <int PITCH_SLOTS>
+__device__ __forceinline__ bf16x8 frag_k(const char* lds, int r0, int kk, int lane) {
+  const int row = r0 + (lane & 31), slot = 2 * kk + (lane >> 5);
+  return *reinterpret_cast<const bf16x8*>(lds + (row * 4 + (slot ^ ((row >> 2) & 3))) * 16);
+}
+
+template <int SPR>
+__device__ __forceinline__ bf16x8 frag_t(const char* lds, int c0, int kk, int lane) {
+  const int krow = kk * 16 + 8 * (lane >> 5) + ((lane & 15) >> 2);
+  const int col = c0 + 16 * ((lane >> 4) & 1) + (lane & 3) * 4;
+  const int slot = (col >> 3) ^ ((krow & 3) << 2);
+  const char* p = lds + (krow * SPR + slot) * 16 + (col & 7) * 2;
+  union {
+    struct { s16x4 lo, hi; } s;
+    bf16x8 v;
+  } u;
+  u.s.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p));
+  u.s.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p + 4 * SPR * 16));
+  return u.v;
+}
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool A_T, bool B_T, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  using OpA = Operand<BM, A_T, NW>;
+  using OpB = Operand<BN, B_T, NW>;
+  constexpr int STAGE_BYTES = OpA::kBytes + OpB::kBytes;
+  constexpr int LOADS = OpA::kPerWave + OpB::kPerWave;  // per thread per tile
+  static_assert(3 * LOADS <= 63, "vmcnt range");
+  static_assert(NSTAGE >= 3 && kBK == 32, "pipeline below is written for two MFMA steps per tile");
+
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // LDS byte address of the ring (address-space-3 offset, what M0 takes)
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int nk = p.K / kBK;
+
+  // per-lane byte offsets; index = row_base / 2 (a transposed 256-wide tile alternates 0, 2)
+  const unsigned voff_a[2] = {OpA::lane_offset(lane, p.lda, 0), OpA::lane_offset(lane, p.lda, 2)};
+  const unsigned voff_b[2] = {OpB::lane_offset(lane, p.ldb, 0), OpB::lane_offset(lane, p.ldb, 2)};
+  // first element of this workgroup's A / B tile for K tile 0
+  const bf16* a_tile0 = A_T ? p.A + m0 : p.A + (size_t)m0 * p.lda;
+  const bf16* b_tile0 = B_T ? p.B + n0 : p.B + (size_t)n0 * p.ldb;
+
+  auto issue = [&](int kt) {
+    const unsigned stage = lds0 + (unsigned)(kt % NSTAGE) * STAGE_BYTES;
+    const bf16* a_k = A_T ? a_tile0 + (size_t)kt * kBK * p.lda : a_tile0 + kt * kBK;
+    const bf16* b_k = B_T ? b_tile0 + (size_t)kt * kBK * p.ldb : b_tile0 + kt * kBK;
+#pragma unroll
+    for (int i = 0; i < OpA::kPerWave; ++i) {
+      const int q = wave * OpA::kPerWave + i;  // which 64-slot group of the tile
+      // rows covered by one instruction: 16 (K-contiguous) or 64 / slots-per-row (transposed)
+      const bf16* src = A_T ? a_k + (size_t)((q * 64) / OpA::kSlotsPerRow) * p.lda + ((q * 64) % OpA::kSlotsPerRow) * 8
+                            : a_k + (size_t)(q * 16) * p.lda;
+      dma16(src, voff_a[OpA::row_base(i) >> 1], stage + q * 1024);
+    }
+#pragma unroll
+    for (int i = 0; i < OpB::kPerWave; ++i) {
+      const int q = wave * OpB::kPerWave + i;
+      const bf16* src = B_T ? b_k + (size_t)((q * 64) / OpB::kSlotsPerRow) * p.ldb + ((q * 64) % OpB::kSlotsPerRow) * 8
+                            : b_k + (size_t)(q * 16) * p.ldb;
+      dma16(src, voff_b[OpB::row_base(i) >> 1], stage + OpA::kBytes + q * 1024);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t)
+    if (t < nk) issue(t);
+
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto read_frags = [&](int kt, int kk, int slot) {
+    const char* a_lds = smem + (kt % NSTAGE) * STAGE_BYTES;
+    const char* b_lds = a_lds + OpA::kBytes;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      fa[slot][i] = A_T ? frag_t<OpA::kSlotsPerRow>(a_lds, wm * WM + i * 32, kk, lane)
+                        : frag_k<4>(a_lds, wm * WM + i * 32, kk, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      fb[slot][j] = B_T ? frag_t<OpB::kSlotsPerRow>(b_lds, wn * WN + j * 32, kk, lane)
+                        : frag_k<4>(b_lds, wn * WN + j * 32, kk, lane);
+  };
+  auto mfma_step = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
+  };
+  // issue order of one step: the LDS reads of the next step go out one per MFMA at the start
+  // of the step, so the last of them has a good part of the step to complete
+  auto interleave = [&]() {
+    constexpr int kDs = (A_T ? 2 : 1) * TM + (B_T ? 2 : 1) * TN;
+    constexpr int kMfma = TM * TN;
+    constexpr int kDsEach = kMfma >= kDs ? 1 : (kDs + kMfma - 1) / kMfma;
+    constexpr int kGroups = kMfma >= kDs ? kDs : kMfma;
+#pragma unroll
+    for (int g = 0; g < kGroups; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x100, kDsEach, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    if (kMfma > kGroups) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kGroups, 0);
+  };
+
+  // Tile 0 has landed once only tiles 1 .. NSTAGE-2 are outstanding.
+  wait_tiles<LOADS>(min(NSTAGE - 2, nk - 1));
+  __syncthreads();
+  read_frags(0, 0, 0);
+
+  // Steady state, per K tile (two MFMA steps of 16):
+  //   step 0 of tile kt   | LDS reads: step 1 of tile kt
+  //   wait until tile kt+1 has landed; barrier (also: everyone has finished tile kt-1)
+  //   start the loads of tile kt+NSTAGE-1 into the buffer tile kt-1 occupied
+  //   step 1 of tile kt   | LDS reads: step 0 of tile kt+1
+  // so the barrier never drains the fragment pipeline.
+  for (int kt = 0; kt + 1 < nk; ++kt) {
+    read_frags(kt, 1, 1);
+    mfma_step(0);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    wait_tiles<LOADS>(min(NSTAGE - 3, nk - 2 - kt));
+    __syncthreads();
+    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(kt + 1, 0, 0);
+    mfma_step(1);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  read_frags(nk - 1, 1, 1);
+  mfma_step(0);
+  interleave();
+  __builtin_amdgcn_sched_barrier(0);
+  mfma_step(1);
+
+  // Epilogue: register group q of a tile holds columns n .. n+3 of row m,
+  //   m = tile_m + lane % 32,  n = tile_n + 8 q + 4 (lane / 32).
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm * WM + i * 32 + (lane & 31);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * (lane >> 5);
+        const size_t at = (size_t)m * p.ldc + n;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+        if constexpr (EPI == EPI_ACCUM_F32) {
+          f32x4 c = *reinterpret_cast<f32x4*>(p.Cf + at);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) c[e] += v[e];
+          *reinterpret_cast<f32x4*>(p.Cf + at) = c;
+        } else {
+          if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
+            const bf16x4 b = *reinterpret_cast<const bf16x4*>(p.bias + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)b[e];
+          }
+          if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_ADD) {
+            const bf16x4 x = *reinterpret_cast<const bf16x4*>(p.aux + at);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)x[e];
+          }
+          if constexpr (EPI == EPI_MUL_DGELU) {
+            const bf16x4 h = *reinterpret_cast<const bf16x4*>(p.aux + at);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_fast((float)h[e]);
+          }
+          if constexpr (EPI == EPI_BIAS_GELU) {
+            bf16x4 h;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              h[e] = (bf16)v[e];
+              v[e] = gelu_fast(v[e]);
+            }
+            *reinterpret_cast<bf16x4*>(p.aux_out + at) = h;
+          }
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
+          *reinterpret_cast<bf16x4*>(p.C + at) = o;
+        }
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool A_T, bool B_T, int EPI>
+int launch(const DmaGemm& p, hipStream_t stream) {
+  using OpA = Operand<BM, A_T, WGM * WGN>;
+  using OpB = Operand<BN, B_T, WGM * WGN>;
+  constexpr size_t lds = (size_t)NSTAGE * (OpA::kBytes + OpB::kBytes);
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, NSTAGE, A_T, B_T, EPI>;
+  static thread_local bool raised = false;
+  if (lds > 64 * 1024 && !raised) {
+    const hipError_t e =
+        hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return set_error(HANAYO_EHIP, "gemm_dma: cannot raise LDS limit: %s", hipGetErrorString(e));
+    raised = true;
+  }
+  const dim3 grid(p.N / BN, p.M / BM);
+  hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, stream, p);
+  return check_launch("gemm_dma");
+}
+
+template <int BM, int BN, int WGM, int WGN, int NSTAGE>
+int launch_layout(const GemmArgs& g, const DmaGemm& p, hipStream_t stream) {
+  if (!g.a_t && g.b_t) {
+    switch (g.epi) {
+      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, false, true, EPI_BIAS>(p, stream);
+      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, false, true, EPI_BIAS_GELU>(p, stream);
+      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, false, true, EPI_BIAS_RES>(p, stream);
+      default: break;
+    }
+  } else if (!g.a_t && !g.b_t) {
+    switch (g.epi) {
+      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, false, false, EPI_NONE>(p, stream);
+      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, false, false, EPI_MUL_DGELU>(p, stream);
+      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, false, false, EPI_ADD>(p, stream);
+      default: break;
+    }
+  } else if (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32) {
+    return launch<BM, BN, WGM, WGN, NSTAGE, true, true, EPI_ACCUM_F32>(p, stream);
+  }
+  return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: layout/epilogue combination not built");
+}
+
+}  // namespace
+
+// Tile configurations: 0 = 256 x 256 (4 wavefronts), 1 = 128 x 128 (4 wavefronts), 2 = 256 x 128 (4 wavefronts)
+bool gemm_dma_supported(const GemmArgs& g, int config) {
+  const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
+                     (!g.a_t && !g.b_t && (g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD)) ||
+                     (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32);
+  const int bm = config == 1 ? 128 : 256, bn = config == 0 ? 256 : 128;
+  // lane offsets are 32-bit byte offsets from the tile origin
+  const long span_a = (long)(g.a_t ? kBK : bm) * g.lda * 2, span_b = (long)(g.b_t ? kBK : bn) * g.ldb * 2;
+  return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % kBK == 0 && g.K >= kBK && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
+         g.ldc % 4 == 0 && span_a < (1L << 31) && span_b < (1L << 31);
+}
+
+int gemm_dma(const GemmArgs& g, int config, hipStream_t stream) {
+  if (!gemm_dma_supported(g, config)) return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: shape not supported");
+  DmaGemm p;
+  p.A = (const bf16*)g.A; p.B = (const bf16*)g.B; p.C = (bf16*)g.C; p.Cf = (float*)g.C;
+  p.bias = (const bf16*)g.bias; p.aux = (const bf16*)g.aux; p.aux_out = (bf16*)g.aux_out;
+  p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+  switch (config) {
+    case 0: return launch_layout<256, 256, 2, 2, 4>(g, p, stream);
+    case 1: return launch_layout<128, 128, 2, 2, 4>(g, p, stream);
+    default: return launch_layout<256, 128, 2, 2, 4>(g, p, stream);
+  }
+}
+
+}  // namespace k
+}  // namespace hanayo

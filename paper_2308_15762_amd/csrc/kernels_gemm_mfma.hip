@@ -251,14 +251,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmDev p) {
           if constexpr (EPI == EPI_MUL_DGELU) {
             const bf16x4 h = *reinterpret_cast<const bf16x4*>(p.aux + at);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f((float)h[e]);
+            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_fast((float)h[e]);
           }
           if constexpr (EPI == EPI_BIAS_GELU) {
             bf16x4 h;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
               h[e] = (bf16)v[e];
-              v[e] = gelu_f(v[e]);
+              v[e] = gelu_fast(v[e]);
             }
             *reinterpret_cast<bf16x4*>(p.aux_out + at) = h;
           }

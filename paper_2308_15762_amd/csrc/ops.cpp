@@ -35,6 +35,12 @@ int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int 
   return k::gemm(dtype, g, static_cast<hipStream_t>(hip_stream));
 }
 
+int hanayo_op_gemm_config(int config) {
+  if (config < -1 || config > 3) return set_error(HANAYO_EINVAL, "op_gemm_config: config must be -1..3");
+  k::set_gemm_config(config);
+  return HANAYO_OK;
+}
+
 int hanayo_op_layernorm_forward(int dtype, const void* x, const void* gamma, const void* beta, void* out, float* stats,
                                 void* copy_out, int rows, int hidden, float eps, void* hip_stream) {
   if (int rc = check_dtype(dtype)) return rc;

@@ -63,7 +63,7 @@ EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
            "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_device_info",
-           "hanayo_op_gemm", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
+           "hanayo_op_gemm", "hanayo_op_gemm_config", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
@@ -88,6 +88,7 @@ _lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
 _lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp]
+_lib.hanayo_op_gemm_config.argtypes = [_int]
 _lib.hanayo_op_layernorm_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _vp, _vp, _int, _int, ctypes.c_float, _vp]
 _lib.hanayo_op_layernorm_backward.argtypes = [_int] + [_vp] * 9 + [_int, _int, _vp]
 _lib.hanayo_op_colsum_add.argtypes = [_int, _vp, _int, _int, _vp, _vp, _vp]
@@ -225,6 +226,10 @@ def hanayo_op_gemm(dtype, A, B, C, M, N, K, lda, ldb, ldc, a_t, b_t, epilogue, b
                    stream=None):
     _check(_lib.hanayo_op_gemm(dtype, _ptr(A), _ptr(B), _ptr(C), M, N, K, lda, ldb, ldc, int(a_t), int(b_t), epilogue,
                                _ptr(bias), _ptr(aux), _ptr(aux_out), stream))
+
+
+def hanayo_op_gemm_config(config):
+    _check(_lib.hanayo_op_gemm_config(int(config)))
 
 
 def hanayo_op_layernorm_forward(dtype, x, gamma, beta, out, stats, copy_out, rows, hidden, eps, stream=None):

@@ -1,0 +1,90 @@
+"""GPU parity at the benchmark's full chunk shapes, in the launch configuration bench.py
+times (same kernels, same dispatch).  The oracle cannot replay a whole rank list at these
+sizes in seconds, so: one full micro-batch forward+backward of one chunk is compared
+element by element (configurations 2, 3 and 5; configuration 4 with one sequence chunk on
+sampled tensors), and for the benchmark workload the executor's outputs for one sampled
+micro-batch are compared with the oracle walking that micro-batch's tasks."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import block as OB
+from paper_2308_15762_amd import hanayo as hn
+from paper_2308_15762_amd import synth
+from helpers import TOL, GpuChunk, GpuRank, compare_grads, host, nerr, oracle_cfg
+
+pytestmark = pytest.mark.gpu
+
+W = synth.WORKLOADS
+
+
+@pytest.mark.parametrize("name", ["gpt_1024_bf16", "bert_1024_bf16", "gpt_2560_wave4_bf16"])
+def test_full_size_chunk_pair(name):
+    wl = W[name]
+    tol = TOL[wl.dtype]
+    params = synth.chunk_params(wl, 0)
+    x, dy = synth.forward_input(wl, 0, 0), synth.upstream_grad(wl, 0, 0)
+    vl = synth.valid_lengths(wl, 0)
+    cfg = oracle_cfg(wl)
+    y_ref, st = OB.chunk_forward(params, x, cfg, vl)
+    dx_ref, g_ref = OB.chunk_backward(cfg, st, dy)
+    del st
+    gpu = GpuChunk(wl, params)
+    y, stash = gpu.forward(x, vl)
+    assert nerr(y, y_ref) <= tol, "y %.3g" % nerr(y, y_ref)
+    dx = gpu.backward(dy, stash)
+    assert nerr(dx, dx_ref) <= tol, "dx %.3g" % nerr(dx, dx_ref)
+    compare_grads(gpu.grad_dicts(), g_ref, tol, name)
+
+
+def test_largest_chunk_shape_single_block():
+    # configuration 4's block (H = 4096, 32 heads of 128, F = 16384, seq 2048): one block of the
+    # chunk, full size, so the oracle stays within tens of seconds
+    wl = W["gpt_4096_bf16"].scaled(n_blocks=1)
+    tol = TOL["bf16"]
+    params = synth.chunk_params(wl, 0)
+    x, dy = synth.forward_input(wl, 0, 0), synth.upstream_grad(wl, 0, 0)
+    cfg = oracle_cfg(wl)
+    y_ref, st = OB.chunk_forward(params, x, cfg, dtype=np.float32)
+    dx_ref, g_ref = OB.chunk_backward(cfg, st, dy)
+    del st
+    gpu = GpuChunk(wl, params)
+    y, stash = gpu.forward(x)
+    assert nerr(y, y_ref) <= tol
+    dx = gpu.backward(dy, stash)
+    assert nerr(dx, dx_ref) <= tol
+    compare_grads(gpu.grad_dicts(), g_ref, tol, "gpt_4096 block")
+
+
+def test_benchmark_workload_sampled_micro_batch():
+    """Rank 0's full 64-task list of the benchmark workload; micro-batch 5's boundary outputs
+    against the oracle (chunks 1 -> 2 are the local turn-around)."""
+    wl = W["gpt_1024_bf16"]
+    tol = TOL["bf16"]
+    gpu = GpuRank(wl, 0)
+    peak = gpu.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0] == 16
+    m = 5
+    cfg = oracle_cfg(wl)
+    nchunk = 2 * wl.W
+    params = [synth.chunk_params(wl, c) for c in range(nchunk)]
+    y, st = {}, {}
+    y[0], st[0] = OB.chunk_forward(params[0], synth.forward_input(wl, m, 0), cfg)
+    y[1], st[1] = OB.chunk_forward(params[1], synth.forward_input(wl, m, 1), cfg)
+    y[2], st[2] = OB.chunk_forward(params[2], y[1], cfg)                       # local hand-off
+    y[3], st[3] = OB.chunk_forward(params[3], synth.forward_input(wl, m, 3), cfg)
+    d = {}
+    d[3], _ = OB.chunk_backward(cfg, st[3], synth.upstream_grad(wl, m, 3))
+    d[2], _ = OB.chunk_backward(cfg, st[2], synth.upstream_grad(wl, m, 2))
+    d[1], _ = OB.chunk_backward(cfg, st[1], d[2])                              # local hand-off
+    d[0], _ = OB.chunk_backward(cfg, st[0], synth.upstream_grad(wl, m, 0))
+    for c in range(nchunk):
+        e = nerr(host(gpu.act_out[m * nchunk + c]), y[c])
+        assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
+        e = nerr(host(gpu.grad_out[m * nchunk + c]), d[c])
+        assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
+    # property that holds at any size: every gradient buffer is finite and non-trivial
+    for g in gpu.grads:
+        assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0

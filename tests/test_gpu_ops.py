@@ -38,10 +38,29 @@ EPIS = {"fwd": [hn.EPI_BIAS, hn.EPI_BIAS_GELU, hn.EPI_BIAS_RES],
         "dw": [hn.EPI_ACCUM_F32]}
 
 
+@pytest.fixture
+def gemm_config(request):
+    hn.hanayo_op_gemm_config(request.param)
+    yield request.param
+    hn.hanayo_op_gemm_config(-1)
+
+
+# every bf16 MFMA kernel variant on shapes that are whole numbers of its tile
+@pytest.mark.parametrize("gemm_config", [0, 1, 2, 3], indirect=True)
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+@pytest.mark.parametrize("shape", [(512, 768, 256), (256, 256, 32), (1024, 512, 96)])
+def test_gemm_kernel_variants(gemm_config, layout, shape):
+    run_gemm_case("bf16", layout, shape)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
 @pytest.mark.parametrize("layout", list(LAYOUTS))
 @pytest.mark.parametrize("shape", GEMM_SHAPES)
 def test_gemm(dtype, layout, shape):
+    run_gemm_case(dtype, layout, shape)
+
+
+def run_gemm_case(dtype, layout, shape):
     M, N, K = shape
     if dtype == "fp32" and M * N * K > 4096 * 4096 * 64:
         M, N = M // 4, N // 4
