@@ -376,6 +376,449 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnDev p) {
   }
 }
 
+// ======================================================================================
+// Direct-to-LDS variants for head dims 64 and 128 (DP == d): K/V (forward, dQ) or Q/dC (dK/dV)
+// tiles of 64 rows go global -> LDS with global_load_lds_dwordx4 through a ring of NST buffers,
+// so the loads of tile t+NST-1 are in flight while tile t is used; one barrier per tile.
+// LDS rows are unpadded and XOR-swizzled in 16-byte slots so that both access patterns are
+// bank-conflict free:
+//   16-byte fragment reads: 16 consecutive rows at one slot;
+//   transpose reads: 4 consecutive rows x 4 consecutive slots per half wavefront.
+// DP = 64 (8 slots/row, two rows per 256-byte bank line): slot' = slot ^ (r1<<2 | r3<<1 | r2)
+// DP = 128 (16 slots/row, one row per bank line):         slot' = slot ^ (r1<<3 | r0<<2 | r3<<1 | r2)
+// with r0..r3 the low bits of the row.
+// Softmax arithmetic is kept to one fma and one v_exp_f32 per score (scores stay unscaled, the
+// scale goes into the exponent), masks are applied only on tiles that cross the diagonal or the
+// end of the valid keys, and the output accumulator is rescaled only when a row maximum moved.
+// ======================================================================================
+
+__device__ __forceinline__ void dma16(const void* base, unsigned voff, unsigned lds_byte_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dwordx4 %0, %1"
+      :
+      : "v"(voff), "s"(base), "s"(lds_byte_addr)
+      : "memory");
+}
+__device__ __forceinline__ void dma4(const void* base, unsigned voff, unsigned lds_byte_addr) {
+  asm volatile(
+      "s_mov_b32 m0, %2\n\t"
+      "s_nop 0\n\t"
+      "global_load_lds_dword %0, %1"
+      :
+      : "v"(voff), "s"(base), "s"(lds_byte_addr)
+      : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+template <int LOADS>
+__device__ __forceinline__ void wait_tiles(int tiles_in_flight) {
+  if (tiles_in_flight <= 0) wait_vmcnt<0>();
+  else if (tiles_in_flight == 1) wait_vmcnt<LOADS>();
+  else wait_vmcnt<2 * LOADS>();
+}
+
+template <int DP>
+struct SwTile {
+  static_assert(DP == 64 || DP == 128, "swizzled tiles exist for head dims 64 and 128");
+  static constexpr int SPR = DP / 8;
+  static constexpr int kRowsPerInstr = 64 / SPR;
+  static constexpr int kInstr = 64 / kRowsPerInstr;  // per 64-row tile
+  static constexpr int kPerWave = kInstr / 4;
+  static constexpr int kBytes = 64 * DP * 2;
+
+  __device__ static int swz(int row) {
+    return DP == 64 ? ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)) : (((row & 3) << 2) | ((row >> 2) & 3));
+  }
+  // This wavefront's share of the tile whose first row is row0 (rows clamped to s-1).
+  __device__ static void issue(const bf16* gbase, int ld, int row0, int s, unsigned lds_addr, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < kPerWave; ++i) {
+      const int q = wave * kPerWave + i;
+      const int lr = q * kRowsPerInstr + lane / SPR, sp = lane % SPR;
+      const int row = min(row0 + lr, s - 1);
+      dma16(gbase, (unsigned)((row * ld + ((sp ^ swz(lr)) << 3)) * 2), lds_addr + q * 1024);
+    }
+  }
+  // Per-lane byte offsets of every fragment read inside a tile, computed once per kernel.  The swizzle
+  // depends on the row's low four bits only, so a fragment that starts r0 rows further down (r0 a
+  // multiple of 16) is the same offset plus r0 * SPR * 16, an immediate in the LDS instruction.
+  struct Offsets {
+    unsigned rows[DP / 16];     // 16-byte fragment of contraction step kk (rows = lane % 32)
+    unsigned cols_lo[DP / 32];  // transpose reads of column tile dt: tile rows 4 (lane/32) + 0..3
+    unsigned cols_hi[DP / 32];  //                                   and those rows + 8
+  };
+  __device__ static void init(Offsets& f, int lane) {
+#pragma unroll
+    for (int kk = 0; kk < DP / 16; ++kk) {
+      const int row = lane & 31, slot = 2 * kk + (lane >> 5);
+      f.rows[kk] = (unsigned)((row * SPR + (slot ^ swz(row))) * 16);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DP / 32; ++dt) {
+      const int row = 4 * (lane >> 5) + ((lane & 15) >> 2);
+      const int col = 32 * dt + 16 * ((lane >> 4) & 1) + (lane & 3) * 4;
+      const int slot = col >> 3, sub = (col & 7) * 2;
+      f.cols_lo[dt] = (unsigned)((row * SPR + (slot ^ swz(row))) * 16 + sub);
+      f.cols_hi[dt] = (unsigned)(((row + 8) * SPR + (slot ^ swz(row + 8))) * 16 + sub);
+    }
+  }
+  // rows r0 + lane % 32 (r0 multiple of 16), contraction step kk
+  __device__ static bf16x8 frag_rows(const char* lds, const Offsets& f, int r0, int kk) {
+    return *reinterpret_cast<const bf16x8*>(lds + f.rows[kk] + r0 * SPR * 16);
+  }
+  // columns 32 dt + lane % 32; contraction rows r0 + {0..3, 8..11} + 4 (lane / 32) (r0 multiple of 16)
+  __device__ static bf16x8 frag_cols(const char* lds, const Offsets& f, int r0, int dt) {
+    union {
+      struct { s16x4 lo, hi; } s;
+      bf16x8 v;
+    } u;
+    u.s.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + f.cols_lo[dt] + r0 * SPR * 16));
+    u.s.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(lds + f.cols_hi[dt] + r0 * SPR * 16));
+    return u.v;
+  }
+};
+
+template <int DP, int NST>
+__global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
+  using Tile = SwTile<DP>;
+  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
+  typename Tile::Offsets fo;
+  Tile::init(fo, lane);
+  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int H = p.heads * p.d, ld3 = 3 * H;
+  const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
+  const int len = seq_len(p, n);
+  const int q0 = qt * 128, qw0 = q0 + 32 * wave, q = qw0 + (lane & 31);
+  const int kv_end = p.causal ? min(len, q0 + 128) : len;
+  const int nt = (kv_end + BKV - 1) / BKV;
+  const float c2 = rsqrtf((float)p.d) * kLog2e;
+
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
+    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+  };
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < nt) issue(t);
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) qf[kk] = frag_global(base + (size_t)q * ld3, q < p.s, kk, lane, p.d);
+  f32x16 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = zero16();
+  float m = -INFINITY, lsum = 0.f;  // m in units of raw (unscaled) scores
+
+  for (int t = 0; t < nt; ++t) {
+    wait_tiles<LOADS>(min(NST - 2, nt - 1 - t));
+    __syncthreads();
+    if (t + NST - 1 < nt) issue(t + NST - 1);
+    const int k0 = t * BKV;
+    if (p.causal && k0 > qw0 + 31) continue;  // all keys of the tile are ahead of this wavefront's rows
+    const char* Ks = smem + (t % NST) * STAGE;
+    const char* Vs = Ks + Tile::kBytes;
+    f32x16 sc[2];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) sc[c] = zero16();
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Ks, fo, 32 * c, kk), qf[kk], sc[c], 0, 0, 0);
+    if ((p.causal && k0 + BKV - 1 > qw0) || k0 + BKV > len) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * c + acc_row(r, half);
+          if (!(key < len && (!p.causal || key <= q))) sc[c][r] = -INFINITY;
+        }
+    }
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, sc[c][r]);
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float m_new = fmaxf(m, mloc);  // finite: key 0 is allowed for every row and comes first
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c2);
+    const float shift = -m_new * c2;
+    float rs = 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(sc[c][r], c2, shift));
+        sc[c][r] = e;
+        rs += e;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    lsum = lsum * alpha + rs;
+    m = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {  // the running maximum moved for some row
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 pf = pack_half(sc[c], tt);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Vs, fo, 32 * c + 16 * tt, dt), pf, o[dt], 0, 0, 0);
+      }
+  }
+  if (q < p.s) {
+    const float inv = 1.f / lsum;
+    bf16* out = p.ctx + ((size_t)n * p.s + q) * H + h * p.d;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = 32 * dt + 8 * g + 4 * half;
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[dt][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(out + col) = v;
+      }
+    if (half == 0) p.lse[((size_t)n * p.heads + h) * p.s + q] = (m * c2 + log2f(lsum)) * kLn2;
+  }
+}
+
+template <int DP, int NST>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
+  using Tile = SwTile<DP>;
+  constexpr int BQ = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int STAGE = 2 * Tile::kBytes + 512;  // Q tile, dC tile, 64 lse, 64 delta
+  constexpr int LOADS = 2 * Tile::kPerWave + 1;  // every wavefront also issues one 4-byte-per-lane load
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
+  typename Tile::Offsets fo;
+  Tile::init(fo, lane);
+  const int kt = blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int H = p.heads * p.d, ld3 = 3 * H;
+  const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
+  const bf16* dcb = p.dctx + (size_t)n * p.s * H + h * p.d;
+  const size_t stat0 = ((size_t)n * p.heads + h) * p.s;
+  const int len = seq_len(p, n);
+  const int k0 = kt * 128, kw0 = k0 + 32 * wave, key = kw0 + (lane & 31);
+  const float scale = rsqrtf((float)p.d), c2 = scale * kLog2e;
+
+  const int q_begin = (p.causal && k0 < len) ? (k0 / BQ) * BQ : 0;
+  const int q_end = k0 < len ? p.s : 0;  // a tile of masked keys gets zero gradients
+  const int nt = q_end > q_begin ? (q_end - q_begin + BQ - 1) / BQ : 0;
+
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
+    const int q0 = q_begin + t * BQ;
+    Tile::issue(base, ld3, q0, p.s, st, wave, lane);
+    Tile::issue(dcb, H, q0, p.s, st + Tile::kBytes, wave, lane);
+    // wavefronts 0 / 1 fetch the 64 log-sum-exp / delta values; 2 / 3 repeat them (same data, keeps
+    // every wavefront's load count equal)
+    const int qq = min(q0 + lane, p.s - 1);
+    const float* src = (wave & 1) ? p.delta + stat0 : p.lse + stat0;
+    dma4(src, (unsigned)(qq * 4), st + 2 * Tile::kBytes + (wave & 1) * 256);
+  };
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < nt) issue(t);
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    kf[kk] = frag_global(base + H + (size_t)key * ld3, key < p.s, kk, lane, p.d);
+    vf[kk] = frag_global(base + 2 * H + (size_t)key * ld3, key < p.s, kk, lane, p.d);
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    dk[dt] = zero16();
+    dv[dt] = zero16();
+  }
+  for (int t = 0; t < nt; ++t) {
+    wait_tiles<LOADS>(min(NST - 2, nt - 1 - t));
+    __syncthreads();
+    if (t + NST - 1 < nt) issue(t + NST - 1);
+    const int q0 = q_begin + t * BQ;
+    const char* Qs = smem + (t % NST) * STAGE;
+    const char* Cs = Qs + Tile::kBytes;
+    const float* lse_s = reinterpret_cast<const float*>(Cs + Tile::kBytes);
+    const float* dlt_s = lse_s + 64;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      if (p.causal && q0 + 32 * c + 31 < kw0) continue;  // all these queries precede the wavefront's keys
+      f32x16 sacc = zero16(), dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Qs, fo, 32 * c, kk), kf[kk], sacc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Cs, fo, 32 * c, kk), vf[kk], dp, 0, 0, 0);
+      }
+      // P = 2^(c2 s - lse log2e), dS = P (dP - delta); lse and delta of this lane's 16 queries come as 4-vectors
+      const bool need_mask = (p.causal && q0 + 32 * c < kw0 + 31) || kw0 + 31 >= len || q0 + 32 * c + 31 >= p.s;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int ql = 32 * c + 8 * g + 4 * half;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ql);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dlt_s + ql);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g + e;
+          float pr = __builtin_amdgcn_exp2f(fmaf(sacc[r], c2, -l4[e] * kLog2e));
+          if (need_mask) {
+            const int qq = q0 + ql + e;
+            if (!(qq < p.s && key < len && (!p.causal || key <= qq))) pr = 0.f;
+          }
+          sacc[r] = pr;
+          dp[r] = pr * (dp[r] - d4[e]);
+        }
+      }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 pf = pack_half(sacc, tt), dsf = pack_half(dp, tt);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Cs, fo, 32 * c + 16 * tt, dt), pf, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Qs, fo, 32 * c + 16 * tt, dt), dsf, dk[dt], 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (key < p.s) {
+    bf16* out = p.dqkv + ((size_t)n * p.s + key) * ld3 + h * p.d;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = 32 * dt + 8 * g + 4 * half;
+        bf16x4 a, b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = (bf16)(dk[dt][4 * g + e] * scale);
+          b[e] = (bf16)dv[dt][4 * g + e];
+        }
+        *reinterpret_cast<bf16x4*>(out + H + col) = a;
+        *reinterpret_cast<bf16x4*>(out + 2 * H + col) = b;
+      }
+  }
+}
+
+template <int DP, int NST>
+__global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
+  using Tile = SwTile<DP>;
+  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
+  typename Tile::Offsets fo;
+  Tile::init(fo, lane);
+  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int H = p.heads * p.d, ld3 = 3 * H;
+  const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
+  const int len = seq_len(p, n);
+  const int q0 = qt * 128, qw0 = q0 + 32 * wave, q = qw0 + (lane & 31);
+  const int kv_end = p.causal ? min(len, q0 + 128) : len;
+  const int nt = (kv_end + BKV - 1) / BKV;
+  const float scale = rsqrtf((float)p.d), c2 = scale * kLog2e;
+
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
+    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+  };
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < nt) issue(t);
+
+  const size_t stat = ((size_t)n * p.heads + h) * p.s + q;
+  const float my_lse2 = q < p.s ? p.lse[stat] * kLog2e : 0.f;
+  const float my_delta = q < p.s ? p.delta[stat] : 0.f;
+  bf16x8 qf[KS], cf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    qf[kk] = frag_global(base + (size_t)q * ld3, q < p.s, kk, lane, p.d);
+    cf[kk] = frag_global(p.dctx + ((size_t)n * p.s + q) * H + h * p.d, q < p.s, kk, lane, p.d);
+  }
+  f32x16 dq[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) dq[dt] = zero16();
+
+  for (int t = 0; t < nt; ++t) {
+    wait_tiles<LOADS>(min(NST - 2, nt - 1 - t));
+    __syncthreads();
+    if (t + NST - 1 < nt) issue(t + NST - 1);
+    const int k0 = t * BKV;
+    if (p.causal && k0 > qw0 + 31) continue;
+    const char* Ks = smem + (t % NST) * STAGE;
+    const char* Vs = Ks + Tile::kBytes;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      f32x16 sacc = zero16(), dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk) {
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Ks, fo, 32 * c, kk), qf[kk], sacc, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Vs, fo, 32 * c, kk), cf[kk], dp, 0, 0, 0);
+      }
+      const bool need_mask = (p.causal && k0 + 32 * c + 31 > qw0) || k0 + 32 * c + 32 > len;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pr = __builtin_amdgcn_exp2f(fmaf(sacc[r], c2, -my_lse2));
+        if (need_mask) {
+          const int key = k0 + 32 * c + acc_row(r, half);
+          if (!(key < len && (!p.causal || key <= q))) pr = 0.f;
+        }
+        dp[r] = pr * (dp[r] - my_delta);
+      }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 dsf = pack_half(dp, tt);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Ks, fo, 32 * c + 16 * tt, dt), dsf, dq[dt], 0, 0, 0);
+      }
+    }
+  }
+  if (q < p.s) {
+    bf16* out = p.dqkv + ((size_t)n * p.s + q) * ld3 + h * p.d;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = 32 * dt + 8 * g + 4 * half;
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(dq[dt][4 * g + e] * scale);
+        *reinterpret_cast<bf16x4*>(out + col) = v;
+      }
+  }
+}
+
+template <typename K>
+int raise_lds(K kern, size_t lds) {
+  if (lds <= 64 * 1024) return HANAYO_OK;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return set_error(HANAYO_EHIP, "attention: cannot raise LDS limit: %s", hipGetErrorString(e));
+  return HANAYO_OK;
+}
+
+// 32-bit lane offsets: the largest byte offset inside one sequence's rows must stay below 2^31
+bool dma_ok(const AttnArgs& a) {
+  return (a.d == 64 || a.d == 128) && (long)a.s * 3 * a.heads * a.d * 2 < (1L << 31);
+}
+
 AttnDev to_dev(const AttnArgs& a) {
   AttnDev p;
   p.qkv = (const bf16*)a.qkv; p.valid_len = a.valid_len; p.ctx = (bf16*)a.ctx; p.lse = a.lse;
@@ -392,6 +835,16 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
   if (!attn_mfma_supported(a)) return set_error(HANAYO_EUNSUPPORTED, "attn_mfma: head dim %d", a.d);
   const AttnDev p = to_dev(a);
   const dim3 grid((a.s + 127) / 128, a.heads, a.b), block(256);
+  if (dma_ok(a)) {
+    if (a.d == 64) {
+      constexpr size_t lds = 3 * 2 * SwTile<64>::kBytes;
+      hipLaunchKernelGGL((attn_fwd_dma_kernel<64, 3>), grid, block, lds, stream, p);
+    } else {
+      constexpr size_t lds = 2 * 2 * SwTile<128>::kBytes;
+      hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2>), grid, block, lds, stream, p);
+    }
+    return check_launch("attn_fwd_dma");
+  }
   if (a.d <= 64) hipLaunchKernelGGL((attn_fwd_kernel<64>), grid, block, 0, stream, p);
   else if (a.d <= 96) hipLaunchKernelGGL((attn_fwd_kernel<96>), grid, block, 0, stream, p);
   else hipLaunchKernelGGL((attn_fwd_kernel<128>), grid, block, 0, stream, p);
@@ -404,6 +857,19 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
   if (rc) return rc;
   const AttnDev p = to_dev(a);
   const dim3 grid((a.s + 127) / 128, a.heads, a.b), block(256);
+  if (dma_ok(a)) {
+    if (a.d == 64) {
+      hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<64, 3>), grid, block, 3 * (2 * SwTile<64>::kBytes + 512), stream, p);
+      hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<64, 3>), grid, block, 3 * 2 * SwTile<64>::kBytes, stream, p);
+    } else {
+      constexpr size_t lds_dkv = 2 * (2 * SwTile<128>::kBytes + 512);
+      rc = raise_lds(attn_bwd_dkv_dma_kernel<128, 2>, lds_dkv);
+      if (rc) return rc;
+      hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<128, 2>), grid, block, lds_dkv, stream, p);
+      hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<128, 2>), grid, block, 2 * 2 * SwTile<128>::kBytes, stream, p);
+    }
+    return check_launch("attn_bwd_dma");
+  }
   if (a.d <= 64) {
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<64>), grid, block, 0, stream, p);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<64>), grid, block, 0, stream, p);
