@@ -241,8 +241,9 @@ int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int 
                    void* hip_stream);
 
 /* Tuning knob for measurements: which bf16 MFMA GEMM kernel hanayo_op_gemm and the chunk calls use.
-   -1 (default) = chosen from the shape; 0 / 1 / 2 = direct-to-LDS kernel with 256x256 / 128x128 /
-   256x128 tiles wherever the shape is a whole number of tiles; 3 = register-staged kernel only.
+   -1 (default) = chosen from the shape; 0 / 1 / 2 / 4 = direct-to-LDS kernel with 256x256 / 128x128
+   (8-deep load ring) / 256x128 / 128x128 (4-deep ring) tiles wherever the shape is a whole number of
+   tiles; 3 = register-staged kernel only.
    Process-wide, not thread-safe. */
 int hanayo_op_gemm_config(int config);
 

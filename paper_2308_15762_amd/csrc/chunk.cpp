@@ -96,14 +96,16 @@ void set_gemm_config(int config) { g_gemm_config = config; }
 int gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
   if (g.M < 1 || g.N < 1 || g.K < 1) return set_error(HANAYO_EINVAL, "gemm: empty problem");
   if (dtype == HANAYO_BF16) {
-    if (g_gemm_config >= 0 && g_gemm_config <= 2 && gemm_dma_supported(g, g_gemm_config))
+    if (g_gemm_config >= 0 && g_gemm_config != 3 && gemm_dma_supported(g, g_gemm_config))
       return gemm_dma(g, g_gemm_config, stream);
     if (g_gemm_config == -1) {
-      // Measured on MI355X: the 256 x 256 tile wins once there are at least two of them per CU,
-      // below that the 128 x 128 tile keeps more CUs busy.
-      const long t256 = (long)(g.M / 256) * (g.N / 256);
+      // Measured on MI355X: the 256 x 256 tile wins once there are at least two of them per CU.
+      // Below that, 128 x 128 tiles: if at most about one per CU exists, each gets a CU's whole LDS
+      // as an 8-deep load ring; otherwise a 4-deep ring so that two workgroups share a CU.
+      const long t256 = (long)(g.M / 256) * (g.N / 256), t128 = (long)(g.M / 128) * (g.N / 128);
       if (t256 >= 512 && gemm_dma_supported(g, 0)) return gemm_dma(g, 0, stream);
-      if (gemm_dma_supported(g, 1)) return gemm_dma(g, 1, stream);
+      if (t128 <= 320 && gemm_dma_supported(g, 1)) return gemm_dma(g, 1, stream);
+      if (gemm_dma_supported(g, 4)) return gemm_dma(g, 4, stream);
     }
     if (gemm_mfma_supported(g)) return gemm_mfma(g, stream);
   }

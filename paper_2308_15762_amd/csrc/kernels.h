@@ -73,10 +73,11 @@ int attn_backward_alu(int dtype, const AttnArgs& a, hipStream_t stream);
 int attn_delta(int dtype, const AttnArgs& a, hipStream_t stream);  // delta = rowsum(dctx * ctx)
 bool gemm_mfma_supported(const GemmArgs& g);
 int gemm_mfma(const GemmArgs& g, hipStream_t stream);  // bf16 only
-// Direct-to-LDS multi-stage kernel for tile-aligned shapes; config 0 = 256x256, 1 = 128x128, 2 = 256x128.
+// Direct-to-LDS multi-stage kernel for tile-aligned shapes; config 0 = 256x256, 1 = 128x128 (8-deep ring),
+// 2 = 256x128, 4 = 128x128 (4-deep ring).
 bool gemm_dma_supported(const GemmArgs& g, int config);
 int gemm_dma(const GemmArgs& g, int config, hipStream_t stream);
-// -1 = automatic choice; 0..2 = force that direct-to-LDS configuration where it applies; 3 = staged kernel only
+// -1 = automatic choice; 0, 1, 2, 4 = force that direct-to-LDS configuration where it applies; 3 = staged kernel only
 void set_gemm_config(int config);
 bool attn_mfma_supported(const AttnArgs& a);
 int attn_forward_mfma(const AttnArgs& a, hipStream_t stream);

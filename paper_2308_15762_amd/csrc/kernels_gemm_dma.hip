@@ -65,10 +65,16 @@ __device__ __forceinline__ void wait_vmcnt() {
 // Waits until at most `tiles_in_flight` tiles (LOADS instructions each) are still outstanding.
 template <int LOADS>
 __device__ __forceinline__ void wait_tiles(int tiles_in_flight) {
-  if (tiles_in_flight <= 0) wait_vmcnt<0>();
-  else if (tiles_in_flight == 1) wait_vmcnt<LOADS>();
-  else if (tiles_in_flight == 2) wait_vmcnt<2 * LOADS>();
-  else wait_vmcnt<3 * LOADS>();
+  switch (tiles_in_flight) {
+    case 0: wait_vmcnt<0>(); break;
+    case 1: wait_vmcnt<LOADS>(); break;
+    case 2: wait_vmcnt<2 * LOADS>(); break;
+    case 3: wait_vmcnt<3 * LOADS>(); break;
+    case 4: wait_vmcnt<(4 * LOADS > 63 ? 63 : 4 * LOADS)>(); break;
+    case 5: wait_vmcnt<(5 * LOADS > 63 ? 63 : 5 * LOADS)>(); break;
+    case 6: wait_vmcnt<(6 * LOADS > 63 ? 63 : 6 * LOADS)>(); break;
+    default: wait_vmcnt<(7 * LOADS > 63 ? 63 : 7 * LOADS)>(); break;
+  }
 }
 
 // Operand tile description.  T = contraction strided in memory (tile is [32][EXT]).
@@ -124,7 +130,10 @@ __device__ __forceinline__ bf16x8 frag_t(const char* lds, int c0, int kk, int la
   return u.v;
 }
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool A_T, bool B_T, int EPI>
+// FDEEP: fragments are read a whole K tile ahead (small wavefront tiles, where one MFMA step is
+// shorter than the LDS latency); a tile's LDS buffer is then free one iteration earlier, so all
+// NSTAGE buffers can be in flight.
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool FDEEP, bool A_T, bool B_T, int EPI>
 __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
   constexpr int NW = WGM * WGN;
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
@@ -132,7 +141,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
   using OpB = Operand<BN, B_T, NW>;
   constexpr int STAGE_BYTES = OpA::kBytes + OpB::kBytes;
   constexpr int LOADS = OpA::kPerWave + OpB::kPerWave;  // per thread per tile
-  static_assert(3 * LOADS <= 63, "vmcnt range");
+  static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt range");
   static_assert(NSTAGE >= 3 && kBK == 32, "pipeline below is written for two MFMA steps per tile");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -144,32 +153,42 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int nk = p.K / kBK;
 
-  // per-lane byte offsets; index = row_base / 2 (a transposed 256-wide tile alternates 0, 2)
-  const unsigned voff_a[2] = {OpA::lane_offset(lane, p.lda, 0), OpA::lane_offset(lane, p.lda, 2)};
-  const unsigned voff_b[2] = {OpB::lane_offset(lane, p.ldb, 0), OpB::lane_offset(lane, p.ldb, 2)};
-  // first element of this workgroup's A / B tile for K tile 0
-  const bf16* a_tile0 = A_T ? p.A + m0 : p.A + (size_t)m0 * p.lda;
-  const bf16* b_tile0 = B_T ? p.B + n0 : p.B + (size_t)n0 * p.ldb;
-
-  auto issue = [&](int kt) {
-    const unsigned stage = lds0 + (unsigned)(kt % NSTAGE) * STAGE_BYTES;
-    const bf16* a_k = A_T ? a_tile0 + (size_t)kt * kBK * p.lda : a_tile0 + kt * kBK;
-    const bf16* b_k = B_T ? b_tile0 + (size_t)kt * kBK * p.ldb : b_tile0 + kt * kBK;
+  // Direct loads of one K tile.  The wavefront's i-th instruction for an operand covers the 64
+  // slots q = wave * kPerWave + i of the tile; which rows that is goes into the lane's byte
+  // offset (one VGPR per instruction, constant over the K loop), so every instruction of a tile
+  // shares one uniform base pointer that just advances by a K tile.
+  unsigned voff_a[OpA::kPerWave], voff_b[OpB::kPerWave];
 #pragma unroll
-    for (int i = 0; i < OpA::kPerWave; ++i) {
-      const int q = wave * OpA::kPerWave + i;  // which 64-slot group of the tile
-      // rows covered by one instruction: 16 (K-contiguous) or 64 / slots-per-row (transposed)
-      const bf16* src = A_T ? a_k + (size_t)((q * 64) / OpA::kSlotsPerRow) * p.lda + ((q * 64) % OpA::kSlotsPerRow) * 8
-                            : a_k + (size_t)(q * 16) * p.lda;
-      dma16(src, voff_a[OpA::row_base(i) >> 1], stage + q * 1024);
-    }
+  for (int i = 0; i < OpA::kPerWave; ++i) {
+    const int q = wave * OpA::kPerWave + i;
+    const unsigned first = A_T ? (unsigned)((((q * 64) / OpA::kSlotsPerRow) * p.lda + ((q * 64) % OpA::kSlotsPerRow) * 8) * 2)
+                               : (unsigned)((q * 16 * p.lda) * 2);
+    voff_a[i] = first + OpA::lane_offset(lane, p.lda, OpA::row_base(i));
+  }
 #pragma unroll
-    for (int i = 0; i < OpB::kPerWave; ++i) {
-      const int q = wave * OpB::kPerWave + i;
-      const bf16* src = B_T ? b_k + (size_t)((q * 64) / OpB::kSlotsPerRow) * p.ldb + ((q * 64) % OpB::kSlotsPerRow) * 8
-                            : b_k + (size_t)(q * 16) * p.ldb;
-      dma16(src, voff_b[OpB::row_base(i) >> 1], stage + OpA::kBytes + q * 1024);
-    }
+  for (int i = 0; i < OpB::kPerWave; ++i) {
+    const int q = wave * OpB::kPerWave + i;
+    const unsigned first = B_T ? (unsigned)((((q * 64) / OpB::kSlotsPerRow) * p.ldb + ((q * 64) % OpB::kSlotsPerRow) * 8) * 2)
+                               : (unsigned)((q * 16 * p.ldb) * 2);
+    voff_b[i] = first + OpB::lane_offset(lane, p.ldb, OpB::row_base(i));
+  }
+  // uniform running state of the loader: next tile's base pointers and LDS buffer
+  const bf16* a_next = A_T ? p.A + m0 : p.A + (size_t)m0 * p.lda;
+  const bf16* b_next = B_T ? p.B + n0 : p.B + (size_t)n0 * p.ldb;
+  const size_t a_step = A_T ? (size_t)kBK * p.lda : (size_t)kBK;
+  const size_t b_step = B_T ? (size_t)kBK * p.ldb : (size_t)kBK;
+  unsigned stage_next = 0;  // buffer index the next issued tile goes to
+  const unsigned wave_lds_a = lds0 + wave * OpA::kPerWave * 1024;
+  const unsigned wave_lds_b = lds0 + OpA::kBytes + wave * OpB::kPerWave * 1024;
+  auto issue = [&]() {
+    const unsigned st = stage_next * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < OpA::kPerWave; ++i) dma16(a_next, voff_a[i], wave_lds_a + st + i * 1024);
+#pragma unroll
+    for (int i = 0; i < OpB::kPerWave; ++i) dma16(b_next, voff_b[i], wave_lds_b + st + i * 1024);
+    a_next += a_step;
+    b_next += b_step;
+    stage_next = stage_next + 1 == NSTAGE ? 0 : stage_next + 1;
   };
 
   f32x16 acc[TM][TN];
@@ -180,32 +199,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-#pragma unroll
-  for (int t = 0; t < NSTAGE - 1; ++t)
-    if (t < nk) issue(t);
-
-  bf16x8 fa[2][TM], fb[2][TN];
-  auto read_frags = [&](int kt, int kk, int slot) {
-    const char* a_lds = smem + (kt % NSTAGE) * STAGE_BYTES;
-    const char* b_lds = a_lds + OpA::kBytes;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-      fa[slot][i] = A_T ? frag_t<OpA::kSlotsPerRow>(a_lds, wm * WM + i * 32, kk, lane)
-                        : frag_k<4>(a_lds, wm * WM + i * 32, kk, lane);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-      fb[slot][j] = B_T ? frag_t<OpB::kSlotsPerRow>(b_lds, wn * WN + j * 32, kk, lane)
-                        : frag_k<4>(b_lds, wn * WN + j * 32, kk, lane);
-  };
-  auto mfma_step = [&](int slot) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[slot][j], fa[slot][i], acc[i][j], 0, 0, 0);
-  };
-  // issue order of one step: the LDS reads of the next step go out one per MFMA at the start
-  // of the step, so the last of them has a good part of the step to complete
+  // issue order of one step: the LDS reads go out one per MFMA at the start of the step, so the
+  // last of them has a good part of the step to complete
   auto interleave = [&]() {
     constexpr int kDs = (A_T ? 2 : 1) * TM + (B_T ? 2 : 1) * TN;
     constexpr int kMfma = TM * TN;
@@ -218,37 +213,123 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
     }
     if (kMfma > kGroups) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kGroups, 0);
   };
+  auto read_a = [&](int kt, int kk, bf16x8 (&f)[TM]) {
+    const char* a_lds = smem + (kt % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+      f[i] = A_T ? frag_t<OpA::kSlotsPerRow>(a_lds, wm * WM + i * 32, kk, lane) : frag_k<4>(a_lds, wm * WM + i * 32, kk, lane);
+  };
+  auto read_b = [&](int kt, int kk, bf16x8 (&f)[TN]) {
+    const char* b_lds = smem + (kt % NSTAGE) * STAGE_BYTES + OpA::kBytes;
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+      f[j] = B_T ? frag_t<OpB::kSlotsPerRow>(b_lds, wn * WN + j * 32, kk, lane) : frag_k<4>(b_lds, wn * WN + j * 32, kk, lane);
+  };
+  auto mfma_step = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+  };
 
-  // Tile 0 has landed once only tiles 1 .. NSTAGE-2 are outstanding.
-  wait_tiles<LOADS>(min(NSTAGE - 2, nk - 1));
-  __syncthreads();
-  read_frags(0, 0, 0);
-
-  // Steady state, per K tile (two MFMA steps of 16):
-  //   step 0 of tile kt   | LDS reads: step 1 of tile kt
-  //   wait until tile kt+1 has landed; barrier (also: everyone has finished tile kt-1)
-  //   start the loads of tile kt+NSTAGE-1 into the buffer tile kt-1 occupied
-  //   step 1 of tile kt   | LDS reads: step 0 of tile kt+1
-  // so the barrier never drains the fragment pipeline.
-  for (int kt = 0; kt + 1 < nk; ++kt) {
-    read_frags(kt, 1, 1);
-    mfma_step(0);
-    interleave();
-    __builtin_amdgcn_sched_barrier(0);
-    wait_tiles<LOADS>(min(NSTAGE - 3, nk - 2 - kt));
+  if constexpr (!FDEEP) {
+#pragma unroll
+    for (int t = 0; t < NSTAGE - 1; ++t)
+      if (t < nk) issue();
+    bf16x8 fa[2][TM], fb[2][TN];
+    // Tile 0 has landed once only tiles 1 .. NSTAGE-2 are outstanding.
+    wait_tiles<LOADS>(min(NSTAGE - 2, nk - 1));
     __syncthreads();
-    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
-    __builtin_amdgcn_sched_barrier(0);
-    read_frags(kt + 1, 0, 0);
-    mfma_step(1);
+    read_a(0, 0, fa[0]);
+    read_b(0, 0, fb[0]);
+    // Steady state, per K tile (two MFMA steps of 16):
+    //   step 0 of tile kt   | LDS reads: step 1 of tile kt
+    //   wait until tile kt+1 has landed; barrier (also: everyone has finished tile kt-1)
+    //   start the loads of tile kt+NSTAGE-1 into the buffer tile kt-1 occupied
+    //   step 1 of tile kt   | LDS reads: step 0 of tile kt+1
+    // so the barrier never drains the fragment pipeline.
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+      read_a(kt, 1, fa[1]);
+      read_b(kt, 1, fb[1]);
+      mfma_step(fa[0], fb[0]);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      if (kt + NSTAGE - 1 < nk) {  // steady state: a fixed number of tiles stays in flight
+        wait_vmcnt<(NSTAGE - 3) * LOADS>();
+        __syncthreads();
+        issue();
+      } else {
+        wait_tiles<LOADS>(min(NSTAGE - 3, nk - 2 - kt));
+        __syncthreads();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      read_a(kt + 1, 0, fa[0]);
+      read_b(kt + 1, 0, fb[0]);
+      mfma_step(fa[1], fb[1]);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    read_a(nk - 1, 1, fa[1]);
+    read_b(nk - 1, 1, fb[1]);
+    mfma_step(fa[0], fb[0]);
     interleave();
     __builtin_amdgcn_sched_barrier(0);
+    mfma_step(fa[1], fb[1]);
+  } else {
+    // All NSTAGE buffers are filled up front.  In iteration kt the fragments of tile kt are already
+    // in registers (read during iteration kt-1), so after the barrier its buffer takes tile kt+NSTAGE.
+#pragma unroll
+    for (int t = 0; t < NSTAGE; ++t)
+      if (t < nk) issue();
+    bf16x8 fa[2][2][TM], fb[2][2][TN];  // [tile parity][step]
+    wait_tiles<LOADS>(min(NSTAGE - 1, nk - 1));
+    __syncthreads();
+    read_a(0, 0, fa[0][0]);
+    read_b(0, 0, fb[0][0]);
+    read_a(0, 1, fa[0][1]);
+    read_b(0, 1, fb[0][1]);
+    auto tile_iter = [&](int kt, auto parity, auto more) {
+      constexpr int P = decltype(parity)::value;
+      if constexpr (decltype(more)::value) {
+        // tile kt+1 has landed, for everyone after the barrier; tile kt's buffer is free then
+        if (kt + NSTAGE < nk) {  // steady state
+          wait_vmcnt<(NSTAGE - 2) * LOADS>();
+          __syncthreads();
+          issue();
+        } else {
+          wait_tiles<LOADS>(min(NSTAGE - 2, nk - 2 - kt));
+          __syncthreads();
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(kt + 1, 0, fa[P ^ 1][0]);
+        read_b(kt + 1, 0, fb[P ^ 1][0]);
+        mfma_step(fa[P][0], fb[P][0]);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(kt + 1, 1, fa[P ^ 1][1]);
+        read_b(kt + 1, 1, fb[P ^ 1][1]);
+        mfma_step(fa[P][1], fb[P][1]);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+        mfma_step(fa[P][0], fb[P][0]);
+        mfma_step(fa[P][1], fb[P][1]);
+      }
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    int kt = 0;
+    for (; kt + 2 < nk; kt += 2) {
+      tile_iter(kt, P0{}, std::true_type{});
+      tile_iter(kt + 1, P1{}, std::true_type{});
+    }
+    if (kt + 1 < nk) {
+      tile_iter(kt, P0{}, std::true_type{});
+      tile_iter(kt + 1, P1{}, std::false_type{});
+    } else {
+      tile_iter(kt, P0{}, std::false_type{});
+    }
   }
-  read_frags(nk - 1, 1, 1);
-  mfma_step(0);
-  interleave();
-  __builtin_amdgcn_sched_barrier(0);
-  mfma_step(1);
 
   // Epilogue: register group q of a tile holds columns n .. n+3 of row m,
   //   m = tile_m + lane % 32,  n = tile_n + 8 q + 4 (lane / 32).
@@ -304,12 +385,12 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool A_T, bool B_T, int EPI>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool FDEEP, bool A_T, bool B_T, int EPI>
 int launch(const DmaGemm& p, hipStream_t stream) {
   using OpA = Operand<BM, A_T, WGM * WGN>;
   using OpB = Operand<BN, B_T, WGM * WGN>;
   constexpr size_t lds = (size_t)NSTAGE * (OpA::kBytes + OpB::kBytes);
-  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, NSTAGE, A_T, B_T, EPI>;
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, NSTAGE, FDEEP, A_T, B_T, EPI>;
   static thread_local bool raised = false;
   if (lds > 64 * 1024 && !raised) {
     const hipError_t e =
@@ -322,36 +403,37 @@ int launch(const DmaGemm& p, hipStream_t stream) {
   return check_launch("gemm_dma");
 }
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool FDEEP>
 int launch_layout(const GemmArgs& g, const DmaGemm& p, hipStream_t stream) {
   if (!g.a_t && g.b_t) {
     switch (g.epi) {
-      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, false, true, EPI_BIAS>(p, stream);
-      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, false, true, EPI_BIAS_GELU>(p, stream);
-      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, false, true, EPI_BIAS_RES>(p, stream);
+      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, true, EPI_BIAS>(p, stream);
+      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, true, EPI_BIAS_GELU>(p, stream);
+      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, true, EPI_BIAS_RES>(p, stream);
       default: break;
     }
   } else if (!g.a_t && !g.b_t) {
     switch (g.epi) {
-      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, false, false, EPI_NONE>(p, stream);
-      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, false, false, EPI_MUL_DGELU>(p, stream);
-      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, false, false, EPI_ADD>(p, stream);
+      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, false, EPI_NONE>(p, stream);
+      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, false, EPI_MUL_DGELU>(p, stream);
+      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, false, EPI_ADD>(p, stream);
       default: break;
     }
   } else if (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32) {
-    return launch<BM, BN, WGM, WGN, NSTAGE, true, true, EPI_ACCUM_F32>(p, stream);
+    return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, true, true, EPI_ACCUM_F32>(p, stream);
   }
   return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: layout/epilogue combination not built");
 }
 
 }  // namespace
 
-// Tile configurations: 0 = 256 x 256 (4 wavefronts), 1 = 128 x 128 (4 wavefronts), 2 = 256 x 128 (4 wavefronts)
+// Tile configurations: 0 = 256 x 256, 1 = 128 x 128 with an 8-deep buffer ring, 2 = 256 x 128,
+// 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU).  All use 4 wavefronts.
 bool gemm_dma_supported(const GemmArgs& g, int config) {
   const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
                      (!g.a_t && !g.b_t && (g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD)) ||
                      (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32);
-  const int bm = config == 1 ? 128 : 256, bn = config == 0 ? 256 : 128;
+  const int bm = (config == 1 || config == 4) ? 128 : 256, bn = config == 0 ? 256 : 128;
   // lane offsets are 32-bit byte offsets from the tile origin
   const long span_a = (long)(g.a_t ? kBK : bm) * g.lda * 2, span_b = (long)(g.b_t ? kBK : bn) * g.ldb * 2;
   return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % kBK == 0 && g.K >= kBK && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
@@ -365,9 +447,10 @@ int gemm_dma(const GemmArgs& g, int config, hipStream_t stream) {
   p.bias = (const bf16*)g.bias; p.aux = (const bf16*)g.aux; p.aux_out = (bf16*)g.aux_out;
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
   switch (config) {
-    case 0: return launch_layout<256, 256, 2, 2, 4>(g, p, stream);
-    case 1: return launch_layout<128, 128, 2, 2, 4>(g, p, stream);
-    default: return launch_layout<256, 128, 2, 2, 4>(g, p, stream);
+    case 0: return launch_layout<256, 256, 2, 2, 4, false>(g, p, stream);
+    case 1: return launch_layout<128, 128, 2, 2, 8, true>(g, p, stream);   // 128 KiB LDS: one workgroup per CU
+    case 4: return launch_layout<128, 128, 2, 2, 4, true>(g, p, stream);   // 64 KiB LDS: two per CU
+    default: return launch_layout<256, 128, 2, 2, 4, false>(g, p, stream);
   }
 }
 
