@@ -235,10 +235,14 @@ enum {
  * C, aux, aux_out are row-major with leading dimension ldc; bias has N entries.
  * The forward linears use (a_t, b_t) = (0, 1), the input gradients (0, 0), the
  * weight gradients (1, 1) with HANAYO_EPI_ACCUM_F32.
+ * colsum (device fp32 [N], may be NULL; needs b_t = 1 and ldb = N): colsum[n] += sum over k of B[k][n],
+ * the bias gradient that belongs to a weight-gradient GEMM; the bf16 MFMA kernels fold it into the
+ * GEMM (fp32 atomics, so the summation order is not fixed), the others run a column-sum pass using
+ * colsum_scratch (device, at least 64 * N floats).
  */
 int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
-                   int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out,
-                   void* hip_stream);
+                   int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, float* colsum,
+                   float* colsum_scratch, void* hip_stream);
 
 /* Tuning knob for measurements: which bf16 MFMA GEMM kernel hanayo_op_gemm and the chunk calls use.
    -1 (default) = chosen from the shape; 0 / 1 / 2 / 4 = direct-to-LDS kernel with 256x256 / 128x128

@@ -80,8 +80,8 @@ int linear_bwd_params(const Shape& sh, const void* x, const void* dy, float* dW,
   g.A = x; g.B = dy; g.C = dW;
   g.M = K; g.N = N; g.K = sh.T; g.lda = K; g.ldb = N; g.ldc = N;
   g.a_t = true; g.b_t = true; g.epi = k::EPI_ACCUM_F32;
-  TRY(k::gemm(sh.dtype, g, st));
-  return k::colsum_add(sh.dtype, dy, sh.T, N, db, partial, st);
+  g.colsum = db; g.colsum_scratch = partial;  // bias gradient rides along with the weight gradient
+  return k::gemm(sh.dtype, g, st);
 }
 
 }  // namespace
@@ -95,7 +95,9 @@ void set_gemm_config(int config) { g_gemm_config = config; }
 
 int gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
   if (g.M < 1 || g.N < 1 || g.K < 1) return set_error(HANAYO_EINVAL, "gemm: empty problem");
+  if (g.colsum && (!g.b_t || !g.colsum_scratch)) return set_error(HANAYO_EINVAL, "gemm: colsum needs b_t and scratch");
   if (dtype == HANAYO_BF16) {
+    // the direct-to-LDS kernels fold the column sums into the GEMM
     if (g_gemm_config >= 0 && g_gemm_config != 3 && gemm_dma_supported(g, g_gemm_config))
       return gemm_dma(g, g_gemm_config, stream);
     if (g_gemm_config == -1) {
@@ -107,9 +109,12 @@ int gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
       if (t128 <= 320 && gemm_dma_supported(g, 1)) return gemm_dma(g, 1, stream);
       if (gemm_dma_supported(g, 4)) return gemm_dma(g, 4, stream);
     }
-    if (gemm_mfma_supported(g)) return gemm_mfma(g, stream);
   }
-  return gemm_alu(dtype, g, stream);
+  int rc;
+  if (dtype == HANAYO_BF16 && gemm_mfma_supported(g)) rc = gemm_mfma(g, stream);
+  else rc = gemm_alu(dtype, g, stream);
+  if (rc || !g.colsum) return rc;
+  return colsum_add(dtype, g.B, g.K, g.N, g.colsum, g.colsum_scratch, stream);  // B is stored [K][ldb = N]
 }
 
 int attn_forward(int dtype, const AttnArgs& a, hipStream_t stream) {

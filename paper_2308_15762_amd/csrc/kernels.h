@@ -47,6 +47,11 @@ struct GemmArgs {
   int lda, ldb, ldc;
   bool a_t, b_t;
   Epilogue epi;
+  // Optional, only with b_t: colsum[n] (fp32) += sum over k of B[k][n] (the bias gradient that
+  // goes with a weight-gradient GEMM).  colsum_scratch: at least 64 * N floats, used by the
+  // kernels that cannot fold the sums into the GEMM itself.
+  float* colsum;
+  float* colsum_scratch;
 };
 int gemm(int dtype, const GemmArgs& g, hipStream_t stream);
 

@@ -39,6 +39,7 @@ struct DmaGemm {
   bf16* aux_out;
   int M, N, K;
   int lda, ldb, ldc;
+  float* colsum;  // see GemmArgs; folded into the kernel (B_T only)
 };
 
 constexpr int kBK = 32;
@@ -232,6 +233,27 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
       for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
   };
 
+  // Column sums of B (bias gradient): the K tiles are dealt round-robin to the workgroups of a
+  // column of the grid, each thread adds 4 columns x (32 / kColRowGroups) rows of a tile it owns.
+  constexpr int kColGroups = BN / 4, kColRowGroups = NW * 64 / kColGroups, kColRows = kBK / kColRowGroups;
+  float csum[4] = {0.f, 0.f, 0.f, 0.f};
+  auto colsum_tile = [&](int kt) {
+    if constexpr (B_T) {
+      if (p.colsum && kt % (int)gridDim.y == (int)blockIdx.y) {
+        const char* b_lds = smem + (kt % NSTAGE) * STAGE_BYTES + OpA::kBytes;
+        const int c = (threadIdx.x % kColGroups) * 4, rg = threadIdx.x / kColGroups;
+#pragma unroll
+        for (int r = 0; r < kColRows; ++r) {
+          const int row = rg * kColRows + r;
+          const int slot = (c >> 3) ^ ((row & 3) << 2);
+          const bf16x4 v = *reinterpret_cast<const bf16x4*>(b_lds + (row * OpB::kSlotsPerRow + slot) * 16 + (c & 7) * 2);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) csum[e] += (float)v[e];
+        }
+      }
+    }
+  };
+
   if constexpr (!FDEEP) {
 #pragma unroll
     for (int t = 0; t < NSTAGE - 1; ++t)
@@ -240,6 +262,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
     // Tile 0 has landed once only tiles 1 .. NSTAGE-2 are outstanding.
     wait_tiles<LOADS>(min(NSTAGE - 2, nk - 1));
     __syncthreads();
+    colsum_tile(0);
     read_a(0, 0, fa[0]);
     read_b(0, 0, fb[0]);
     // Steady state, per K tile (two MFMA steps of 16):
@@ -262,6 +285,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
         wait_tiles<LOADS>(min(NSTAGE - 3, nk - 2 - kt));
         __syncthreads();
       }
+      colsum_tile(kt + 1);
       __builtin_amdgcn_sched_barrier(0);
       read_a(kt + 1, 0, fa[0]);
       read_b(kt + 1, 0, fb[0]);
@@ -284,6 +308,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
     bf16x8 fa[2][2][TM], fb[2][2][TN];  // [tile parity][step]
     wait_tiles<LOADS>(min(NSTAGE - 1, nk - 1));
     __syncthreads();
+    colsum_tile(0);
     read_a(0, 0, fa[0][0]);
     read_b(0, 0, fb[0][0]);
     read_a(0, 1, fa[0][1]);
@@ -300,6 +325,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
           wait_tiles<LOADS>(min(NSTAGE - 2, nk - 2 - kt));
           __syncthreads();
         }
+        colsum_tile(kt + 1);
         __builtin_amdgcn_sched_barrier(0);
         read_a(kt + 1, 0, fa[P ^ 1][0]);
         read_b(kt + 1, 0, fb[P ^ 1][0]);
@@ -328,6 +354,23 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
       tile_iter(kt + 1, P1{}, std::false_type{});
     } else {
       tile_iter(kt, P0{}, std::false_type{});
+    }
+  }
+
+  if constexpr (B_T) {
+    if (p.colsum) {  // combine the row groups through LDS (the ring is idle now), one atomic per column
+      __syncthreads();
+      float* red = reinterpret_cast<float*>(smem);
+      const int c = (threadIdx.x % kColGroups) * 4, rg = threadIdx.x / kColGroups;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) red[rg * BN + c + e] = csum[e];
+      __syncthreads();
+      if (threadIdx.x < BN) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < kColRowGroups; ++g) t += red[g * BN + threadIdx.x];
+        atomicAdd(p.colsum + n0 + threadIdx.x, t);
+      }
     }
   }
 
@@ -446,6 +489,7 @@ int gemm_dma(const GemmArgs& g, int config, hipStream_t stream) {
   p.A = (const bf16*)g.A; p.B = (const bf16*)g.B; p.C = (bf16*)g.C; p.Cf = (float*)g.C;
   p.bias = (const bf16*)g.bias; p.aux = (const bf16*)g.aux; p.aux_out = (bf16*)g.aux_out;
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+  p.colsum = g.b_t ? g.colsum : nullptr;
   switch (config) {
     case 0: return launch_layout<256, 256, 2, 2, 4, false>(g, p, stream);
     case 1: return launch_layout<128, 128, 2, 2, 8, true>(g, p, stream);   // 128 KiB LDS: one workgroup per CU

@@ -19,7 +19,8 @@ int check_dtype(int dtype) {
 extern "C" {
 
 int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
-                   int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, void* hip_stream) {
+                   int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, float* colsum,
+                   float* colsum_scratch, void* hip_stream) {
   if (int rc = check_dtype(dtype)) return rc;
   if (!A || !B || !C || M < 1 || N < 1 || K < 1) return set_error(HANAYO_EINVAL, "op_gemm: NULL operand or empty problem");
   if (epilogue < HANAYO_EPI_NONE || epilogue > HANAYO_EPI_ACCUM_F32) return set_error(HANAYO_EINVAL, "op_gemm: epilogue");
@@ -32,6 +33,9 @@ int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int 
   g.A = A; g.B = B; g.C = C; g.bias = bias; g.aux = aux; g.aux_out = aux_out;
   g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.a_t = a_t != 0; g.b_t = b_t != 0; g.epi = static_cast<k::Epilogue>(epilogue);
+  if (colsum && (!b_t || !colsum_scratch || ldb != N))
+    return set_error(HANAYO_EINVAL, "op_gemm: colsum needs b_t = 1, ldb = N and a scratch buffer");
+  g.colsum = colsum; g.colsum_scratch = colsum_scratch;
   return k::gemm(dtype, g, static_cast<hipStream_t>(hip_stream));
 }
 

@@ -87,7 +87,7 @@ _lib.hanayo_stash_arena_bytes.restype = _sz
 _lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
-_lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp]
+_lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_op_gemm_config.argtypes = [_int]
 _lib.hanayo_op_layernorm_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _vp, _vp, _int, _int, ctypes.c_float, _vp]
 _lib.hanayo_op_layernorm_backward.argtypes = [_int] + [_vp] * 9 + [_int, _int, _vp]
@@ -223,9 +223,9 @@ def hanayo_chunk_backward(desc, weights, grads, dy, valid_len, stash_entry, dx, 
 
 
 def hanayo_op_gemm(dtype, A, B, C, M, N, K, lda, ldb, ldc, a_t, b_t, epilogue, bias=None, aux=None, aux_out=None,
-                   stream=None):
+                   colsum=None, colsum_scratch=None, stream=None):
     _check(_lib.hanayo_op_gemm(dtype, _ptr(A), _ptr(B), _ptr(C), M, N, K, lda, ldb, ldc, int(a_t), int(b_t), epilogue,
-                               _ptr(bias), _ptr(aux), _ptr(aux_out), stream))
+                               _ptr(bias), _ptr(aux), _ptr(aux_out), _ptr(colsum), _ptr(colsum_scratch), stream))
 
 
 def hanayo_op_gemm_config(config):

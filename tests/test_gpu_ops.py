@@ -85,9 +85,17 @@ def run_gemm_case(dtype, layout, shape):
                     hn.EPI_BIAS_RES: ref + bias + aux, hn.EPI_MUL_DGELU: ref * OB.gelu_grad(aux.astype(np.float64)),
                     hn.EPI_ADD: ref + aux}[epi]
         out2 = torch.empty((M, N), dtype=Ad.dtype, device="cuda") if epi == hn.EPI_BIAS_GELU else None
+        cs = cs0 = scratch = None
+        if epi == hn.EPI_ACCUM_F32 and N % 8 == 0:   # the bias gradient rides along: column sums of B
+            cs0 = rng.normal(size=N).astype(np.float32)
+            cs = torch.from_numpy(cs0).cuda()
+            scratch = torch.empty(64 * N, dtype=torch.float32, device="cuda")
         hn.hanayo_op_gemm(DT[dtype], Ad, Bd, Cd, M, N, K, M if a_t else K, N if b_t else K, N, a_t, b_t, epi,
-                          bd, xd, out2)
+                          bd, xd, out2, cs, scratch)
         torch.cuda.synchronize()
+        if cs is not None:
+            want_cs = B.astype(np.float64).sum(0)
+            assert nerr(cs.cpu().numpy() - cs0, want_cs) <= 1e-4, "column sums"
         e = nerr(host(Cd), want)
         assert e <= TOL[dtype], "epilogue %d: %.3g" % (epi, e)
         if out2 is not None:
