@@ -237,9 +237,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
   // column of the grid, each thread adds 4 columns x (32 / kColRowGroups) rows of a tile it owns.
   constexpr int kColGroups = BN / 4, kColRowGroups = NW * 64 / kColGroups, kColRows = kBK / kColRowGroups;
   float csum[4] = {0.f, 0.f, 0.f, 0.f};
+  int colsum_next = p.colsum ? (int)blockIdx.y : 0x7fffffff;  // next K tile this workgroup sums
   auto colsum_tile = [&](int kt) {
     if constexpr (B_T) {
-      if (p.colsum && kt % (int)gridDim.y == (int)blockIdx.y) {
+      if (kt == colsum_next) {
+        colsum_next += (int)gridDim.y;
         const char* b_lds = smem + (kt % NSTAGE) * STAGE_BYTES + OpA::kBytes;
         const int c = (threadIdx.x % kColGroups) * 4, rg = threadIdx.x / kColGroups;
 #pragma unroll

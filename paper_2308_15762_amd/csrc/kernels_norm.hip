@@ -67,15 +67,19 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 }
 
 // ------------------------------------------------------------------ LN backward
-// Each wavefront walks rows row0, row0 + stride, ...; its lanes keep the column
-// sums of dout*xhat and dout for their columns in registers.  The four
-// wavefronts of a block are then combined through LDS into one partial row.
-template <typename T, int NV>
-__global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ x,
+// Workgroup = 8 wavefronts; each wavefront walks rows two at a time (both rows' loads are
+// issued before either is reduced, which doubles the bytes in flight), its lanes keep the
+// column sums of dout*xhat and dout for their columns in registers.  The eight wavefronts are
+// combined through LDS (upper four into lower four, then the four into one partial row).
+// U = rows in flight per wavefront (2 where the registers allow), WAVES = wavefronts per workgroup
+// (8, or 4 for the widest rows whose register arrays need the larger per-wavefront budget).
+template <typename T, int NV, int U, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ x,
                                                      const T* __restrict__ gamma, const float2* __restrict__ stats,
                                                      const T* __restrict__ addend, T* __restrict__ dz,
                                                      float* __restrict__ partial, int rows, int H) {
-  extern __shared__ float red[];  // [kRowsPerBlock][H]
+  extern __shared__ float red[];  // [4][H]
+  constexpr int kBwdWaves = WAVES;
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
   float acc_g[NV][8], acc_b[NV][8], gm[NV][8];
@@ -86,87 +90,117 @@ __global__ __launch_bounds__(256) void ln_bwd_kernel(const T* __restrict__ dout,
     for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = gm[i][j] = 0.f;
     if (c < H) load8(gamma + c, gm[i]);
   }
-  for (int row = blockIdx.x * kRowsPerBlock + wave; row < rows; row += gridDim.x * kRowsPerBlock) {
-    const float2 st = stats[row];
-    const size_t base = (size_t)row * H;
-    float xh[NV][8], dy[NV][8];
-    float s1 = 0.f, s2 = 0.f;
+  const int stride = gridDim.x * kBwdWaves;
+  for (int row0 = blockIdx.x * kBwdWaves + wave; row0 < rows; row0 += U * stride) {
+    const int row1 = row0 + stride;
+    const bool has1 = U == 2 && row1 < rows;
+    float xh[U][NV][8], dy[U][NV][8];
+    float2 st[U];
+    st[0] = stats[row0];
+    if (U == 2) st[U - 1] = has1 ? stats[row1] : make_float2(0.f, 0.f);
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 8;
-      if (c < H) {
-        load8(x + base + c, xh[i]);
-        load8(dout + base + c, dy[i]);
+    for (int u = 0; u < U; ++u) {
+      const size_t base = (size_t)(u ? row1 : row0) * H;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          xh[i][j] = (xh[i][j] - st.x) * st.y;
-          acc_g[i][j] += dy[i][j] * xh[i][j];
-          acc_b[i][j] += dy[i][j];
-          const float dxh = dy[i][j] * gm[i][j];
-          s1 += dxh;
-          s2 += dxh * xh[i][j];
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 8;
+        if (c < H && (u == 0 || has1)) {
+          load8(x + base + c, xh[u][i]);
+          load8(dout + base + c, dy[u][i]);
         }
       }
     }
-    const float c1 = wave_sum(s1) / (float)H;
-    const float c2 = wave_sum(s2) / (float)H;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 8;
-      if (c < H) {
-        float o[8];
+    for (int u = 0; u < U; ++u) {
+      if (u == 1 && !has1) break;
+      const size_t base = (size_t)(u ? row1 : row0) * H;
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) o[j] = (dy[i][j] * gm[i][j] - c1 - xh[i][j] * c2) * st.y;
-        if (addend) {
-          float a[8];
-          load8(addend + base + c, a);
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 8;
+        if (c < H) {
 #pragma unroll
-          for (int j = 0; j < 8; ++j) o[j] += a[j];
+          for (int j = 0; j < 8; ++j) {
+            xh[u][i][j] = (xh[u][i][j] - st[u].x) * st[u].y;
+            acc_g[i][j] += dy[u][i][j] * xh[u][i][j];
+            acc_b[i][j] += dy[u][i][j];
+            const float dxh = dy[u][i][j] * gm[i][j];
+            s1 += dxh;
+            s2 += dxh * xh[u][i][j];
+          }
         }
-        store8(dz + base + c, o);
+      }
+      const float c1 = wave_sum(s1) / (float)H;
+      const float c2 = wave_sum(s2) / (float)H;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 8;
+        if (c < H) {
+          float o[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[j] = (dy[u][i][j] * gm[i][j] - c1 - xh[u][i][j] * c2) * st[u].y;
+          if (addend) {
+            float a[8];
+            load8(addend + base + c, a);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) o[j] += a[j];
+          }
+          store8(dz + base + c, o);
+        }
       }
     }
   }
-  // combine the block's four wavefronts: first the gamma sums, then the beta sums
+  // combine: pass 0 = gamma sums, pass 1 = beta sums
   for (int pass = 0; pass < 2; ++pass) {
+    if (WAVES == 8 && wave >= 4) {
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = (i * 64 + lane) * 8;
-      if (c < H) {
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 8;
+        if (c < H) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) red[wave * H + c + j] = pass == 0 ? acc_g[i][j] : acc_b[i][j];
+          for (int j = 0; j < 8; ++j) red[(wave - 4) * H + c + j] = pass == 0 ? acc_g[i][j] : acc_b[i][j];
+        }
+      }
+    }
+    if (WAVES == 8) __syncthreads();
+    if (wave < 4) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = (i * 64 + lane) * 8;
+        if (c < H) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            float v = pass == 0 ? acc_g[i][j] : acc_b[i][j];
+            if (WAVES == 8) v += red[wave * H + c + j];
+            red[wave * H + c + j] = v;
+          }
+        }
       }
     }
     __syncthreads();
     for (int c = threadIdx.x; c < H; c += blockDim.x) {
       float t = 0.f;
 #pragma unroll
-      for (int w = 0; w < kRowsPerBlock; ++w) t += red[w * H + c];
+      for (int w = 0; w < 4; ++w) t += red[w * H + c];
       partial[(size_t)blockIdx.x * 2 * H + pass * H + c] = t;
     }
     __syncthreads();
   }
 }
 
-// out[c] += sum_r partial[r][c] for c in [0, n): a block owns 32 columns, its 8 row groups
-// split the rows, LDS combines them in a fixed order.  Columns >= split go to out1[c - split].
+// out[c] += sum_r partial[r][c] for c in [0, n): a thread owns one column of a slab of 32 partial
+// rows and adds its sum with one atomic, so the reduction is spread over (n / 256) x (rows / 32)
+// workgroups instead of running down the rows in a few.  Columns >= split go to out1[c - split].
+// (fp32 atomics: the order in which the slabs are added is not fixed.)
+constexpr int kFinalizeRows = 32;
 __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n,
                                                        float* __restrict__ out0, float* __restrict__ out1, int split) {
-  __shared__ float red[8][33];
-  const int cl = threadIdx.x & 31, rg = threadIdx.x >> 5;
-  const int c = blockIdx.x * 32 + cl;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c >= n) return;
+  const int r0 = blockIdx.y * kFinalizeRows, r1 = min(rows, r0 + kFinalizeRows);
   float t = 0.f;
-  if (c < n)
-    for (int r = rg; r < rows; r += 8) t += partial[(size_t)r * ld + c];
-  red[rg][cl] = t;
-  __syncthreads();
-  if (rg == 0 && c < n) {
-    float sum = 0.f;
-#pragma unroll
-    for (int g = 0; g < 8; ++g) sum += red[g][cl];
-    float* dst = c < split ? out0 + c : out1 + (c - split);
-    *dst += sum;
-  }
+  for (int r = r0; r < r1; ++r) t += partial[(size_t)r * ld + c];
+  atomicAdd(c < split ? out0 + c : out1 + (c - split), t);
 }
 
 // ------------------------------------------------------------------ column sums
@@ -218,22 +252,23 @@ int ln_forward_t(const void* x, const void* gamma, const void* beta, void* out, 
 template <typename T>
 int ln_backward_t(const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend, void* dz,
                   float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
-  int blocks = (T_ + kRowsPerBlock - 1) / kRowsPerBlock;
-  if (blocks > 256) blocks = 256;  // a wavefront then walks several rows; 256 partial rows at most
-  const size_t lds = (size_t)kRowsPerBlock * H * sizeof(float);
   const int nv = (H + 511) / 512;
-#define LAUNCH(NV)                                                                                            \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NV>), dim3(blocks), dim3(256), lds, stream, (const T*)dout, (const T*)x, \
-                     (const T*)gamma, stats, (const T*)addend, (T*)dz, partial, T_, H)
-  if (nv <= 1) LAUNCH(1);
-  else if (nv <= 2) LAUNCH(2);
-  else if (nv <= 4) LAUNCH(4);
-  else LAUNCH(8);
+  const int waves = nv <= 4 ? 8 : 4;
+  int blocks = (T_ + waves - 1) / waves;
+  if (blocks > 256) blocks = 256;  // a wavefront then walks several rows; 256 partial rows at most
+  const size_t lds = (size_t)4 * H * sizeof(float);
+#define LAUNCH(NV, U, WAVES)                                                                                   \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NV, U, WAVES>), dim3(blocks), dim3(WAVES * 64), lds, stream, (const T*)dout, \
+                     (const T*)x, (const T*)gamma, stats, (const T*)addend, (T*)dz, partial, T_, H)
+  if (nv <= 1) LAUNCH(1, 2, 8);
+  else if (nv <= 2) LAUNCH(2, 2, 8);
+  else if (nv <= 4) LAUNCH(4, 1, 8);
+  else LAUNCH(8, 1, 4);
 #undef LAUNCH
   int rc = check_launch("ln_backward");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((2 * H + 31) / 32), dim3(256), 0, stream, partial, blocks, 2 * H, 2 * H,
-                     dgamma, dbeta, H);
+  hipLaunchKernelGGL(finalize_kernel, dim3((2 * H + 255) / 256, (blocks + kFinalizeRows - 1) / kFinalizeRows), dim3(256), 0,
+                     stream, partial, blocks, 2 * H, 2 * H, dgamma, dbeta, H);
   return check_launch("ln_backward finalize");
 }
 
@@ -246,7 +281,8 @@ int colsum_t(const void* in, int T_, int N, float* out, float* partial, hipStrea
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, stream, (const T*)in, T_, N, partial);
   int rc = check_launch("colsum");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((N + 31) / 32), dim3(256), 0, stream, partial, gy, N, N, out, out, N);
+  hipLaunchKernelGGL(finalize_kernel, dim3((N + 255) / 256, (gy + kFinalizeRows - 1) / kFinalizeRows), dim3(256), 0, stream,
+                     partial, gy, N, N, out, out, N);
   return check_launch("colsum finalize");
 }
 
