@@ -131,12 +131,19 @@ __device__ __forceinline__ bf16x8 frag_t(const char* lds, int c0, int kk, int la
   return u.v;
 }
 
-// FDEEP: fragments are read a whole K tile ahead (small wavefront tiles, where one MFMA step is
-// shorter than the LDS latency); a tile's LDS buffer is then free one iteration earlier, so all
-// NSTAGE buffers can be in flight.
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool FDEEP, bool A_T, bool B_T, int EPI>
-__global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
-  constexpr int NW = WGM * WGN;
+// MODE 0: fragments are read one MFMA step ahead (large wavefront tiles).
+// MODE 1: fragments are read a whole K tile ahead (small wavefront tiles, where one MFMA step is
+//         shorter than the LDS latency); a tile's LDS buffer is then free one iteration earlier,
+//         so all NSTAGE buffers can be in flight.
+// MODE 2: as 1, with twice the wavefronts: the first WGM*WGN take MFMA step 0 of every K tile, the
+//         second WGM*WGN take step 1, and the two partial tiles are added through LDS at the end.
+//         A SIMD then holds two wavefronts that fill each other's stalls, and twice as many
+//         wavefronts issue LDS reads (the per-wavefront LDS request rate limits the 4-wavefront form).
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE, bool A_T, bool B_T, int EPI>
+__global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_kernel(DmaGemm p) {
+  constexpr bool FDEEP = MODE >= 1;
+  constexpr int NSP = WGM * WGN;                 // wavefronts that tile the output
+  constexpr int NW = NSP * (MODE == 2 ? 2 : 1);  // wavefronts in the workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   using OpA = Operand<BM, A_T, NW>;
   using OpB = Operand<BN, B_T, NW>;
@@ -150,7 +157,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
   const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave / WGN, wn = wave % WGN;
+  const int khalf = wave / NSP;  // MODE 2: which MFMA step of a K tile this wavefront owns
+  const int wm = (wave % NSP) / WGN, wn = (wave % NSP) % WGN;
   const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
   const int nk = p.K / kBK;
 
@@ -307,14 +315,19 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
 #pragma unroll
     for (int t = 0; t < NSTAGE; ++t)
       if (t < nk) issue();
-    bf16x8 fa[2][2][TM], fb[2][2][TN];  // [tile parity][step]
+    bf16x8 fa[2][2][TM], fb[2][2][TN];  // [tile parity][step]; MODE 2 uses step slot 0 only
     wait_tiles<LOADS>(min(NSTAGE - 1, nk - 1));
     __syncthreads();
     colsum_tile(0);
-    read_a(0, 0, fa[0][0]);
-    read_b(0, 0, fb[0][0]);
-    read_a(0, 1, fa[0][1]);
-    read_b(0, 1, fb[0][1]);
+    if constexpr (MODE == 1) {
+      read_a(0, 0, fa[0][0]);
+      read_b(0, 0, fb[0][0]);
+      read_a(0, 1, fa[0][1]);
+      read_b(0, 1, fb[0][1]);
+    } else {
+      read_a(0, khalf, fa[0][0]);
+      read_b(0, khalf, fb[0][0]);
+    }
     auto tile_iter = [&](int kt, auto parity, auto more) {
       constexpr int P = decltype(parity)::value;
       if constexpr (decltype(more)::value) {
@@ -329,19 +342,26 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
         }
         colsum_tile(kt + 1);
         __builtin_amdgcn_sched_barrier(0);
-        read_a(kt + 1, 0, fa[P ^ 1][0]);
-        read_b(kt + 1, 0, fb[P ^ 1][0]);
-        mfma_step(fa[P][0], fb[P][0]);
-        interleave();
-        __builtin_amdgcn_sched_barrier(0);
-        read_a(kt + 1, 1, fa[P ^ 1][1]);
-        read_b(kt + 1, 1, fb[P ^ 1][1]);
-        mfma_step(fa[P][1], fb[P][1]);
-        interleave();
+        if constexpr (MODE == 1) {
+          read_a(kt + 1, 0, fa[P ^ 1][0]);
+          read_b(kt + 1, 0, fb[P ^ 1][0]);
+          mfma_step(fa[P][0], fb[P][0]);
+          interleave();
+          __builtin_amdgcn_sched_barrier(0);
+          read_a(kt + 1, 1, fa[P ^ 1][1]);
+          read_b(kt + 1, 1, fb[P ^ 1][1]);
+          mfma_step(fa[P][1], fb[P][1]);
+          interleave();
+        } else {
+          read_a(kt + 1, khalf, fa[P ^ 1][0]);
+          read_b(kt + 1, khalf, fb[P ^ 1][0]);
+          mfma_step(fa[P][0], fb[P][0]);
+          interleave();
+        }
         __builtin_amdgcn_sched_barrier(0);
       } else {
         mfma_step(fa[P][0], fb[P][0]);
-        mfma_step(fa[P][1], fb[P][1]);
+        if constexpr (MODE == 1) mfma_step(fa[P][1], fb[P][1]);
       }
     };
     using P0 = std::integral_constant<int, 0>;
@@ -356,6 +376,38 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
       tile_iter(kt + 1, P1{}, std::false_type{});
     } else {
       tile_iter(kt, P0{}, std::false_type{});
+    }
+  }
+
+  if constexpr (MODE == 2) {
+    // add the step-1 group's partial tile to the step-0 group's: through LDS, 16 KiB per pair
+    __syncthreads();  // every wavefront is done with the load ring
+    float* xch = reinterpret_cast<float*>(smem) + (size_t)(wave % NSP) * (TM * TN * 16 * 64);
+    if (khalf == 1) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+            *reinterpret_cast<f32x4*>(xch + (((i * TN + j) * 4 + q) * 64 + lane) * 4) = v;
+          }
+    }
+    __syncthreads();
+    if (khalf == 0) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4 v = *reinterpret_cast<const f32x4*>(xch + (((i * TN + j) * 4 + q) * 64 + lane) * 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += v[e];
+          }
     }
   }
 
@@ -376,66 +428,81 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_dma_kernel(DmaGemm p) {
     }
   }
 
-  // Epilogue: register group q of a tile holds columns n .. n+3 of row m,
-  //   m = tile_m + lane % 32,  n = tile_n + 8 q + 4 (lane / 32).
+  // Epilogue through LDS.  In registers a lane holds 4 consecutive columns of one row, and the 32
+  // lanes of a half wavefront hold 32 different rows: stores (and the reads of the residual or
+  // pre-activation operand) straight from that layout touch 16 bytes per row.  Instead, one band
+  // of 32 rows per wavefront row (WGM * 32 rows x BN columns, fp32) at a time is parked in LDS and
+  // taken out again with each thread owning 8 consecutive columns, so every global access of the
+  // epilogue is a run of full rows: 16 bytes per lane, whole 128-byte lines.
+  constexpr int EP = BN + 4;  // fp32 row pitch in LDS: +4 keeps the register-layout writes conflict-free
+  float* stage = reinterpret_cast<float*>(smem);
+  constexpr int kBandRows = WGM * 32, kVecPerRow = BN / 8, kVecs = kBandRows * kVecPerRow;
+  static_assert((size_t)kBandRows * EP * 4 <= (size_t)NSTAGE * STAGE_BYTES, "epilogue band must fit the load ring");
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm * WM + i * 32 + (lane & 31);
+    __syncthreads();  // the ring (first band) or the previous band is no longer being read
+    if (MODE != 2 || khalf == 0) {
+      float* dst = stage + (wm * 32 + (lane & 31)) * EP + wn * WN + 4 * (lane >> 5);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn * WN + j * 32 + 8 * q + 4 * (lane >> 5);
-        const size_t at = (size_t)m * p.ldc + n;
-        float v[4];
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-        if constexpr (EPI == EPI_ACCUM_F32) {
-          f32x4 c = *reinterpret_cast<f32x4*>(p.Cf + at);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) c[e] += v[e];
-          *reinterpret_cast<f32x4*>(p.Cf + at) = c;
-        } else {
-          if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
-            const bf16x4 b = *reinterpret_cast<const bf16x4*>(p.bias + n);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)b[e];
-          }
-          if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_ADD) {
-            const bf16x4 x = *reinterpret_cast<const bf16x4*>(p.aux + at);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)x[e];
-          }
-          if constexpr (EPI == EPI_MUL_DGELU) {
-            const bf16x4 h = *reinterpret_cast<const bf16x4*>(p.aux + at);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_fast((float)h[e]);
-          }
-          if constexpr (EPI == EPI_BIAS_GELU) {
-            bf16x4 h;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              h[e] = (bf16)v[e];
-              v[e] = gelu_fast(v[e]);
-            }
-            *reinterpret_cast<bf16x4*>(p.aux_out + at) = h;
-          }
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16)v[e];
-          *reinterpret_cast<bf16x4*>(p.C + at) = o;
+          for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+          *reinterpret_cast<f32x4*>(dst + j * 32 + 8 * q) = v;
         }
+    }
+    __syncthreads();
+    for (int vi = threadIdx.x; vi < kVecs; vi += NW * 64) {
+      const int br = vi / kVecPerRow, c = (vi % kVecPerRow) * 8;  // band row, first column
+      const int m = m0 + (br >> 5) * WM + i * 32 + (br & 31), n = n0 + c;
+      const size_t at = (size_t)m * p.ldc + n;
+      float v[8];
+      load8(stage + br * EP + c, v);
+      if constexpr (EPI == EPI_ACCUM_F32) {
+        float cur[8];
+        load8(p.Cf + at, cur);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) cur[e] += v[e];
+        store8(p.Cf + at, cur);
+      } else {
+        if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
+          float b[8];
+          load8(p.bias + n, b);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += b[e];
+        }
+        if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_ADD) {
+          float x[8];
+          load8(p.aux + at, x);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] += x[e];
+        }
+        if constexpr (EPI == EPI_MUL_DGELU) {
+          float h[8];
+          load8(p.aux + at, h);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(h[e]);
+        }
+        if constexpr (EPI == EPI_BIAS_GELU) {
+          store8(p.aux_out + at, v);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) v[e] = gelu_fast(v[e]);
+        }
+        store8(p.C + at, v);
       }
     }
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool FDEEP, bool A_T, bool B_T, int EPI>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE, bool A_T, bool B_T, int EPI>
 int launch(const DmaGemm& p, hipStream_t stream) {
-  using OpA = Operand<BM, A_T, WGM * WGN>;
-  using OpB = Operand<BN, B_T, WGM * WGN>;
+  constexpr int NW = WGM * WGN * (MODE == 2 ? 2 : 1);
+  using OpA = Operand<BM, A_T, NW>;
+  using OpB = Operand<BN, B_T, NW>;
   constexpr size_t lds = (size_t)NSTAGE * (OpA::kBytes + OpB::kBytes);
-  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, NSTAGE, FDEEP, A_T, B_T, EPI>;
+  auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, NSTAGE, MODE, A_T, B_T, EPI>;
   static thread_local bool raised = false;
   if (lds > 64 * 1024 && !raised) {
     const hipError_t e =
@@ -444,28 +511,28 @@ int launch(const DmaGemm& p, hipStream_t stream) {
     raised = true;
   }
   const dim3 grid(p.N / BN, p.M / BM);
-  hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), lds, stream, p);
+  hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, p);
   return check_launch("gemm_dma");
 }
 
-template <int BM, int BN, int WGM, int WGN, int NSTAGE, bool FDEEP>
+template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE>
 int launch_layout(const GemmArgs& g, const DmaGemm& p, hipStream_t stream) {
   if (!g.a_t && g.b_t) {
     switch (g.epi) {
-      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, true, EPI_BIAS>(p, stream);
-      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, true, EPI_BIAS_GELU>(p, stream);
-      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, true, EPI_BIAS_RES>(p, stream);
+      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS>(p, stream);
+      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_GELU>(p, stream);
+      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_RES>(p, stream);
       default: break;
     }
   } else if (!g.a_t && !g.b_t) {
     switch (g.epi) {
-      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, false, EPI_NONE>(p, stream);
-      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, false, EPI_MUL_DGELU>(p, stream);
-      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, false, false, EPI_ADD>(p, stream);
+      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_NONE>(p, stream);
+      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_MUL_DGELU>(p, stream);
+      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_ADD>(p, stream);
       default: break;
     }
   } else if (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32) {
-    return launch<BM, BN, WGM, WGN, NSTAGE, FDEEP, true, true, EPI_ACCUM_F32>(p, stream);
+    return launch<BM, BN, WGM, WGN, NSTAGE, MODE, true, true, EPI_ACCUM_F32>(p, stream);
   }
   return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: layout/epilogue combination not built");
 }
@@ -478,7 +545,7 @@ bool gemm_dma_supported(const GemmArgs& g, int config) {
   const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
                      (!g.a_t && !g.b_t && (g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD)) ||
                      (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32);
-  const int bm = (config == 1 || config == 4) ? 128 : 256, bn = config == 0 ? 256 : 128;
+  const int bm = (config == 1 || config == 4 || config == 5) ? 128 : 256, bn = config == 0 ? 256 : 128;
   // lane offsets are 32-bit byte offsets from the tile origin
   const long span_a = (long)(g.a_t ? kBK : bm) * g.lda * 2, span_b = (long)(g.b_t ? kBK : bn) * g.ldb * 2;
   return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % kBK == 0 && g.K >= kBK && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
@@ -493,10 +560,11 @@ int gemm_dma(const GemmArgs& g, int config, hipStream_t stream) {
   p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
   p.colsum = g.b_t ? g.colsum : nullptr;
   switch (config) {
-    case 0: return launch_layout<256, 256, 2, 2, 4, false>(g, p, stream);
-    case 1: return launch_layout<128, 128, 2, 2, 8, true>(g, p, stream);   // 128 KiB LDS: one workgroup per CU
-    case 4: return launch_layout<128, 128, 2, 2, 4, true>(g, p, stream);   // 64 KiB LDS: two per CU
-    default: return launch_layout<256, 128, 2, 2, 4, false>(g, p, stream);
+    case 0: return launch_layout<256, 256, 2, 2, 4, 0>(g, p, stream);
+    case 1: return launch_layout<128, 128, 2, 2, 8, 1>(g, p, stream);  // 128 KiB LDS: one workgroup per CU
+    case 4: return launch_layout<128, 128, 2, 2, 4, 1>(g, p, stream);  // 64 KiB LDS: two per CU
+    case 5: return launch_layout<128, 128, 2, 2, 4, 2>(g, p, stream);  // 8 wavefronts, K steps split
+    default: return launch_layout<256, 128, 2, 2, 4, 0>(g, p, stream);
   }
 }
 

@@ -40,7 +40,7 @@ int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int 
 }
 
 int hanayo_op_gemm_config(int config) {
-  if (config < -1 || config > 4) return set_error(HANAYO_EINVAL, "op_gemm_config: config must be -1..4");
+  if (config < -1 || config > 5) return set_error(HANAYO_EINVAL, "op_gemm_config: config must be -1..5");
   k::set_gemm_config(config);
   return HANAYO_OK;
 }
