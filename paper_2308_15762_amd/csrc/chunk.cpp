@@ -101,13 +101,21 @@ int gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
     if (g_gemm_config >= 0 && g_gemm_config != 3 && gemm_dma_supported(g, g_gemm_config))
       return gemm_dma(g, g_gemm_config, stream);
     if (g_gemm_config == -1) {
-      // Measured on MI355X: the 256 x 256 tile wins once there are at least two of them per CU.
-      // Below that, 128 x 128 tiles: if at most about one per CU exists, each gets a CU's whole LDS
-      // as an 8-deep load ring; otherwise a 4-deep ring so that two workgroups share a CU.
-      const long t256 = (long)(g.M / 256) * (g.N / 256), t128 = (long)(g.M / 128) * (g.N / 128);
-      if (t256 >= 512 && gemm_dma_supported(g, 0)) return gemm_dma(g, 0, stream);
-      if (t128 <= 320 && gemm_dma_supported(g, 1)) return gemm_dma(g, 1, stream);
-      if (gemm_dma_supported(g, 4)) return gemm_dma(g, 4, stream);
+      // Pick the tile by a cost model fitted to timings on MI355X: a launch runs ceil(tiles / 256 CUs)
+      // rounds, each costing one K tile's time per 32 columns of K (0.88 us for 256 x 256, 0.52 us for
+      // 256 x 128, 0.295 us for 128 x 128 with two workgroups sharing a CU), plus a fixed start and
+      // epilogue cost.  Large tiles reuse operands better; small ones waste less of the last round.
+      static const struct { int config, bm, bn; double per_ktile, fixed; } kTiles[] = {
+          {0, 256, 256, 0.88, 10.0}, {2, 256, 128, 0.52, 8.0}, {4, 128, 128, 0.295, 5.0}};
+      int best = -1;
+      double best_cost = 0.0;
+      for (const auto& t : kTiles) {
+        if (!gemm_dma_supported(g, t.config)) continue;
+        const long tiles = (long)(g.M / t.bm) * (g.N / t.bn);
+        const double cost = t.fixed + (double)((tiles + 255) / 256) * (g.K / 32) * t.per_ktile;
+        if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
+      }
+      if (best >= 0) return gemm_dma(g, best, stream);
     }
   }
   int rc;

@@ -62,6 +62,24 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Workgroup -> output tile, XCD-aware.  The dispatcher hands consecutive workgroup ids to the chip's
+// 8 XCDs in turn, and each XCD has an L2 of its own, so workgroup w runs on XCD w % 8 as that XCD's
+// (w / 8)-th.  Each XCD therefore gets one contiguous run of tile numbers, and tile numbers walk the
+// tile grid in bands of kTileBand tile rows, column by column within a band: the workgroups resident
+// on one XCD at a time then cover a compact patch of the output and share their operand panels in
+// that L2 instead of each XCD fetching every panel.  Any bijection is correct; this one is fast.
+constexpr int kXcds = 8, kTileBand = 8;
+__device__ __forceinline__ void xcd_tile(int w, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int total = tiles_m * tiles_n, per = total / kXcds, rem = total % kXcds;
+  const int xcd = w % kXcds;
+  const int t = xcd * per + (xcd < rem ? xcd : rem) + w / kXcds;
+  const int band = t / (kTileBand * tiles_n), first = band * kTileBand;
+  const int rows = tiles_m - first < kTileBand ? tiles_m - first : kTileBand;
+  const int r = t - band * kTileBand * tiles_n;
+  tm = first + r % rows;
+  tn = r / rows;
+}
+
 // GELU(h) = h/2 (1 + erf(h / sqrt 2)) and its derivative Phi(h) + h phi(h).
 __device__ __forceinline__ float gelu_f(float h) { return 0.5f * h * (1.0f + erff(h * 0.70710678118654752f)); }
 __device__ __forceinline__ float gelu_grad_f(float h) {

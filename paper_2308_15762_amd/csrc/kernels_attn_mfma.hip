@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(AttnDev p) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[BKV * PITCH];
   __shared__ __attribute__((aligned(16))) bf16 Vs[BKV * PITCH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, h = blockIdx.x, n = blockIdx.y;
   const int H = p.heads * p.d;
   const size_t ld3 = (size_t)3 * H;
   const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_kernel(AttnDev p) {
   __shared__ float lse2[BQ];
   __shared__ float dlt[BQ];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
-  const int kt = blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int kt = blockIdx.z, h = blockIdx.x, n = blockIdx.y;
   const int H = p.heads * p.d;
   const size_t ld3 = (size_t)3 * H;
   const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
@@ -307,7 +307,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnDev p) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[BKV * PITCH];
   __shared__ __attribute__((aligned(16))) bf16 Vs[BKV * PITCH];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, half = lane >> 5;
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, h = blockIdx.x, n = blockIdx.y;
   const int H = p.heads * p.d;
   const size_t ld3 = (size_t)3 * H;
   const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
@@ -492,7 +492,7 @@ __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
   typename Tile::Offsets fo;
   Tile::init(fo, lane);
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, h = blockIdx.x, n = blockIdx.y;
   const int H = p.heads * p.d, ld3 = 3 * H;
   const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
   const int len = seq_len(p, n);
@@ -608,7 +608,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
   typename Tile::Offsets fo;
   Tile::init(fo, lane);
-  const int kt = blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int kt = blockIdx.z, h = blockIdx.x, n = blockIdx.y;
   const int H = p.heads * p.d, ld3 = 3 * H;
   const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
   const bf16* dcb = p.dctx + (size_t)n * p.s * H + h * p.d;
@@ -725,7 +725,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
   typename Tile::Offsets fo;
   Tile::init(fo, lane);
-  const int qt = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, h = blockIdx.x, n = blockIdx.y;
   const int H = p.heads * p.d, ld3 = 3 * H;
   const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
   const int len = seq_len(p, n);
@@ -829,12 +829,16 @@ AttnDev to_dev(const AttnArgs& a) {
 
 }  // namespace
 
-bool attn_mfma_supported(const AttnArgs& a) { return a.d % 8 == 0 && a.d >= 8 && a.d <= 128; }
+// Grid = (head, sequence, 128-row tile).  Workgroup ids run head-fastest and the dispatcher deals them to
+// the 8 XCDs in turn, so with a multiple of 8 (sequence, head) pairs every tile of a pair lands on one
+// XCD and K and V are fetched into one L2 only; the tile index is slowest and the kernels count it from
+// the causal mask's heavy end, so the long tiles start first and the short ones fill in behind them.
+bool attn_mfma_supported(const AttnArgs& a) { return a.d % 8 == 0 && a.d >= 8 && a.d <= 128 && a.b <= 65535; }
 
 int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
   if (!attn_mfma_supported(a)) return set_error(HANAYO_EUNSUPPORTED, "attn_mfma: head dim %d", a.d);
   const AttnDev p = to_dev(a);
-  const dim3 grid((a.s + 127) / 128, a.heads, a.b), block(256);
+  const dim3 grid(a.heads, a.b, (a.s + 127) / 128), block(256);
   if (dma_ok(a)) {
     if (a.d == 64) {
       constexpr size_t lds = 3 * 2 * SwTile<64>::kBytes;
@@ -856,7 +860,7 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
   int rc = attn_delta(HANAYO_BF16, a, stream);
   if (rc) return rc;
   const AttnDev p = to_dev(a);
-  const dim3 grid((a.s + 127) / 128, a.heads, a.b), block(256);
+  const dim3 grid(a.heads, a.b, (a.s + 127) / 128), block(256);
   if (dma_ok(a)) {
     if (a.d == 64) {
       hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<64, 3>), grid, block, 3 * (2 * SwTile<64>::kBytes + 512), stream, p);

@@ -159,7 +159,12 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int khalf = wave / NSP;  // MODE 2: which MFMA step of a K tile this wavefront owns
   const int wm = (wave % NSP) / WGN, wn = (wave % NSP) % WGN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int tiles_m = p.M / BM, tiles_n = p.N / BN;
+  int tile_m, tile_n;
+  xcd_tile(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  tile_m = __builtin_amdgcn_readfirstlane(tile_m);
+  tile_n = __builtin_amdgcn_readfirstlane(tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
   const int nk = p.K / kBK;
 
   // Direct loads of one K tile.  The wavefront's i-th instruction for an operand covers the 64
@@ -245,11 +250,11 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   // column of the grid, each thread adds 4 columns x (32 / kColRowGroups) rows of a tile it owns.
   constexpr int kColGroups = BN / 4, kColRowGroups = NW * 64 / kColGroups, kColRows = kBK / kColRowGroups;
   float csum[4] = {0.f, 0.f, 0.f, 0.f};
-  int colsum_next = p.colsum ? (int)blockIdx.y : 0x7fffffff;  // next K tile this workgroup sums
+  int colsum_next = p.colsum ? tile_m : 0x7fffffff;  // next K tile this workgroup sums
   auto colsum_tile = [&](int kt) {
     if constexpr (B_T) {
       if (kt == colsum_next) {
-        colsum_next += (int)gridDim.y;
+        colsum_next += tiles_m;
         const char* b_lds = smem + (kt % NSTAGE) * STAGE_BYTES + OpA::kBytes;
         const int c = (threadIdx.x % kColGroups) * 4, rg = threadIdx.x / kColGroups;
 #pragma unroll
@@ -510,7 +515,7 @@ int launch(const DmaGemm& p, hipStream_t stream) {
     if (e != hipSuccess) return set_error(HANAYO_EHIP, "gemm_dma: cannot raise LDS limit: %s", hipGetErrorString(e));
     raised = true;
   }
-  const dim3 grid(p.N / BN, p.M / BM);
+  const dim3 grid((p.N / BN) * (p.M / BM));
   hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, p);
   return check_launch("gemm_dma");
 }
