@@ -74,14 +74,14 @@ int linear_bwd_input(const Shape& sh, const void* dy, const void* W, void* dx, i
 }
 
 // dW[K][N] += x[T][K]^T dy[T][N];  db[N] += column sums of dy
-int linear_bwd_params(const Shape& sh, const void* x, const void* dy, float* dW, float* db, int K, int N, float* partial,
-                      hipStream_t st) {
+k::GemmArgs bwd_params_gemm(const Shape& sh, const void* x, const void* dy, float* dW, float* db, int K, int N,
+                            float* partial) {
   k::GemmArgs g{};
   g.A = x; g.B = dy; g.C = dW;
   g.M = K; g.N = N; g.K = sh.T; g.lda = K; g.ldb = N; g.ldc = N;
   g.a_t = true; g.b_t = true; g.epi = k::EPI_ACCUM_F32;
   g.colsum = db; g.colsum_scratch = partial;  // bias gradient rides along with the weight gradient
-  return k::gemm(sh.dtype, g, st);
+  return g;
 }
 
 }  // namespace
@@ -93,36 +93,73 @@ int g_gemm_config = -1;
 }
 void set_gemm_config(int config) { g_gemm_config = config; }
 
+// Tile choice for the direct-to-LDS kernels by a cost model fitted to timings on MI355X: a launch
+// runs ceil(tiles / 256 CUs) rounds, each costing one K tile's time per 32 columns of K (0.88 us for
+// 256 x 256, 0.52 us for 256 x 128, 0.295 us for 128 x 128 with two workgroups sharing a CU), plus a
+// fixed start and epilogue cost.  Large tiles reuse operands better; small ones waste less of the
+// last round.  Returns -1 if no configuration takes every problem.
+int choose_dma_config(const GemmArgs* gs, int count) {
+  if (g_gemm_config >= 0 && g_gemm_config != 3) {
+    for (int i = 0; i < count; ++i)
+      if (!gemm_dma_supported(gs[i], g_gemm_config)) return -1;
+    return g_gemm_config;
+  }
+  if (g_gemm_config != -1) return -1;
+  static const struct { int config; double per_ktile, fixed; } kTiles[] = {{0, 0.88, 10.0}, {2, 0.52, 8.0}, {4, 0.295, 5.0}};
+  int best = -1;
+  double best_cost = 0.0;
+  for (const auto& t : kTiles) {
+    int bm, bn;
+    gemm_dma_tile(t.config, bm, bn);
+    long tiles = 0;
+    double ktiles = 0.0;  // summed over all tiles
+    bool ok = true;
+    for (int i = 0; i < count && ok; ++i) {
+      ok = gemm_dma_supported(gs[i], t.config);
+      const long ti = (long)(gs[i].M / bm) * (gs[i].N / bn);
+      tiles += ti;
+      ktiles += (double)ti * (gs[i].K / 32);
+    }
+    if (!ok || tiles == 0) continue;
+    const double cost = t.fixed + (double)((tiles + 255) / 256) * (ktiles / tiles) * t.per_ktile;
+    if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
+  }
+  return best;
+}
+
 int gemm(int dtype, const GemmArgs& g, hipStream_t stream) {
   if (g.M < 1 || g.N < 1 || g.K < 1) return set_error(HANAYO_EINVAL, "gemm: empty problem");
   if (g.colsum && (!g.b_t || !g.colsum_scratch)) return set_error(HANAYO_EINVAL, "gemm: colsum needs b_t and scratch");
   if (dtype == HANAYO_BF16) {
     // the direct-to-LDS kernels fold the column sums into the GEMM
-    if (g_gemm_config >= 0 && g_gemm_config != 3 && gemm_dma_supported(g, g_gemm_config))
-      return gemm_dma(g, g_gemm_config, stream);
-    if (g_gemm_config == -1) {
-      // Pick the tile by a cost model fitted to timings on MI355X: a launch runs ceil(tiles / 256 CUs)
-      // rounds, each costing one K tile's time per 32 columns of K (0.88 us for 256 x 256, 0.52 us for
-      // 256 x 128, 0.295 us for 128 x 128 with two workgroups sharing a CU), plus a fixed start and
-      // epilogue cost.  Large tiles reuse operands better; small ones waste less of the last round.
-      static const struct { int config, bm, bn; double per_ktile, fixed; } kTiles[] = {
-          {0, 256, 256, 0.88, 10.0}, {2, 256, 128, 0.52, 8.0}, {4, 128, 128, 0.295, 5.0}};
-      int best = -1;
-      double best_cost = 0.0;
-      for (const auto& t : kTiles) {
-        if (!gemm_dma_supported(g, t.config)) continue;
-        const long tiles = (long)(g.M / t.bm) * (g.N / t.bn);
-        const double cost = t.fixed + (double)((tiles + 255) / 256) * (g.K / 32) * t.per_ktile;
-        if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
-      }
-      if (best >= 0) return gemm_dma(g, best, stream);
-    }
+    const int config = choose_dma_config(&g, 1);
+    if (config >= 0) return gemm_dma(g, config, stream);
   }
   int rc;
   if (dtype == HANAYO_BF16 && gemm_mfma_supported(g)) rc = gemm_mfma(g, stream);
   else rc = gemm_alu(dtype, g, stream);
   if (rc || !g.colsum) return rc;
   return colsum_add(dtype, g.B, g.K, g.N, g.colsum, g.colsum_scratch, stream);  // B is stored [K][ldb = N]
+}
+
+int gemm_group(int dtype, const GemmArgs* gs, int count, hipStream_t stream) {
+  if (count < 1 || count > 4) return set_error(HANAYO_EINVAL, "gemm_group: %d problems", count);
+  bool alike = dtype == HANAYO_BF16;
+  for (int i = 0; i < count; ++i) {
+    const GemmArgs& g = gs[i];
+    if (g.M < 1 || g.N < 1 || g.K < 1) return set_error(HANAYO_EINVAL, "gemm: empty problem");
+    if (g.colsum && (!g.b_t || !g.colsum_scratch)) return set_error(HANAYO_EINVAL, "gemm: colsum needs b_t and scratch");
+    alike = alike && g.a_t == gs[0].a_t && g.b_t == gs[0].b_t && g.epi == gs[0].epi;
+  }
+  if (alike) {
+    const int config = choose_dma_config(gs, count);
+    if (config >= 0) return gemm_dma_group(gs, count, config, stream);
+  }
+  for (int i = 0; i < count; ++i) {
+    const int rc = gemm(dtype, gs[i], stream);
+    if (rc) return rc;
+  }
+  return HANAYO_OK;
 }
 
 int attn_forward(int dtype, const AttnArgs& a, hipStream_t stream) {
@@ -188,6 +225,9 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
   float* partial = reinterpret_cast<float*>(ws + WL.partial);
   const void* dy_blk = dy;
   for (int blk = sh.nb - 1; blk >= 0; --blk) {
+    // The four weight-gradient GEMMs of a block wait until its end and go out as one group: every
+    // activation and gradient they read stays untouched until then.
+    k::GemmArgs dw[4];
     const char* sb = static_cast<const char*>(stash) + (size_t)blk * L.block_bytes;
     const BlockPtrs p = block_ptrs(sh, po, weights, grads, blk);
     // gradient w.r.t. this block's input: the caller's dx for block 0, else a ping-pong buffer
@@ -199,19 +239,19 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
     at.b = sh.b; at.s = sh.s; at.heads = sh.heads; at.d = sh.d; at.causal = sh.mask == HANAYO_MASK_CAUSAL;
     if (sh.norm == HANAYO_PRE_LN) {
       // y = x1 + W2 GELU(W1 LN2(x1))
-      TRY(linear_bwd_params(sh, sb + L.act, dy_blk, p.g[P_W2], p.g[P_B2], F, H, partial, st));
+      dw[0] = bwd_params_gemm(sh, sb + L.act, dy_blk, p.g[P_W2], p.g[P_B2], F, H, partial);
       TRY(linear_bwd_input(sh, dy_blk, p.w[P_W2], ws + WL.d_act, F, H, k::EPI_MUL_DGELU, sb + L.hpre, st));
-      TRY(linear_bwd_params(sh, sb + L.ln_b, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial, st));
+      dw[1] = bwd_params_gemm(sh, sb + L.ln_b, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_act, p.w[P_W1], ws + WL.d_h0, H, F, k::EPI_NONE, nullptr, st));
       // dx1 = dy + LN2'(d_h0)
       TRY(k::ln_backward(sh.dtype, ws + WL.d_h0, sb + L.x1, p.w[P_LN2G], reinterpret_cast<const float2*>(sb + L.stats2),
                          dy_blk, ws + WL.d_h1, p.g[P_LN2G], p.g[P_LN2B], partial, T, H, st));
       // x1 = x + Wo ctx
-      TRY(linear_bwd_params(sh, sb + L.ctx, ws + WL.d_h1, p.g[P_WO], p.g[P_BO], H, H, partial, st));
+      dw[2] = bwd_params_gemm(sh, sb + L.ctx, ws + WL.d_h1, p.g[P_WO], p.g[P_BO], H, H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_h1, p.w[P_WO], ws + WL.d_h0, H, H, k::EPI_NONE, nullptr, st));
       at.dctx = ws + WL.d_h0;
       TRY(k::attn_backward(sh.dtype, at, st));
-      TRY(linear_bwd_params(sh, sb + L.ln_a, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial, st));
+      dw[3] = bwd_params_gemm(sh, sb + L.ln_a, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_qkv, p.w[P_WQKV], ws + WL.d_h2, H, 3 * H, k::EPI_NONE, nullptr, st));
       // dx = dx1 + LN1'(d_h2)
       TRY(k::ln_backward(sh.dtype, ws + WL.d_h2, sb + L.x, p.w[P_LN1G], reinterpret_cast<const float2*>(sb + L.stats1),
@@ -220,22 +260,23 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
       // y = LN2(f), f = x1 + W2 GELU(W1 x1)
       TRY(k::ln_backward(sh.dtype, dy_blk, sb + L.ln_b, p.w[P_LN2G], reinterpret_cast<const float2*>(sb + L.stats2),
                          nullptr, ws + WL.d_h0, p.g[P_LN2G], p.g[P_LN2B], partial, T, H, st));
-      TRY(linear_bwd_params(sh, sb + L.act, ws + WL.d_h0, p.g[P_W2], p.g[P_B2], F, H, partial, st));
+      dw[0] = bwd_params_gemm(sh, sb + L.act, ws + WL.d_h0, p.g[P_W2], p.g[P_B2], F, H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_h0, p.w[P_W2], ws + WL.d_act, F, H, k::EPI_MUL_DGELU, sb + L.hpre, st));
-      TRY(linear_bwd_params(sh, sb + L.x1, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial, st));
+      dw[1] = bwd_params_gemm(sh, sb + L.x1, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial);
       // dx1 = df + d_act W1^T
       TRY(linear_bwd_input(sh, ws + WL.d_act, p.w[P_W1], ws + WL.d_h1, H, F, k::EPI_ADD, ws + WL.d_h0, st));
       // x1 = LN1(a), a = x + Wo ctx
       TRY(k::ln_backward(sh.dtype, ws + WL.d_h1, sb + L.ln_a, p.w[P_LN1G], reinterpret_cast<const float2*>(sb + L.stats1),
                          nullptr, ws + WL.d_h2, p.g[P_LN1G], p.g[P_LN1B], partial, T, H, st));
-      TRY(linear_bwd_params(sh, sb + L.ctx, ws + WL.d_h2, p.g[P_WO], p.g[P_BO], H, H, partial, st));
-      TRY(linear_bwd_input(sh, ws + WL.d_h2, p.w[P_WO], ws + WL.d_h0, H, H, k::EPI_NONE, nullptr, st));
-      at.dctx = ws + WL.d_h0;
+      dw[2] = bwd_params_gemm(sh, sb + L.ctx, ws + WL.d_h2, p.g[P_WO], p.g[P_BO], H, H, partial);
+      TRY(linear_bwd_input(sh, ws + WL.d_h2, p.w[P_WO], ws + WL.d_h3, H, H, k::EPI_NONE, nullptr, st));
+      at.dctx = ws + WL.d_h3;  // d_h0 still feeds the W2 gradient
       TRY(k::attn_backward(sh.dtype, at, st));
-      TRY(linear_bwd_params(sh, sb + L.x, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial, st));
+      dw[3] = bwd_params_gemm(sh, sb + L.x, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial);
       // dx = da + dqkv Wqkv^T
       TRY(linear_bwd_input(sh, ws + WL.d_qkv, p.w[P_WQKV], dx_blk, H, 3 * H, k::EPI_ADD, ws + WL.d_h2, st));
     }
+    TRY(k::gemm_group(sh.dtype, dw, 4, st));
     dy_blk = dx_blk;
   }
   return HANAYO_OK;

@@ -65,6 +65,7 @@ struct WorkLayout {
   size_t d_h0;     // [T][H]  scratch gradient tensors
   size_t d_h1;     // [T][H]
   size_t d_h2;     // [T][H]
+  size_t d_h3;     // [T][H]
   size_t d_qkv;    // [T][3H]
   size_t d_ping;   // [T][H]  dy hand-off between blocks
   size_t d_pong;   // [T][H]

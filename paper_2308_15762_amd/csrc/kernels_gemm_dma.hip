@@ -42,6 +42,16 @@ struct DmaGemm {
   float* colsum;  // see GemmArgs; folded into the kernel (B_T only)
 };
 
+// One launch covers up to kMaxGroup independent problems of one layout and epilogue: workgroups
+// first[i] .. first[i + 1] - 1 are the tiles of problem i.  Four weight-gradient GEMMs of a block,
+// none of which fills the chip alone, share one grid this way.
+constexpr int kMaxGroup = 4;
+struct DmaGemmGroup {
+  DmaGemm prob[kMaxGroup];
+  int first[kMaxGroup + 1];
+  int count;
+};
+
 constexpr int kBK = 32;
 
 // One wavefront-wide 16-byte-per-lane load from global memory into LDS: lane L's
@@ -140,7 +150,13 @@ __device__ __forceinline__ bf16x8 frag_t(const char* lds, int c0, int kk, int la
 //         A SIMD then holds two wavefronts that fill each other's stalls, and twice as many
 //         wavefronts issue LDS reads (the per-wavefront LDS request rate limits the 4-wavefront form).
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE, bool A_T, bool B_T, int EPI>
-__global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_kernel(DmaGemm p) {
+__global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_kernel(DmaGemmGroup grp) {
+  int gi = 0;
+#pragma unroll
+  for (int j = 1; j < kMaxGroup; ++j)
+    if (j < grp.count && (int)blockIdx.x >= grp.first[j]) gi = j;
+  const DmaGemm p = grp.prob[gi];
+  const int wg = (int)blockIdx.x - grp.first[gi];  // tile number within the problem
   constexpr bool FDEEP = MODE >= 1;
   constexpr int NSP = WGM * WGN;                 // wavefronts that tile the output
   constexpr int NW = NSP * (MODE == 2 ? 2 : 1);  // wavefronts in the workgroup
@@ -161,7 +177,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   const int wm = (wave % NSP) / WGN, wn = (wave % NSP) % WGN;
   const int tiles_m = p.M / BM, tiles_n = p.N / BN;
   int tile_m, tile_n;
-  xcd_tile(blockIdx.x, tiles_m, tiles_n, tile_m, tile_n);
+  xcd_tile(wg, tiles_m, tiles_n, tile_m, tile_n);
   tile_m = __builtin_amdgcn_readfirstlane(tile_m);
   tile_n = __builtin_amdgcn_readfirstlane(tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
@@ -502,7 +518,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
 }
 
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE, bool A_T, bool B_T, int EPI>
-int launch(const DmaGemm& p, hipStream_t stream) {
+int launch(DmaGemmGroup& grp, hipStream_t stream) {
   constexpr int NW = WGM * WGN * (MODE == 2 ? 2 : 1);
   using OpA = Operand<BM, A_T, NW>;
   using OpB = Operand<BN, B_T, NW>;
@@ -515,29 +531,35 @@ int launch(const DmaGemm& p, hipStream_t stream) {
     if (e != hipSuccess) return set_error(HANAYO_EHIP, "gemm_dma: cannot raise LDS limit: %s", hipGetErrorString(e));
     raised = true;
   }
-  const dim3 grid((p.N / BN) * (p.M / BM));
-  hipLaunchKernelGGL(kern, grid, dim3(NW * 64), lds, stream, p);
+  long tiles = 0;
+  for (int i = 0; i < grp.count; ++i) {
+    grp.first[i] = (int)tiles;
+    tiles += (long)(grp.prob[i].N / BN) * (grp.prob[i].M / BM);
+  }
+  for (int i = grp.count; i <= kMaxGroup; ++i) grp.first[i] = (int)tiles;
+  if (tiles > 0x7fffffffL) return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: too many tiles");
+  hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(NW * 64), lds, stream, grp);
   return check_launch("gemm_dma");
 }
 
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE>
-int launch_layout(const GemmArgs& g, const DmaGemm& p, hipStream_t stream) {
+int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
   if (!g.a_t && g.b_t) {
     switch (g.epi) {
-      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS>(p, stream);
-      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_GELU>(p, stream);
-      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_RES>(p, stream);
+      case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS>(grp, stream);
+      case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_GELU>(grp, stream);
+      case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_RES>(grp, stream);
       default: break;
     }
   } else if (!g.a_t && !g.b_t) {
     switch (g.epi) {
-      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_NONE>(p, stream);
-      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_MUL_DGELU>(p, stream);
-      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_ADD>(p, stream);
+      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_NONE>(grp, stream);
+      case EPI_MUL_DGELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_MUL_DGELU>(grp, stream);
+      case EPI_ADD: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, false, EPI_ADD>(grp, stream);
       default: break;
     }
   } else if (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32) {
-    return launch<BM, BN, WGM, WGN, NSTAGE, MODE, true, true, EPI_ACCUM_F32>(p, stream);
+    return launch<BM, BN, WGM, WGN, NSTAGE, MODE, true, true, EPI_ACCUM_F32>(grp, stream);
   }
   return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: layout/epilogue combination not built");
 }
@@ -545,33 +567,51 @@ int launch_layout(const GemmArgs& g, const DmaGemm& p, hipStream_t stream) {
 }  // namespace
 
 // Tile configurations: 0 = 256 x 256, 1 = 128 x 128 with an 8-deep buffer ring, 2 = 256 x 128,
-// 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU).  All use 4 wavefronts.
+// 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU), 5 = as 4 with 8 wavefronts that split
+// the MFMA steps of a K tile.  The others use 4 wavefronts.
+void gemm_dma_tile(int config, int& bm, int& bn) {
+  bm = (config == 1 || config == 4 || config == 5) ? 128 : 256;
+  bn = config == 0 ? 256 : 128;
+}
+
 bool gemm_dma_supported(const GemmArgs& g, int config) {
   const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
                      (!g.a_t && !g.b_t && (g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD)) ||
                      (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32);
-  const int bm = (config == 1 || config == 4 || config == 5) ? 128 : 256, bn = config == 0 ? 256 : 128;
+  int bm, bn;
+  gemm_dma_tile(config, bm, bn);
   // lane offsets are 32-bit byte offsets from the tile origin
   const long span_a = (long)(g.a_t ? kBK : bm) * g.lda * 2, span_b = (long)(g.b_t ? kBK : bn) * g.ldb * 2;
   return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % kBK == 0 && g.K >= kBK && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
          g.ldc % 4 == 0 && span_a < (1L << 31) && span_b < (1L << 31);
 }
 
-int gemm_dma(const GemmArgs& g, int config, hipStream_t stream) {
-  if (!gemm_dma_supported(g, config)) return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: shape not supported");
-  DmaGemm p;
-  p.A = (const bf16*)g.A; p.B = (const bf16*)g.B; p.C = (bf16*)g.C; p.Cf = (float*)g.C;
-  p.bias = (const bf16*)g.bias; p.aux = (const bf16*)g.aux; p.aux_out = (bf16*)g.aux_out;
-  p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
-  p.colsum = g.b_t ? g.colsum : nullptr;
+// The problems of a group share layout and epilogue (those of gs[0]); each must pass gemm_dma_supported.
+int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream) {
+  if (count < 1 || count > kMaxGroup) return set_error(HANAYO_EINVAL, "gemm_dma: group of %d", count);
+  DmaGemmGroup grp{};
+  grp.count = count;
+  for (int i = 0; i < count; ++i) {
+    const GemmArgs& g = gs[i];
+    if (!gemm_dma_supported(g, config) || g.a_t != gs[0].a_t || g.b_t != gs[0].b_t || g.epi != gs[0].epi)
+      return set_error(HANAYO_EUNSUPPORTED, "gemm_dma: shape not supported");
+    DmaGemm& p = grp.prob[i];
+    p.A = (const bf16*)g.A; p.B = (const bf16*)g.B; p.C = (bf16*)g.C; p.Cf = (float*)g.C;
+    p.bias = (const bf16*)g.bias; p.aux = (const bf16*)g.aux; p.aux_out = (bf16*)g.aux_out;
+    p.M = g.M; p.N = g.N; p.K = g.K; p.lda = g.lda; p.ldb = g.ldb; p.ldc = g.ldc;
+    p.colsum = g.b_t ? g.colsum : nullptr;
+  }
+  const GemmArgs& g = gs[0];
   switch (config) {
-    case 0: return launch_layout<256, 256, 2, 2, 4, 0>(g, p, stream);
-    case 1: return launch_layout<128, 128, 2, 2, 8, 1>(g, p, stream);  // 128 KiB LDS: one workgroup per CU
-    case 4: return launch_layout<128, 128, 2, 2, 4, 1>(g, p, stream);  // 64 KiB LDS: two per CU
-    case 5: return launch_layout<128, 128, 2, 2, 4, 2>(g, p, stream);  // 8 wavefronts, K steps split
-    default: return launch_layout<256, 128, 2, 2, 4, 0>(g, p, stream);
+    case 0: return launch_layout<256, 256, 2, 2, 4, 0>(g, grp, stream);
+    case 1: return launch_layout<128, 128, 2, 2, 8, 1>(g, grp, stream);  // 128 KiB LDS: one workgroup per CU
+    case 4: return launch_layout<128, 128, 2, 2, 4, 1>(g, grp, stream);  // 64 KiB LDS: two per CU
+    case 5: return launch_layout<128, 128, 2, 2, 4, 2>(g, grp, stream);
+    default: return launch_layout<256, 128, 2, 2, 4, 0>(g, grp, stream);
   }
 }
+
+int gemm_dma(const GemmArgs& g, int config, hipStream_t stream) { return gemm_dma_group(&g, 1, config, stream); }
 
 }  // namespace k
 }  // namespace hanayo

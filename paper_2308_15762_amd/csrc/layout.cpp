@@ -102,6 +102,7 @@ WorkLayout work_layout(const Shape& sh) {
   L.d_h0 = take(th);
   L.d_h1 = take(th);
   L.d_h2 = take(th);
+  L.d_h3 = take(th);
   L.d_qkv = take(3 * th);
   L.d_ping = take(th);
   L.d_pong = take(th);
