@@ -168,7 +168,8 @@ int hanayo_chunk_backward(const hanayo_chunk_desc* d, const void* weights, float
 
 /* ------------------------------------------------------------------------- *
  * Per-rank task executor (the worker-side interpreter of the runtime section,
- * compute actions only).  Runs `list` in order on one stream.  All chunks of
+ * compute actions only).  Runs `list` in order (on one stream unless lanes
+ * are asked for, see below).  All chunks of
  * the rank share one descriptor.  Tables are host arrays of device pointers
  * indexed [mb * 2W + chunk].
  *
@@ -196,8 +197,9 @@ typedef struct hanayo_exec_args {
   const int32_t* const* valid_len; /* host [M] -> device int32 [b], or NULL */
   void* stash_arena;               /* device */
   size_t stash_arena_bytes;        /* >= hanayo_stash_arena_bytes() */
-  void* workspace;                 /* device, hanayo_workspace_bytes() */
+  void* workspace;                 /* device, lanes * hanayo_workspace_bytes() */
   void* hip_stream;
+  int lanes;                       /* 0 or 1: everything on hip_stream; 2..4: see below */
 } hanayo_exec_args;
 
 /* Arena size the executor needs for `list`; 0 on error. */
@@ -210,6 +212,28 @@ size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const 
  * number of stash entries that were live at once.
  */
 int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_args* args, int* peak_seen);
+
+/*
+ * Lanes.  With args->lanes > 1 the executor spreads the list over that many HIP
+ * streams (lane 0 is hip_stream, the others belong to the library: default
+ * priority, created once per device and kept), so that tasks which do not
+ * depend on each other overlap on the GPU.  A task waits, through events, for
+ * the tasks hanayo_executor_plan lists for it; tasks of one lane run in list
+ * order; the side lanes start after the work hip_stream already holds and
+ * hip_stream ends after all of them, so the caller sees one ordered stream.
+ * Results equal those of one lane (a chunk's gradient accumulations keep their
+ * list order).  Calls with lanes > 1 on one device are serialised on the host.
+ *
+ * hanayo_executor_plan reports that plan without touching the GPU:
+ *   lane  host [n]     lane of each task
+ *   deps  host [n][4]  indices of earlier tasks that task i waits for, -1 = none:
+ *         [0] the local stage producing its input, [1] (B) its own forward,
+ *         [2] (F) the backward that last read the stash entry it overwrites,
+ *         [3] (B) the previous backward of the same chunk.
+ * Same list checks and error codes as hanayo_executor_run.
+ */
+int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int32_t* lane,
+                         int32_t* deps);
 
 
 /* ------------------------------------------------------------------------- *

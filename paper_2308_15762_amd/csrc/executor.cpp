@@ -1,11 +1,22 @@
 // Per-rank task executor: the worker-side interpreter of the paper's runtime
 // section, restricted to compute actions.  It validates the list against the
 // rank's task set and the local dependencies, plans the stash, then walks the
-// list once, enqueueing chunk_forward / chunk_backward on one stream.  Stage
-// boundaries are buffers in HBM; the turn-around between two stages that share
-// this rank is a pointer hand-off.
+// list once, enqueueing chunk_forward / chunk_backward.  Stage boundaries are
+// buffers in HBM; the turn-around between two stages that share this rank is a
+// pointer hand-off.
+//
+// With one lane everything goes to the caller's stream in list order.  With
+// more, tasks that do not depend on each other run side by side on HIP streams
+// of the library's own (lane 0 is the caller's stream): a GEMM's store-heavy
+// tail and the memory-bound kernels of one task then overlap another task's
+// MFMA work.  Every true dependency becomes an event wait, every task still
+// starts in list order on its lane, and the weight gradients of a chunk are
+// still accumulated in list order, so the results do not depend on the lane
+// count.
 #include <hip/hip_runtime.h>
 
+#include <array>
+#include <mutex>
 #include <vector>
 
 #include "internal.h"
@@ -41,6 +52,101 @@ int make_plan(const hanayo_task* list, size_t n, int W, Plan& pl) {
   pl.entries = at;
   return HANAYO_OK;
 }
+
+// What a task must wait for besides the tasks before it on its own lane.
+enum { DEP_INPUT, DEP_FORWARD, DEP_SLOT, DEP_GRADS, N_DEPS };
+struct LanePlan {
+  std::vector<int32_t> lane;
+  std::vector<std::array<int32_t, N_DEPS>> dep;  // task indices, -1 = none
+};
+
+// Dependencies of each task on earlier tasks of the list, and a lane for each by list scheduling
+// with the schedule's own cost model (forward 1, backward 2): a task goes to the lane on which it
+// can start first.
+//   DEP_INPUT    the local stage that produces its input activation / gradient
+//   DEP_FORWARD  (backward) its own forward, which filled the stash entry
+//   DEP_SLOT     (forward) the backward that last read the stash entry it is about to overwrite
+//   DEP_GRADS    (backward) the previous backward of the same chunk: one accumulation at a time
+void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, const Plan& pl,
+                LanePlan& lp) {
+  const int nchunk = 2 * W, S = 2 * W * P;
+  lp.lane.assign(n, 0);
+  lp.dep.assign(n, {-1, -1, -1, -1});
+  std::vector<int32_t> f_at((size_t)M * nchunk, -1), b_at((size_t)M * nchunk, -1), last_b(nchunk, -1);
+  std::vector<std::vector<int32_t>> slot_reader(nchunk);
+  for (int c = 0; c < nchunk; ++c) slot_reader[c].assign(pl.per_chunk[c], -1);
+  std::vector<double> done(n, 0.0), lane_free(lanes, 0.0);
+  for (size_t i = 0; i < n; ++i) {
+    const hanayo_task& tk = list[i];
+    const size_t at = (size_t)tk.mb * nchunk + tk.chunk;
+    const int stage = (int)tk.stage;
+    auto& d = lp.dep[i];
+    if (tk.kind == HANAYO_F) {
+      if (stage > 0 && stage_rank(P, stage - 1) == rank) d[DEP_INPUT] = f_at[at - 1];
+      d[DEP_SLOT] = slot_reader[tk.chunk][pl.slot[i]];
+      f_at[at] = (int32_t)i;
+    } else {
+      if (stage < S - 1 && stage_rank(P, stage + 1) == rank) d[DEP_INPUT] = b_at[at + 1];
+      d[DEP_FORWARD] = f_at[at];
+      d[DEP_GRADS] = last_b[tk.chunk];
+      b_at[at] = last_b[tk.chunk] = (int32_t)i;
+      slot_reader[tk.chunk][pl.slot[i]] = (int32_t)i;
+    }
+    double ready = 0.0;
+    for (int32_t j : d)
+      if (j >= 0 && done[j] > ready) ready = done[j];
+    int best = 0;
+    double best_start = 0.0;
+    for (int l = 0; l < lanes; ++l) {
+      const double start = lane_free[l] > ready ? lane_free[l] : ready;
+      if (l == 0 || start < best_start) best = l, best_start = start;
+    }
+    lp.lane[i] = best;
+    done[i] = lane_free[best] = best_start + (tk.kind == HANAYO_F ? 1.0 : 2.0);
+  }
+}
+
+// Side streams and events, made once per device and kept: default priority, non-blocking.
+constexpr int kMaxLanes = 4;
+struct LaneResources {
+  int device = -1;
+  hipStream_t side[kMaxLanes - 1] = {};
+  std::vector<hipEvent_t> events;
+};
+std::mutex g_lane_mutex;
+std::vector<LaneResources> g_lane_resources;
+
+int lane_resources(int lanes, size_t n_events, LaneResources** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return set_error(HANAYO_EHIP, "executor: hipGetDevice failed");
+  LaneResources* r = nullptr;
+  for (auto& x : g_lane_resources)
+    if (x.device == dev) r = &x;
+  if (!r) {
+    g_lane_resources.reserve(64);  // pointers handed out stay valid
+    if (g_lane_resources.size() == g_lane_resources.capacity()) return set_error(HANAYO_ESTATE, "executor: too many devices");
+    g_lane_resources.emplace_back();
+    r = &g_lane_resources.back();
+    r->device = dev;
+  }
+  for (int l = 0; l + 1 < lanes; ++l)
+    if (!r->side[l] && hipStreamCreateWithFlags(&r->side[l], hipStreamNonBlocking) != hipSuccess)
+      return set_error(HANAYO_EHIP, "executor: cannot create a stream: %s", hipGetErrorString(hipGetLastError()));
+  while (r->events.size() < n_events) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess)
+      return set_error(HANAYO_EHIP, "executor: cannot create an event: %s", hipGetErrorString(hipGetLastError()));
+    r->events.push_back(e);
+  }
+  *out = r;
+  return HANAYO_OK;
+}
+
+#define HIP_TRY(call)                                                                                  \
+  do {                                                                                                 \
+    const hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess) return set_error(HANAYO_EHIP, "executor: %s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
 
 // The list must hold exactly this rank's tasks, once each, in an order in which
 // every task's local predecessor has already run.
@@ -86,6 +192,25 @@ size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const 
   return pl.entries * (stash_layout(sh).block_bytes * sh.nb);
 }
 
+int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int32_t* lane,
+                         int32_t* deps) {
+  if (!list || !lane || !deps) return set_error(HANAYO_EINVAL, "executor_plan: NULL argument");
+  if (P < 1 || W < 1 || M < 1 || rank < 0 || rank >= P || 2 * W > 255 || lanes < 1 || lanes > kMaxLanes)
+    return set_error(HANAYO_EINVAL, "executor_plan: bad P=%d W=%d M=%d rank=%d lanes=%d", P, W, M, rank, lanes);
+  int rc = validate(list, n, P, W, M, rank);
+  if (rc) return rc;
+  Plan pl;
+  rc = make_plan(list, n, W, pl);
+  if (rc) return rc;
+  LanePlan lp;
+  plan_lanes(list, n, P, W, M, rank, lanes, pl, lp);
+  for (size_t i = 0; i < n; ++i) {
+    lane[i] = lp.lane[i];
+    for (int k = 0; k < N_DEPS; ++k) deps[i * N_DEPS + k] = lp.dep[i][k];
+  }
+  return HANAYO_OK;
+}
+
 int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_args* a, int* peak_seen) {
   if (!list || !a || !a->desc || !a->weights || !a->grads || !a->act_in || !a->grad_in || !a->act_out || !a->grad_out ||
       !a->stash_arena || !a->workspace)
@@ -122,13 +247,41 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
         return set_error(HANAYO_EINVAL, "executor: missing gradient buffer for mb %u chunk %d", tk.mb, tk.chunk);
     }
   }
-  hipStream_t st = static_cast<hipStream_t>(a->hip_stream);
+  const int lanes = a->lanes < 1 ? 1 : a->lanes;
+  if (lanes > kMaxLanes) return set_error(HANAYO_EINVAL, "executor: at most %d lanes", kMaxLanes);
+  LanePlan lp;
+  plan_lanes(list, n, P, W, M, rank, lanes, pl, lp);
+  // a task records an event if a task on another lane waits for it
+  std::vector<char> signals(n, 0);
+  for (size_t i = 0; i < n; ++i)
+    for (int32_t j : lp.dep[i])
+      if (j >= 0 && lp.lane[j] != lp.lane[i]) signals[j] = 1;
+
+  std::unique_lock<std::mutex> lock(g_lane_mutex, std::defer_lock);
+  hipStream_t stream[kMaxLanes] = {static_cast<hipStream_t>(a->hip_stream)};
+  LaneResources* res = nullptr;
+  if (lanes > 1) {
+    lock.lock();  // the side streams and events are shared by every call on this device
+    rc = lane_resources(lanes, n + kMaxLanes, &res);
+    if (rc) return rc;
+    // fork: the side lanes start after whatever the caller's stream holds so far
+    HIP_TRY(hipEventRecord(res->events[n], stream[0]));
+    for (int l = 1; l < lanes; ++l) {
+      stream[l] = res->side[l - 1];
+      HIP_TRY(hipStreamWaitEvent(stream[l], res->events[n], 0));
+    }
+  }
+  const size_t work_bytes = work_layout(sh).bytes;
   char* arena = static_cast<char*>(a->stash_arena);
   int live = 0, peak = 0;
   for (size_t i = 0; i < n; ++i) {
     const hanayo_task& tk = list[i];
     const size_t at = (size_t)tk.mb * nchunk + tk.chunk;
     const int stage = (int)tk.stage;
+    const int lane = lp.lane[i];
+    hipStream_t st = stream[lane];
+    for (int32_t j : lp.dep[i])
+      if (j >= 0 && lp.lane[j] != lane) HIP_TRY(hipStreamWaitEvent(st, res->events[j], 0));
     void* entry = arena + (pl.chunk_base[tk.chunk] + (size_t)pl.slot[i]) * entry_bytes;
     const int32_t* vl = a->valid_len ? a->valid_len[tk.mb] : nullptr;
     if (tk.kind == HANAYO_F) {
@@ -139,11 +292,19 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     } else {
       const bool local = stage < S - 1 && stage_rank(P, stage + 1) == rank;
       const void* dy = local ? a->grad_out[at + 1] : a->grad_in[at];
-      rc = chunk_backward(sh, a->weights[tk.chunk], a->grads[tk.chunk], dy, vl, entry, a->grad_out[at], a->workspace, st);
+      void* work = static_cast<char*>(a->workspace) + (size_t)lane * work_bytes;  // one workspace per lane
+      rc = chunk_backward(sh, a->weights[tk.chunk], a->grads[tk.chunk], dy, vl, entry, a->grad_out[at], work, st);
       --live;
     }
-    if (rc) return rc;
+    if (rc) break;
+    if (signals[i]) HIP_TRY(hipEventRecord(res->events[i], st));
   }
+  // join, also after a failed enqueue: the caller's stream ends after every side lane
+  for (int l = 1; l < lanes; ++l) {
+    HIP_TRY(hipEventRecord(res->events[n + l], stream[l]));
+    HIP_TRY(hipStreamWaitEvent(stream[0], res->events[n + l], 0));
+  }
+  if (rc) return rc;
   if (peak_seen) *peak_seen = peak;
   return HANAYO_OK;
 }

@@ -49,7 +49,7 @@ class ExecArgs(ctypes.Structure):
                 ("act_out", ctypes.POINTER(ctypes.c_void_p)), ("grad_out", ctypes.POINTER(ctypes.c_void_p)),
                 ("valid_len", ctypes.POINTER(ctypes.c_void_p)),
                 ("stash_arena", ctypes.c_void_p), ("stash_arena_bytes", ctypes.c_size_t),
-                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p)]
+                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p), ("lanes", ctypes.c_int)]
 
 
 class HanayoError(RuntimeError):
@@ -62,7 +62,7 @@ class HanayoError(RuntimeError):
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
-           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_device_info",
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_device_info",
            "hanayo_op_gemm", "hanayo_op_gemm_config", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
@@ -86,6 +86,7 @@ _lib.hanayo_chunk_backward.argtypes = [_descp, _vp, _vp, _vp, _vp, _vp, _vp, _vp
 _lib.hanayo_stash_arena_bytes.restype = _sz
 _lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
+_lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
 _lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_op_gemm_config.argtypes = [_int]
@@ -265,15 +266,25 @@ def _table(items):
     return arr
 
 
+def hanayo_executor_plan(tasks, P, W, M, rank, lanes):
+    """(lane [n], deps [n][4]) of the executor's lane plan; host only."""
+    tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
+    lane = np.zeros(tasks.size, dtype=np.int32)
+    deps = np.zeros((tasks.size, 4), dtype=np.int32)
+    _check(_lib.hanayo_executor_plan(tasks.ctypes.data, tasks.size, P, W, M, rank, lanes, lane.ctypes.data,
+                                     deps.ctypes.data))
+    return lane, deps
+
+
 def hanayo_executor_run(tasks, desc, P, W, M, rank, weights, grads, act_in, grad_in, act_out, grad_out,
-                        valid_len, stash_arena, stash_arena_bytes, workspace, stream=None):
+                        valid_len, stash_arena, stash_arena_bytes, workspace, stream=None, lanes=1):
     """Tables are Python lists of tensors / None: weights, grads [2W]; act_*, grad_* [M*2W]
     indexed mb*2W+chunk; valid_len [M] or None.  Returns the stash peak seen."""
     tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
     tabs = [_table(t) for t in (weights, grads, act_in, grad_in, act_out, grad_out)]
     vl = _table(valid_len) if valid_len is not None else None
     args = ExecArgs(ctypes.pointer(desc), P, W, M, rank, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5],
-                    vl, _ptr(stash_arena), stash_arena_bytes, _ptr(workspace), stream)
+                    vl, _ptr(stash_arena), stash_arena_bytes, _ptr(workspace), stream, lanes)
     peak = _int()
     _check(_lib.hanayo_executor_run(tasks.ctypes.data, tasks.size, ctypes.byref(args), ctypes.byref(peak)))
     return peak.value

@@ -29,16 +29,28 @@ CASES = {
 }
 
 
+_ORACLE = {}
+
+
+def oracle_of(name, tasks):
+    """The oracle's run of a case, computed once per session."""
+    if name not in _ORACLE:
+        wl, rank = CASES[name]
+        _ORACLE[name] = oracle_rank(wl, rank, tasks)
+    return _ORACLE[name]
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 3])
 @pytest.mark.parametrize("name", list(CASES))
-def test_rank_list_matches_oracle(name):
+def test_rank_list_matches_oracle(name, lanes):
     wl, rank = CASES[name]
     tol = TOL[wl.dtype]
-    gpu = GpuRank(wl, rank)
+    gpu = GpuRank(wl, rank, lanes=lanes)
     plan_peak, per_chunk, _ = hn.hanayo_stash_plan(gpu.tasks, wl.W)
     peak = gpu.run()
     torch.cuda.synchronize()
     assert peak == plan_peak == OS.stash_plan(OS.schedule(wl.P, wl.W, wl.M, rank), wl.W)[0]
-    ref = oracle_rank(wl, rank, gpu.tasks)
+    ref = oracle_of(name, gpu.tasks)
     assert ref["peak"] == peak
     nchunk = 2 * wl.W
     worst = 0.0
@@ -67,6 +79,35 @@ def test_second_run_after_zeroing_grads_is_identical_enough():
     assert torch.equal(out_first, gpu.act_out[-1])
     for a, b in zip(first, gpu.grads):
         assert nerr(b.cpu().numpy(), a.cpu().numpy()) <= 1e-5
+
+
+@pytest.mark.parametrize("name", ["gpt_1024_sched_small", "wave4_sched_small_rank3"])
+def test_lanes_do_not_change_results(name):
+    """Boundary outputs are bit-identical whatever the lane count; gradients differ only by the
+    order of the bias-gradient atomics."""
+    wl, rank = CASES[name]
+    runs = []
+    for lanes in (1, 2, 4):
+        gpu = GpuRank(wl, rank, lanes=lanes)
+        for _ in range(2):  # the second run reuses events and side streams
+            gpu.zero_grads()
+            gpu.run()
+        torch.cuda.synchronize()
+        runs.append(gpu)
+    for other in runs[1:]:
+        for a, b in zip(runs[0].act_out + runs[0].grad_out, other.act_out + other.grad_out):
+            assert torch.equal(a, b)
+        for a, b in zip(runs[0].grads, other.grads):
+            assert nerr(b.cpu().numpy(), a.cpu().numpy()) <= 1e-5
+
+
+def test_executor_rejects_too_many_lanes():
+    wl, rank = CASES["gpt_1024_sched_small"]
+    gpu = GpuRank(wl, rank, lanes=4)
+    gpu.lanes = 5
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run()
+    assert e.value.code == hn.EINVAL
 
 
 def test_executor_rejects_bad_lists_without_touching_outputs():

@@ -88,3 +88,71 @@ def test_arena_size_follows_the_plan():
     t = hn.hanayo_schedule(4, 2, 8, 0)
     _, per_chunk, _ = hn.hanayo_stash_plan(t, 2)
     assert hn.hanayo_stash_arena_bytes(t, 2, d) == int(per_chunk.sum()) * hn.hanayo_stash_bytes(d)
+
+
+# ---------------------------------------------------------------- executor lane plan
+
+def _accesses(P, W, rank, tasks, slot, lane):
+    """Read and write sets of every task over the buffers the executor touches."""
+    S_ = 2 * W * P
+    out = []
+    for i, t in enumerate(tasks):
+        kind, m, c, stage = (int(t[k]) for k in ("kind", "mb", "chunk", "stage"))
+        reads, writes = set(), set()
+        if kind == 0:
+            if stage > 0 and S.stage_rank(P, W, stage - 1) == rank:
+                reads.add(("act", m, c - 1))
+            writes.add(("act", m, c))
+            writes.add(("stash", c, int(slot[i])))
+        else:
+            reads.add(("stash", c, int(slot[i])))
+            if stage < S_ - 1 and S.stage_rank(P, W, stage + 1) == rank:
+                reads.add(("grad", m, c + 1))
+            writes.add(("grad", m, c))
+            writes.add(("weight grads", c))          # read-modify-write
+            writes.add(("workspace", int(lane[i])))
+        out.append((reads, writes))
+    return out
+
+
+@pytest.mark.parametrize("lanes", [1, 2, 3, 4])
+@pytest.mark.parametrize("P,W,M", [(2, 1, 4), (4, 2, 8), (4, 1, 16), (8, 4, 12), (3, 2, 5), (1, 2, 3), (5, 3, 2)])
+def test_lane_plan_orders_every_conflict(P, W, M, lanes):
+    """Any two tasks that touch one buffer, at least one of them writing, are ordered by the plan's
+    event waits together with the in-order execution of each lane."""
+    for rank in range(P):
+        tasks = hn.hanayo_schedule(P, W, M, rank)
+        n = len(tasks)
+        lane, deps = hn.hanayo_executor_plan(tasks, P, W, M, rank, lanes)
+        assert lane.min() >= 0 and lane.max() < lanes
+        _, _, slot = S.stash_plan(S.schedule(P, W, M, rank), W)
+        acc = _accesses(P, W, rank, tasks, slot, lane)
+        before = [0] * n           # bit j set: task j is known to finish before task i starts
+        last_on_lane = {}
+        for i in range(n):
+            preds = [int(j) for j in deps[i] if j >= 0]
+            assert all(j < i for j in preds)
+            if int(lane[i]) in last_on_lane:
+                preds.append(last_on_lane[int(lane[i])])
+            last_on_lane[int(lane[i])] = i
+            for j in preds:
+                before[i] |= before[j] | (1 << j)
+        for i in range(n):
+            ri, wi = acc[i]
+            for j in range(i):
+                rj, wj = acc[j]
+                if (wj & (ri | wi)) or (rj & wi):
+                    assert before[i] >> j & 1, "tasks %d and %d share %s unordered" % (j, i, (wj & (ri | wi)) | (rj & wi))
+        if lanes > 1 and P >= 2 and M >= 4:
+            assert len(set(lane.tolist())) > 1   # the plan does use more than one lane
+
+
+def test_lane_plan_rejects_bad_arguments():
+    tasks = hn.hanayo_schedule(2, 1, 4, 0)
+    for lanes in (0, 5):
+        with pytest.raises(hn.HanayoError) as e:
+            hn.hanayo_executor_plan(tasks, 2, 1, 4, 0, lanes)
+        assert e.value.code == hn.EINVAL
+    with pytest.raises(hn.HanayoError) as e:
+        hn.hanayo_executor_plan(tasks[::-1].copy(), 2, 1, 4, 0, 2)
+    assert e.value.code == hn.ESTATE
