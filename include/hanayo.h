@@ -268,6 +268,37 @@ int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int 
                    int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, float* colsum,
                    float* colsum_scratch, void* hip_stream);
 
+/*
+ * Up to 4 independent GEMMs of one layout and epilogue (arguments as for
+ * hanayo_op_gemm) that go out as ONE launch where the tiled bf16 kernels take
+ * every problem, else one after the other.  chunk_backward sends a block's four
+ * weight-gradient GEMMs this way: none of them fills the chip alone.  The
+ * problems must not write the same memory.
+ */
+typedef struct hanayo_gemm_problem {
+  const void* A;
+  const void* B;
+  void* C;
+  const void* bias;
+  const void* aux;
+  void* aux_out;
+  int M, N, K;
+  int lda, ldb, ldc;
+  float* colsum;
+  float* colsum_scratch;
+} hanayo_gemm_problem;
+int hanayo_op_gemm_group(int dtype, int a_t, int b_t, int epilogue, const hanayo_gemm_problem* problems, int count,
+                         void* hip_stream);
+
+/*
+ * dst[0..bytes) = src[0..bytes), device to device, by a plain copy kernel
+ * (16-byte granularity: bytes and both pointers multiples of 16; the ranges
+ * must not overlap).  The post-LN chunk forward stashes its input with it; its
+ * HBM traffic is exactly `bytes` read plus `bytes` written, which makes it the
+ * kernel the hardware traffic counters are scaled against.
+ */
+int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
+
 /* Tuning knob for measurements: which bf16 MFMA GEMM kernel hanayo_op_gemm and the chunk calls use.
    -1 (default) = chosen from the shape; 0 / 1 / 2 / 4 = direct-to-LDS kernel with 256x256 / 128x128
    (8-deep load ring) / 256x128 / 128x128 (4-deep ring) tiles wherever the shape is a whole number of

@@ -18,25 +18,51 @@ int check_dtype(int dtype) {
 
 extern "C" {
 
+namespace {
+int fill_gemm(const hanayo_gemm_problem& q, int a_t, int b_t, int epilogue, k::GemmArgs& g) {
+  if (!q.A || !q.B || !q.C || q.M < 1 || q.N < 1 || q.K < 1)
+    return set_error(HANAYO_EINVAL, "op_gemm: NULL operand or empty problem");
+  if (epilogue < HANAYO_EPI_NONE || epilogue > HANAYO_EPI_ACCUM_F32) return set_error(HANAYO_EINVAL, "op_gemm: epilogue");
+  if (q.lda < (a_t ? q.M : q.K) || q.ldb < (b_t ? q.N : q.K) || q.ldc < q.N)
+    return set_error(HANAYO_EINVAL, "op_gemm: leading dimension too small");
+  const bool need_bias = epilogue == HANAYO_EPI_BIAS || epilogue == HANAYO_EPI_BIAS_GELU || epilogue == HANAYO_EPI_BIAS_RES;
+  const bool need_aux = epilogue == HANAYO_EPI_BIAS_RES || epilogue == HANAYO_EPI_MUL_DGELU || epilogue == HANAYO_EPI_ADD;
+  if ((need_bias && !q.bias) || (need_aux && !q.aux) || (epilogue == HANAYO_EPI_BIAS_GELU && !q.aux_out))
+    return set_error(HANAYO_EINVAL, "op_gemm: epilogue operand missing");
+  if (q.colsum && (!b_t || !q.colsum_scratch || q.ldb != q.N))
+    return set_error(HANAYO_EINVAL, "op_gemm: colsum needs b_t = 1, ldb = N and a scratch buffer");
+  g = k::GemmArgs{};
+  g.A = q.A; g.B = q.B; g.C = q.C; g.bias = q.bias; g.aux = q.aux; g.aux_out = q.aux_out;
+  g.M = q.M; g.N = q.N; g.K = q.K; g.lda = q.lda; g.ldb = q.ldb; g.ldc = q.ldc;
+  g.a_t = a_t != 0; g.b_t = b_t != 0; g.epi = static_cast<k::Epilogue>(epilogue);
+  g.colsum = q.colsum; g.colsum_scratch = q.colsum_scratch;
+  return HANAYO_OK;
+}
+}  // namespace
+
 int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
                    int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, float* colsum,
                    float* colsum_scratch, void* hip_stream) {
   if (int rc = check_dtype(dtype)) return rc;
-  if (!A || !B || !C || M < 1 || N < 1 || K < 1) return set_error(HANAYO_EINVAL, "op_gemm: NULL operand or empty problem");
-  if (epilogue < HANAYO_EPI_NONE || epilogue > HANAYO_EPI_ACCUM_F32) return set_error(HANAYO_EINVAL, "op_gemm: epilogue");
-  if (lda < (a_t ? M : K) || ldb < (b_t ? N : K) || ldc < N) return set_error(HANAYO_EINVAL, "op_gemm: leading dimension too small");
-  const bool need_bias = epilogue == HANAYO_EPI_BIAS || epilogue == HANAYO_EPI_BIAS_GELU || epilogue == HANAYO_EPI_BIAS_RES;
-  const bool need_aux = epilogue == HANAYO_EPI_BIAS_RES || epilogue == HANAYO_EPI_MUL_DGELU || epilogue == HANAYO_EPI_ADD;
-  if ((need_bias && !bias) || (need_aux && !aux) || (epilogue == HANAYO_EPI_BIAS_GELU && !aux_out))
-    return set_error(HANAYO_EINVAL, "op_gemm: epilogue operand missing");
-  k::GemmArgs g{};
-  g.A = A; g.B = B; g.C = C; g.bias = bias; g.aux = aux; g.aux_out = aux_out;
-  g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
-  g.a_t = a_t != 0; g.b_t = b_t != 0; g.epi = static_cast<k::Epilogue>(epilogue);
-  if (colsum && (!b_t || !colsum_scratch || ldb != N))
-    return set_error(HANAYO_EINVAL, "op_gemm: colsum needs b_t = 1, ldb = N and a scratch buffer");
-  g.colsum = colsum; g.colsum_scratch = colsum_scratch;
+  const hanayo_gemm_problem q = {A, B, C, bias, aux, aux_out, M, N, K, lda, ldb, ldc, colsum, colsum_scratch};
+  k::GemmArgs g;
+  if (int rc = fill_gemm(q, a_t, b_t, epilogue, g)) return rc;
   return k::gemm(dtype, g, static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_op_gemm_group(int dtype, int a_t, int b_t, int epilogue, const hanayo_gemm_problem* problems, int count,
+                         void* hip_stream) {
+  if (int rc = check_dtype(dtype)) return rc;
+  if (!problems || count < 1 || count > 4) return set_error(HANAYO_EINVAL, "op_gemm_group: 1 to 4 problems");
+  k::GemmArgs gs[4];
+  for (int i = 0; i < count; ++i)
+    if (int rc = fill_gemm(problems[i], a_t, b_t, epilogue, gs[i])) return rc;
+  return k::gemm_group(dtype, gs, count, static_cast<hipStream_t>(hip_stream));
+}
+
+int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  if (!dst || !src) return set_error(HANAYO_EINVAL, "op_copy: NULL pointer");
+  return k::copy_bytes(dst, src, bytes, static_cast<hipStream_t>(hip_stream));
 }
 
 int hanayo_op_gemm_config(int config) {

@@ -52,6 +52,14 @@ class ExecArgs(ctypes.Structure):
                 ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p), ("lanes", ctypes.c_int)]
 
 
+class GemmProblem(ctypes.Structure):
+    _fields_ = [("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("C", ctypes.c_void_p), ("bias", ctypes.c_void_p),
+                ("aux", ctypes.c_void_p), ("aux_out", ctypes.c_void_p),
+                ("M", ctypes.c_int), ("N", ctypes.c_int), ("K", ctypes.c_int),
+                ("lda", ctypes.c_int), ("ldb", ctypes.c_int), ("ldc", ctypes.c_int),
+                ("colsum", ctypes.c_void_p), ("colsum_scratch", ctypes.c_void_p)]
+
+
 class HanayoError(RuntimeError):
     def __init__(self, code):
         self.code = code
@@ -63,7 +71,7 @@ EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
            "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_device_info",
-           "hanayo_op_gemm", "hanayo_op_gemm_config", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
+           "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
@@ -89,7 +97,9 @@ _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.
 _lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
 _lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp, _vp, _vp]
+_lib.hanayo_op_gemm_group.argtypes = [_int, _int, _int, _int, _vp, _int, _vp]
 _lib.hanayo_op_gemm_config.argtypes = [_int]
+_lib.hanayo_op_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.hanayo_op_layernorm_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _vp, _vp, _int, _int, ctypes.c_float, _vp]
 _lib.hanayo_op_layernorm_backward.argtypes = [_int] + [_vp] * 9 + [_int, _int, _vp]
 _lib.hanayo_op_colsum_add.argtypes = [_int, _vp, _int, _int, _vp, _vp, _vp]
@@ -227,6 +237,44 @@ def hanayo_op_gemm(dtype, A, B, C, M, N, K, lda, ldb, ldc, a_t, b_t, epilogue, b
                    colsum=None, colsum_scratch=None, stream=None):
     _check(_lib.hanayo_op_gemm(dtype, _ptr(A), _ptr(B), _ptr(C), M, N, K, lda, ldb, ldc, int(a_t), int(b_t), epilogue,
                                _ptr(bias), _ptr(aux), _ptr(aux_out), _ptr(colsum), _ptr(colsum_scratch), stream))
+
+
+def _problem_array(problems):
+    arr = (GemmProblem * len(problems))()
+    for q, p in zip(arr, problems):
+        for name, _ in GemmProblem._fields_:
+            v = p.get(name)
+            setattr(q, name, v if isinstance(v, int) and name in ("M", "N", "K", "lda", "ldb", "ldc") else _ptr(v))
+    return arr
+
+
+def hanayo_op_gemm_group(dtype, a_t, b_t, epilogue, problems, stream=None):
+    """problems: list of dicts with the keys of hanayo_gemm_problem (tensors or None, ints)."""
+    arr = _problem_array(problems)
+    _check(_lib.hanayo_op_gemm_group(dtype, int(a_t), int(b_t), epilogue, ctypes.addressof(arr), len(problems), stream))
+
+
+def bound_op_gemm(*args, **kw):
+    """hanayo_op_gemm with its arguments marshalled once: returns a callable for launch loops
+    in which Python's per-call conversion cost would otherwise leave the GPU waiting."""
+    names = ("dtype A B C M N K lda ldb ldc a_t b_t epilogue bias aux aux_out colsum colsum_scratch stream").split()
+    vals = dict(zip(names, args))
+    vals.update(kw)
+    c = [vals["dtype"]] + [_ptr(vals[n]) for n in ("A", "B", "C")] + [int(vals[n]) for n in names[4:13]] + \
+        [_ptr(vals.get(n)) for n in ("bias", "aux", "aux_out", "colsum", "colsum_scratch")] + [vals.get("stream")]
+    fn = _lib.hanayo_op_gemm
+    return lambda: _check(fn(*c))
+
+
+def bound_op_gemm_group(dtype, a_t, b_t, epilogue, problems, stream=None):
+    """hanayo_op_gemm_group with its arguments marshalled once (see bound_op_gemm)."""
+    arr = _problem_array(problems)
+    fn, addr, n = _lib.hanayo_op_gemm_group, ctypes.addressof(arr), len(problems)
+    return lambda keep=arr: _check(fn(dtype, int(a_t), int(b_t), epilogue, addr, n, stream))
+
+
+def hanayo_op_copy(dst, src, nbytes, stream=None):
+    _check(_lib.hanayo_op_copy(_ptr(dst), _ptr(src), nbytes, stream))
 
 
 def hanayo_op_gemm_config(config):

@@ -60,6 +60,34 @@ def test_gemm(dtype, layout, shape):
     run_gemm_case(dtype, layout, shape)
 
 
+@pytest.mark.parametrize("dtype,shapes", [
+    ("bf16", [(512, 384, 256), (128, 128, 256), (256, 1024, 256), (1024, 128, 256)]),   # one tiled launch
+    ("bf16", [(256, 256, 512), (200, 136, 96)]),                                        # ragged member: one by one
+    ("fp32", [(96, 64, 80), (40, 72, 56), (64, 64, 64)]),
+])
+def test_gemm_group_weight_gradients(dtype, shapes):
+    """hanayo_op_gemm_group on weight-gradient problems of different sizes: every C += A^T B and
+    every column sum against numpy, the rows of C a neighbouring problem owns untouched."""
+    rng = np.random.default_rng(len(shapes) * 1009 + shapes[0][0])
+    probs, checks = [], []
+    for (M, N, K) in shapes:
+        A = rnd(rng, (K, M), dtype)
+        B = rnd(rng, (K, N), dtype, 0.05)
+        C0 = rng.normal(size=(M, N)).astype(np.float32)
+        cs0 = rng.normal(size=N).astype(np.float32)
+        t = dict(A=dev(A, dtype), B=dev(B, dtype), C=torch.from_numpy(C0).cuda(), M=M, N=N, K=K, lda=M, ldb=N, ldc=N,
+                 colsum=torch.from_numpy(cs0).cuda(), colsum_scratch=torch.empty(64 * N, dtype=torch.float32, device="cuda"))
+        probs.append(t)
+        checks.append((C0 + A.astype(np.float64).T @ B.astype(np.float64), cs0 + B.astype(np.float64).sum(0)))
+    hn.hanayo_op_gemm_group(DT[dtype], True, True, hn.EPI_ACCUM_F32, probs)
+    torch.cuda.synchronize()
+    for t, (want, want_cs) in zip(probs, checks):
+        assert nerr(t["C"].cpu().numpy(), want) <= TOL[dtype]
+        assert nerr(t["colsum"].cpu().numpy(), want_cs) <= 1e-4
+    with pytest.raises(hn.HanayoError):
+        hn.hanayo_op_gemm_group(DT[dtype], True, True, hn.EPI_ACCUM_F32, (probs * 3)[:5])   # more than 4
+
+
 def run_gemm_case(dtype, layout, shape):
     M, N, K = shape
     if dtype == "fp32" and M * N * K > 4096 * 4096 * 64:
@@ -213,3 +241,17 @@ def test_attention_forward_backward(dtype, case):
     for i, name in enumerate("qkv"):
         e = nerr(got[..., i * H:(i + 1) * H], dqkv_ref[..., i * H:(i + 1) * H])
         assert e <= TOL[dtype], "d%s: %.3g" % (name, e)
+
+
+@pytest.mark.parametrize("nbytes", [0, 16, 4096 + 16, (3 << 20) + 48, 70 << 20])
+def test_copy_kernel(nbytes):
+    """The plain copy kernel: byte-exact, nothing written past the end."""
+    src = torch.randint(0, 256, (nbytes + 64,), dtype=torch.uint8, device="cuda")
+    dst = torch.full((nbytes + 64,), 7, dtype=torch.uint8, device="cuda")
+    hn.hanayo_op_copy(dst, src, nbytes)
+    torch.cuda.synchronize()
+    assert torch.equal(dst[:nbytes], src[:nbytes])
+    assert bool((dst[nbytes:] == 7).all())
+    if nbytes:
+        with pytest.raises(hn.HanayoError):
+            hn.hanayo_op_copy(dst, src, nbytes - 8)
