@@ -110,10 +110,10 @@ enum { HANAYO_FP32 = 0, HANAYO_BF16 = 1 }; /* storage type; accumulation is alwa
 
 typedef struct hanayo_chunk_desc {
   int n_blocks;
-  int hidden; /* H; multiple of 64 */
-  int heads;  /* H / heads must be 64 or 128 (fp32 storage: any multiple of 16 up to 128) */
-  int ffn;    /* F; multiple of 64 */
-  int seq;    /* s; multiple of 64 */
+  int hidden; /* H; multiple of 8, at most 4096 (the fast bf16 kernels want multiples of 128) */
+  int heads;  /* H / heads: multiple of 8, at most 128 (64 and 128 take the fastest attention kernels) */
+  int ffn;    /* F; multiple of 8 */
+  int seq;    /* s; any length >= 1; seq * mb at most 2^24 */
   int mb;     /* sequences per micro-batch b; tokens T = b * s */
   int norm;   /* HANAYO_PRE_LN / HANAYO_POST_LN */
   int mask;   /* HANAYO_MASK_NONE / HANAYO_MASK_CAUSAL; key padding comes from valid_len */
@@ -300,9 +300,10 @@ int hanayo_op_gemm_group(int dtype, int a_t, int b_t, int epilogue, const hanayo
 int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* Tuning knob for measurements: which bf16 MFMA GEMM kernel hanayo_op_gemm and the chunk calls use.
-   -1 (default) = chosen from the shape; 0 / 1 / 2 / 4 = direct-to-LDS kernel with 256x256 / 128x128
-   (8-deep load ring) / 256x128 / 128x128 (4-deep ring) tiles wherever the shape is a whole number of
-   tiles; 3 = register-staged kernel only.
+   -1 (default) = chosen from the shape by a fitted cost model; 0 / 1 / 2 / 4 / 5 = direct-to-LDS kernel
+   with 256x256 / 128x128 (8-deep load ring) / 256x128 / 128x128 (4-deep ring, two workgroups per CU) /
+   128x128 (8 wavefronts that split a K tile's MFMA steps) tiles wherever the shape is a whole number
+   of tiles; 3 = register-staged kernel only.  HANAYO_EINVAL outside -1..5.
    Process-wide, not thread-safe. */
 int hanayo_op_gemm_config(int config);
 

@@ -117,17 +117,35 @@ __global__ __launch_bounds__(64) void attn_fwd_alu_kernel(const T* __restrict__ 
   if (lane == 0) lse[((size_t)n * heads + h) * s + i] = mx + __logf(sum);
 }
 
-// delta[n][h][i] = sum_c dctx[i][c] * ctx[i][c]
+// delta[n][h][i] = sum_c dctx[i][c] * ctx[i][c].  ctx and dctx are read as one stream of 8-element
+// vectors (d / 8 consecutive vectors make one (row, head) group); a workgroup takes kDeltaGroups
+// groups, parks the per-vector sums in LDS and adds each group up.
+constexpr int kDeltaGroups = 64;
 template <typename T>
-__global__ __launch_bounds__(64) void attn_delta_kernel(const T* __restrict__ ctx, const T* __restrict__ dctx,
-                                                        float* __restrict__ delta, int s, int heads, int d) {
-  const int i = blockIdx.x, h = blockIdx.y, n = blockIdx.z, lane = threadIdx.x;
-  const int H = heads * d;
-  const size_t at = ((size_t)n * s + i) * H + h * d;
-  float t = 0.f;
-  for (int c = lane; c < d; c += 64) t += ld(ctx + at + c) * ld(dctx + at + c);
-  t = wave_sum(t);
-  if (lane == 0) delta[((size_t)n * heads + h) * s + i] = t;
+__global__ __launch_bounds__(256) void attn_delta_kernel(const T* __restrict__ ctx, const T* __restrict__ dctx,
+                                                         float* __restrict__ delta, long groups, int s, int heads, int d) {
+  __shared__ float part[kDeltaGroups * 16];
+  const int vpg = d / 8;  // vectors per group, at most 16
+  const long g0 = (long)blockIdx.x * kDeltaGroups;
+  const int ng = (int)(groups - g0 < kDeltaGroups ? groups - g0 : kDeltaGroups);
+  for (int v = threadIdx.x; v < ng * vpg; v += 256) {
+    float a[8], b[8];
+    load8(ctx + (g0 * vpg + v) * 8, a);
+    load8(dctx + (g0 * vpg + v) * 8, b);
+    float t = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) t += a[e] * b[e];
+    part[v] = t;
+  }
+  __syncthreads();
+  if ((int)threadIdx.x < ng) {
+    float t = 0.f;
+    for (int j = 0; j < vpg; ++j) t += part[threadIdx.x * vpg + j];
+    const long g = g0 + threadIdx.x;  // = row * heads + head
+    const long row = g / heads;
+    const int h = (int)(g - row * heads);
+    delta[((row / s) * heads + h) * s + row % s] = t;
+  }
 }
 
 // dQ of one query row: dS_j = P_ij (dP_ij - delta_i), dQ_i = scale * sum_j dS_j K_j
@@ -263,8 +281,10 @@ int attn_fwd_alu_t(const AttnArgs& a, hipStream_t stream) {
 
 template <typename T>
 int attn_delta_t(const AttnArgs& a, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_delta_kernel<T>), dim3(a.s, a.heads, a.b), dim3(64), 0, stream, (const T*)a.ctx,
-                     (const T*)a.dctx, a.delta, a.s, a.heads, a.d);
+  if (a.d % 8 || a.d > 128) return set_error(HANAYO_EUNSUPPORTED, "attn_delta: head dim %d", a.d);
+  const long groups = (long)a.b * a.s * a.heads;
+  hipLaunchKernelGGL((attn_delta_kernel<T>), dim3((unsigned)((groups + kDeltaGroups - 1) / kDeltaGroups)), dim3(256), 0,
+                     stream, (const T*)a.ctx, (const T*)a.dctx, a.delta, groups, a.s, a.heads, a.d);
   return check_launch("attn_delta");
 }
 

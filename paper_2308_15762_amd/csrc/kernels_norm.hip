@@ -188,11 +188,11 @@ __global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict_
   }
 }
 
-// out[c] += sum_r partial[r][c] for c in [0, n): a thread owns one column of a slab of 32 partial
-// rows and adds its sum with one atomic, so the reduction is spread over (n / 256) x (rows / 32)
+// out[c] += sum_r partial[r][c] for c in [0, n): a thread owns one column of a slab of 8 partial
+// rows and adds its sum with one atomic, so the reduction is spread over (n / 256) x (rows / 8)
 // workgroups instead of running down the rows in a few.  Columns >= split go to out1[c - split].
 // (fp32 atomics: the order in which the slabs are added is not fixed.)
-constexpr int kFinalizeRows = 32;
+constexpr int kFinalizeRows = 8;
 __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n,
                                                        float* __restrict__ out0, float* __restrict__ out1, int split) {
   const int c = blockIdx.x * 256 + threadIdx.x;
