@@ -300,10 +300,10 @@ int hanayo_op_gemm_group(int dtype, int a_t, int b_t, int epilogue, const hanayo
 int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* Tuning knob for measurements: which bf16 MFMA GEMM kernel hanayo_op_gemm and the chunk calls use.
-   -1 (default) = chosen from the shape by a fitted cost model; 0 / 1 / 2 / 4 / 5 = direct-to-LDS kernel
-   with 256x256 / 128x128 (8-deep load ring) / 256x128 / 128x128 (4-deep ring, two workgroups per CU) /
-   128x128 (8 wavefronts that split a K tile's MFMA steps) tiles wherever the shape is a whole number
-   of tiles; 3 = register-staged kernel only.  HANAYO_EINVAL outside -1..5.
+   -1 (default) = chosen from the shape by a fitted cost model; 0 / 1 / 2 / 4 / 5 / 6 = direct-to-LDS
+   kernel with 256x256 / 128x128 (8-deep load ring) / 256x128 / 128x128 (4-deep ring, two workgroups per
+   CU) / 128x128 (8 wavefronts that split a K tile's MFMA steps) / 256x256 (8 wavefronts) tiles wherever
+   the shape is a whole number of tiles; 3 = register-staged kernel only.  HANAYO_EINVAL outside -1..6.
    Process-wide, not thread-safe. */
 int hanayo_op_gemm_config(int config);
 

@@ -568,10 +568,11 @@ int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
 
 // Tile configurations: 0 = 256 x 256, 1 = 128 x 128 with an 8-deep buffer ring, 2 = 256 x 128,
 // 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU), 5 = as 4 with 8 wavefronts that split
-// the MFMA steps of a K tile.  The others use 4 wavefronts.
+// the MFMA steps of a K tile, 6 = 256 x 256 with 8 wavefronts (2 x 4, 128 x 64 each: two per SIMD
+// that cover each other's stalls).  The others use 4 wavefronts.
 void gemm_dma_tile(int config, int& bm, int& bn) {
   bm = (config == 1 || config == 4 || config == 5) ? 128 : 256;
-  bn = config == 0 ? 256 : 128;
+  bn = (config == 0 || config == 6) ? 256 : 128;
 }
 
 bool gemm_dma_supported(const GemmArgs& g, int config) {
@@ -607,6 +608,7 @@ int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream
     case 1: return launch_layout<128, 128, 2, 2, 8, 1>(g, grp, stream);  // 128 KiB LDS: one workgroup per CU
     case 4: return launch_layout<128, 128, 2, 2, 4, 1>(g, grp, stream);  // 64 KiB LDS: two per CU
     case 5: return launch_layout<128, 128, 2, 2, 4, 2>(g, grp, stream);
+    case 6: return launch_layout<256, 256, 2, 4, 4, 0>(g, grp, stream);  // 8 wavefronts, 128 x 64 each
     default: return launch_layout<256, 128, 2, 2, 4, 0>(g, grp, stream);
   }
 }
