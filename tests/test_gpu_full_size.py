@@ -62,7 +62,7 @@ def test_benchmark_workload_sampled_micro_batch():
     against the oracle (chunks 1 -> 2 are the local turn-around)."""
     wl = W["gpt_1024_bf16"]
     tol = TOL["bf16"]
-    gpu = GpuRank(wl, 0)
+    gpu = GpuRank(wl, 0, lanes=4)          # the launch configuration bench.py times
     peak = gpu.run()
     torch.cuda.synchronize()
     assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0] == 16
