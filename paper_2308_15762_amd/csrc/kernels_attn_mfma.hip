@@ -597,6 +597,154 @@ __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
   }
 }
 
+// Forward, software-pipelined over the key tiles: the score MFMAs of tile t+1 are issued in the same
+// straight-line block as the softmax of tile t, so the matrix pipe works on the next scores while
+// the VALU does this tile's exponentials (within one wavefront the two would otherwise take turns:
+// the longest query tile's chain of key tiles sets the kernel's duration).  Two score registers
+// sets alternate roles; tile t+1 must have landed when step t starts, hence NST >= 3 buffers and
+// the loads of tile t+NST-1 issued at step t.  Arithmetic is that of attn_fwd_dma_kernel.
+template <int DP, int NST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_pipe_kernel(AttnDev p) {
+  using Tile = SwTile<DP>;
+  static_assert(NST >= 3, "tile t+1 is read while tile t+NST-1 is loaded");
+  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
+  typename Tile::Offsets fo;
+  Tile::init(fo, lane);
+  const int qt = gridDim.z - 1 - blockIdx.z, h = blockIdx.x, n = blockIdx.y;
+  const int H = p.heads * p.d, ld3 = 3 * H;
+  const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
+  const int len = seq_len(p, n);
+  const int q0 = qt * 128, qw0 = q0 + 32 * wave, q = qw0 + (lane & 31);
+  const int kv_end = p.causal ? min(len, q0 + 128) : len;
+  const int nt = (kv_end + BKV - 1) / BKV;
+  const float c2 = rsqrtf((float)p.d) * kLog2e;
+
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
+    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+  };
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < nt) issue(t);
+
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) qf[kk] = frag_global(base + (size_t)q * ld3, q < p.s, kk, lane, p.d);
+  f32x16 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = zero16();
+  float m = -INFINITY, lsum = 0.f;  // m in units of raw (unscaled) scores
+
+  auto scores = [&](int t, f32x16 (&sc)[2]) {
+    const char* Ks = smem + (t % NST) * STAGE;
+#pragma unroll
+    for (int c = 0; c < 2; ++c) sc[c] = zero16();
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk)
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+        sc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Ks, fo, 32 * c, kk), qf[kk], sc[c], 0, 0, 0);
+  };
+  // Step t: scores of tile t are in cur; those of tile t+1 (if MORE) go to nxt.  MORE is a
+  // compile-time flag so that the score MFMAs and the softmax arithmetic share one basic block,
+  // where the scheduling hints below spread the MFMAs between the VALU instructions.
+  auto step = [&](auto more_tag, int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+    constexpr bool MORE = decltype(more_tag)::value;
+    if (MORE) wait_tiles<LOADS>(min(NST - 3, nt - 2 - t));  // tile t+1 has landed (this wavefront's share)
+    __syncthreads();  // everyone's share of it has; everyone is done with tile t-1
+    if (t + NST - 1 < nt) issue(t + NST - 1);
+    const int k0 = t * BKV;
+    if (p.causal && k0 > qw0 + 31) return;  // this and all later tiles are ahead of this wavefront's rows
+    if ((p.causal && k0 + BKV - 1 > qw0) || k0 + BKV > len) {
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * c + acc_row(r, half);
+          if (!(key < len && (!p.causal || key <= q))) cur[c][r] = -INFINITY;
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (MORE) scores(t + 1, nxt);
+    const char* Vs = smem + (t % NST) * STAGE + Tile::kBytes;
+    float mloc = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mloc = fmaxf(mloc, cur[c][r]);
+    mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+    const float m_new = fmaxf(m, mloc);  // finite: key 0 is allowed for every row and comes first
+    const float alpha = __builtin_amdgcn_exp2f((m - m_new) * c2);
+    const float shift = -m_new * c2;
+    float rs = 0.f;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(cur[c][r], c2, shift));
+        cur[c][r] = e;
+        rs += e;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    lsum = lsum * alpha + rs;
+    m = m_new;
+    __builtin_amdgcn_sched_barrier(0);
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {  // the running maximum moved for some row
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 pf = pack_half(cur[c], tt);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Vs, fo, 32 * c + 16 * tt, dt), pf, o[dt], 0, 0, 0);
+      }
+  };
+  const std::true_type more;
+  const std::false_type last;
+
+  wait_tiles<LOADS>(min(NST - 2, nt - 1));  // tile 0
+  __syncthreads();
+  f32x16 sa[2], sb[2];
+  scores(0, sa);
+  int t = 0;
+  for (; t + 2 < nt; t += 2) {
+    step(more, t, sa, sb);
+    step(more, t + 1, sb, sa);
+  }
+  if (t + 1 < nt) {
+    step(more, t, sa, sb);
+    step(last, t + 1, sb, sa);
+  } else {
+    step(last, t, sa, sb);
+  }
+  if (q < p.s) {
+    const float inv = 1.f / lsum;
+    bf16* out = p.ctx + ((size_t)n * p.s + q) * H + h * p.d;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = 32 * dt + 8 * g + 4 * half;
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[dt][4 * g + e] * inv);
+        *reinterpret_cast<bf16x4*>(out + col) = v;
+      }
+    if (half == 0) p.lse[((size_t)n * p.heads + h) * p.s + q] = (m * c2 + log2f(lsum)) * kLn2;
+  }
+}
+
 template <int DP, int NST>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
   using Tile = SwTile<DP>;
@@ -841,8 +989,8 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
   const dim3 grid(a.heads, a.b, (a.s + 127) / 128), block(256);
   if (dma_ok(a)) {
     if (a.d == 64) {
-      constexpr size_t lds = 3 * 2 * SwTile<64>::kBytes;
-      hipLaunchKernelGGL((attn_fwd_dma_kernel<64, 3>), grid, block, lds, stream, p);
+      constexpr size_t lds = 4 * 2 * SwTile<64>::kBytes;
+      hipLaunchKernelGGL((attn_fwd_pipe_kernel<64, 4>), grid, block, lds, stream, p);
     } else {
       constexpr size_t lds = 2 * 2 * SwTile<128>::kBytes;
       hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2>), grid, block, lds, stream, p);
