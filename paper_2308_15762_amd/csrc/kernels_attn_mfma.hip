@@ -954,6 +954,280 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
   }
 }
 
+// dK / dV, software-pipelined in half tiles of 32 queries like attn_bwd_dq_pipe_kernel: the score
+// MFMAs of the next half tile (and this half's dP MFMAs) share a block with the exponentials, dS and
+// the dV / dK MFMAs of this one.  Arithmetic is that of attn_bwd_dkv_dma_kernel.
+template <int DP, int NST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_pipe_kernel(AttnDev p) {
+  using Tile = SwTile<DP>;
+  static_assert(NST >= 3, "tile t+1 is read while tile t+NST-1 is loaded");
+  constexpr int BQ = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int STAGE = 2 * Tile::kBytes + 512;  // Q tile, dC tile, 64 lse, 64 delta
+  constexpr int LOADS = 2 * Tile::kPerWave + 1;  // every wavefront also issues one 4-byte-per-lane load
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
+  typename Tile::Offsets fo;
+  Tile::init(fo, lane);
+  const int kt = blockIdx.z, h = blockIdx.x, n = blockIdx.y;
+  const int H = p.heads * p.d, ld3 = 3 * H;
+  const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
+  const bf16* dcb = p.dctx + (size_t)n * p.s * H + h * p.d;
+  const size_t stat0 = ((size_t)n * p.heads + h) * p.s;
+  const int len = seq_len(p, n);
+  const int k0 = kt * 128, kw0 = k0 + 32 * wave, key = kw0 + (lane & 31);
+  const float scale = rsqrtf((float)p.d), c2 = scale * kLog2e;
+
+  const int q_begin = (p.causal && k0 < len) ? (k0 / BQ) * BQ : 0;
+  const int q_end = k0 < len ? p.s : 0;  // a tile of masked keys gets zero gradients
+  const int nt = q_end > q_begin ? (q_end - q_begin + BQ - 1) / BQ : 0;
+
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
+    const int q0 = q_begin + t * BQ;
+    Tile::issue(base, ld3, q0, p.s, st, wave, lane);
+    Tile::issue(dcb, H, q0, p.s, st + Tile::kBytes, wave, lane);
+    // wavefronts 0 / 1 fetch the 64 log-sum-exp / delta values; 2 / 3 repeat them (same data, keeps
+    // every wavefront's load count equal)
+    const int qq = min(q0 + lane, p.s - 1);
+    const float* src = (wave & 1) ? p.delta + stat0 : p.lse + stat0;
+    dma4(src, (unsigned)(qq * 4), st + 2 * Tile::kBytes + (wave & 1) * 256);
+  };
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < nt) issue(t);
+
+  bf16x8 kf[KS], vf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    kf[kk] = frag_global(base + H + (size_t)key * ld3, key < p.s, kk, lane, p.d);
+    vf[kk] = frag_global(base + 2 * H + (size_t)key * ld3, key < p.s, kk, lane, p.d);
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    dk[dt] = zero16();
+    dv[dt] = zero16();
+  }
+  if (nt == 0) goto store;  // uniform over the workgroup
+  {
+    // S of the 32 queries of half c of tile t
+    auto scores = [&](int t, int c, f32x16& sc) {
+      const char* Qs = smem + (t % NST) * STAGE;
+      sc = zero16();
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+        sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Qs, fo, 32 * c, kk), kf[kk], sc, 0, 0, 0);
+    };
+    // The scores of half c of tile t are in sc; NEXT: those of the following half (tn, cn) go to sc_n.
+    // dP of this half is formed here as well: its MFMAs and the next scores' run under the exponentials.
+    auto half_step = [&](auto next_tag, int t, int c, f32x16& sc, int tn, int cn, f32x16& sc_n) {
+      constexpr bool NEXT = decltype(next_tag)::value;
+      const int q0 = q_begin + t * BQ + 32 * c;
+      const bool active = !(p.causal && q0 + 31 < kw0);  // else all these queries precede the wavefront's keys
+      if (active && ((p.causal && q0 < kw0 + 31) || kw0 + 31 >= len || q0 + 31 >= p.s)) {  // masked scores give P = 0
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qq = q0 + acc_row(r, half);
+          if (!(qq < p.s && key < len && (!p.causal || key <= qq))) sc[r] = -INFINITY;
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (!active) {  // only keep the pipeline going
+        if (NEXT) scores(tn, cn, sc_n);
+        return;
+      }
+      const char* Qs = smem + (t % NST) * STAGE;
+      const char* Cs = Qs + Tile::kBytes;
+      const float* lse_s = reinterpret_cast<const float*>(Cs + Tile::kBytes);
+      const float* dlt_s = lse_s + 64;
+      f32x16 dp = zero16();
+#pragma unroll
+      for (int kk = 0; kk < KS; ++kk)
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Cs, fo, 32 * c, kk), vf[kk], dp, 0, 0, 0);
+      if (NEXT) scores(tn, cn, sc_n);
+      // P = 2^(c2 s - lse log2e), dS = P (dP - delta); lse and delta of this lane's 16 queries come as 4-vectors
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int ql = 32 * c + 8 * g + 4 * half;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(lse_s + ql);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(dlt_s + ql);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * g + e;
+          const float pr = __builtin_amdgcn_exp2f(fmaf(sc[r], c2, -l4[e] * kLog2e));
+          sc[r] = pr;
+          dp[r] = pr * (dp[r] - d4[e]);
+        }
+      }
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const bf16x8 pf = pack_half(sc, tt), dsf = pack_half(dp, tt);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Cs, fo, 32 * c + 16 * tt, dt), pf, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Qs, fo, 32 * c + 16 * tt, dt), dsf, dk[dt], 0, 0, 0);
+        }
+      }
+    };
+    const std::true_type next;
+    const std::false_type none;
+
+    wait_tiles<LOADS>(min(NST - 2, nt - 1));  // tile 0
+    __syncthreads();
+    f32x16 sa, sb;
+    scores(0, 0, sa);
+    for (int t = 0; t < nt; ++t) {
+      half_step(next, t, 0, sa, t, 1, sb);
+      if (t + 1 < nt) {
+        wait_tiles<LOADS>(min(NST - 3, nt - 2 - t));  // tile t+1 has landed (this wavefront's share)
+        __syncthreads();                              // everyone's share has; everyone is done with tile t-1
+        if (t + NST - 1 < nt) issue(t + NST - 1);
+        half_step(next, t, 1, sb, t + 1, 0, sa);
+      } else {
+        half_step(none, t, 1, sb, 0, 0, sa);
+      }
+    }
+  }
+store:
+  if (key < p.s) {
+    bf16* out = p.dqkv + ((size_t)n * p.s + key) * ld3 + h * p.d;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = 32 * dt + 8 * g + 4 * half;
+        bf16x4 a, b;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a[e] = (bf16)(dk[dt][4 * g + e] * scale);
+          b[e] = (bf16)dv[dt][4 * g + e];
+        }
+        *reinterpret_cast<bf16x4*>(out + H + col) = a;
+        *reinterpret_cast<bf16x4*>(out + 2 * H + col) = b;
+      }
+  }
+}
+
+// dQ, software-pipelined in half tiles of 32 keys: the S and dP MFMAs of the next half tile are
+// issued in the block that does the exponentials, dS and the dQ MFMAs of this one.  Two register
+// sets alternate; the barrier that admits tile t+1 sits between the two halves of tile t.
+// Arithmetic is that of attn_bwd_dq_dma_kernel.
+template <int DP, int NST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_pipe_kernel(AttnDev p) {
+  using Tile = SwTile<DP>;
+  static_assert(NST >= 3, "tile t+1 is read while tile t+NST-1 is loaded");
+  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), half = lane >> 5;
+  typename Tile::Offsets fo;
+  Tile::init(fo, lane);
+  const int qt = gridDim.z - 1 - blockIdx.z, h = blockIdx.x, n = blockIdx.y;
+  const int H = p.heads * p.d, ld3 = 3 * H;
+  const bf16* base = p.qkv + (size_t)n * p.s * ld3 + h * p.d;
+  const int len = seq_len(p, n);
+  const int q0 = qt * 128, qw0 = q0 + 32 * wave, q = qw0 + (lane & 31);
+  const int kv_end = p.causal ? min(len, q0 + 128) : len;
+  const int nt = (kv_end + BKV - 1) / BKV;
+  const float scale = rsqrtf((float)p.d), c2 = scale * kLog2e;
+
+  auto issue = [&](int t) {
+    const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
+    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+  };
+#pragma unroll
+  for (int t = 0; t < NST - 1; ++t)
+    if (t < nt) issue(t);
+
+  const size_t stat = ((size_t)n * p.heads + h) * p.s + q;
+  const float my_lse2 = q < p.s ? p.lse[stat] * kLog2e : 0.f;
+  const float my_delta = q < p.s ? p.delta[stat] : 0.f;
+  bf16x8 qf[KS], cf[KS];
+#pragma unroll
+  for (int kk = 0; kk < KS; ++kk) {
+    qf[kk] = frag_global(base + (size_t)q * ld3, q < p.s, kk, lane, p.d);
+    cf[kk] = frag_global(p.dctx + ((size_t)n * p.s + q) * H + h * p.d, q < p.s, kk, lane, p.d);
+  }
+  f32x16 dq[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) dq[dt] = zero16();
+
+  // S (sc) and dP (dp) of the 32 keys of half c of tile t
+  auto products = [&](int t, int c, f32x16& sc, f32x16& dp) {
+    const char* Ks = smem + (t % NST) * STAGE;
+    const char* Vs = Ks + Tile::kBytes;
+    sc = zero16();
+    dp = zero16();
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Ks, fo, 32 * c, kk), qf[kk], sc, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_rows(Vs, fo, 32 * c, kk), cf[kk], dp, 0, 0, 0);
+    }
+  };
+  // Half c of tile t is in (sc, dp); NEXT: the following half (tn, cn) goes to (sc_n, dp_n).
+  auto half_step = [&](auto next_tag, int t, int c, f32x16& sc, f32x16& dp, int tn, int cn, f32x16& sc_n, f32x16& dp_n) {
+    constexpr bool NEXT = decltype(next_tag)::value;
+    const int k0 = t * BKV + 32 * c;
+    if ((p.causal && k0 + 31 > qw0) || k0 + 32 > len) {  // masked scores give P = 0
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + acc_row(r, half);
+        if (!(key < len && (!p.causal || key <= q))) sc[r] = -INFINITY;
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (NEXT) products(tn, cn, sc_n, dp_n);
+    const char* Ks = smem + (t % NST) * STAGE;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const float pr = __builtin_amdgcn_exp2f(fmaf(sc[r], c2, -my_lse2));
+      dp[r] = pr * (dp[r] - my_delta);
+    }
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const bf16x8 dsf = pack_half(dp, tt);
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+        dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Tile::frag_cols(Ks, fo, 32 * c + 16 * tt, dt), dsf, dq[dt], 0, 0, 0);
+    }
+  };
+  const std::true_type next;
+  const std::false_type none;
+
+  wait_tiles<LOADS>(min(NST - 2, nt - 1));  // tile 0
+  __syncthreads();
+  f32x16 sa, da, sb, db;
+  products(0, 0, sa, da);
+  for (int t = 0; t < nt; ++t) {
+    const bool active = !(p.causal && t * BKV > qw0 + 31);  // false from some tile on: keys ahead of all rows
+    if (active) half_step(next, t, 0, sa, da, t, 1, sb, db);
+    if (t + 1 < nt) {
+      wait_tiles<LOADS>(min(NST - 3, nt - 2 - t));  // tile t+1 has landed (this wavefront's share)
+      __syncthreads();                              // everyone's share has; everyone is done with tile t-1
+      if (t + NST - 1 < nt) issue(t + NST - 1);
+      if (active) half_step(next, t, 1, sb, db, t + 1, 0, sa, da);
+    } else if (active) {
+      half_step(none, t, 1, sb, db, 0, 0, sa, da);
+    }
+  }
+  if (q < p.s) {
+    bf16* out = p.dqkv + ((size_t)n * p.s + q) * ld3 + h * p.d;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int col = 32 * dt + 8 * g + 4 * half;
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16)(dq[dt][4 * g + e] * scale);
+        *reinterpret_cast<bf16x4*>(out + col) = v;
+      }
+  }
+}
+
 template <typename K>
 int raise_lds(K kern, size_t lds) {
   if (lds <= 64 * 1024) return HANAYO_OK;
@@ -1011,8 +1285,11 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
   const dim3 grid(a.heads, a.b, (a.s + 127) / 128), block(256);
   if (dma_ok(a)) {
     if (a.d == 64) {
-      hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<64, 3>), grid, block, 3 * (2 * SwTile<64>::kBytes + 512), stream, p);
-      hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<64, 3>), grid, block, 3 * 2 * SwTile<64>::kBytes, stream, p);
+      constexpr size_t lds_dkv = 4 * (2 * SwTile<64>::kBytes + 512);
+      rc = raise_lds(attn_bwd_dkv_pipe_kernel<64, 4>, lds_dkv);
+      if (rc) return rc;
+      hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<64, 4>), grid, block, lds_dkv, stream, p);
+      hipLaunchKernelGGL((attn_bwd_dq_pipe_kernel<64, 4>), grid, block, 4 * 2 * SwTile<64>::kBytes, stream, p);
     } else {
       constexpr size_t lds_dkv = 2 * (2 * SwTile<128>::kBytes + 512);
       rc = raise_lds(attn_bwd_dkv_dma_kernel<128, 2>, lds_dkv);
