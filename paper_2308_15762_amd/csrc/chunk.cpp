@@ -94,10 +94,11 @@ int g_gemm_config = -1;
 void set_gemm_config(int config) { g_gemm_config = config; }
 
 // Tile choice for the direct-to-LDS kernels by a cost model fitted to timings on MI355X: a launch
-// runs ceil(tiles / 256 CUs) rounds, each costing one K tile's time per 32 columns of K (0.84 us for
-// 256 x 256 with 8 wavefronts, 0.52 us for 256 x 128, 0.295 us for 128 x 128 with two workgroups sharing a CU), plus a
-// fixed start and epilogue cost.  Large tiles reuse operands better; small ones waste less of the
-// last round.  Returns -1 if no configuration takes every problem.
+// runs ceil(tiles / 256 CUs) rounds; a round costs one K tile's time per 32 columns of K (0.84 us for
+// 256 x 256 with 8 wavefronts, 0.52 us for 256 x 128, 0.295 us for 128 x 128 with two workgroups
+// sharing a CU) plus an epilogue, and the launch a fixed start-up (pipeline fill grows with the
+// tile).  Large tiles reuse operands better; small ones waste less of the last round.  Returns -1
+// if no configuration takes every problem.
 int choose_dma_config(const GemmArgs* gs, int count) {
   if (g_gemm_config >= 0 && g_gemm_config != 3) {
     for (int i = 0; i < count; ++i)
@@ -105,7 +106,8 @@ int choose_dma_config(const GemmArgs* gs, int count) {
     return g_gemm_config;
   }
   if (g_gemm_config != -1) return -1;
-  static const struct { int config; double per_ktile, fixed; } kTiles[] = {{6, 0.84, 10.0}, {2, 0.52, 8.0}, {4, 0.295, 5.0}};
+  static const struct { int config; double per_ktile, epilogue, start; } kTiles[] = {
+      {6, 0.84, 3.0, 7.0}, {2, 0.52, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
   int best = -1;
   double best_cost = 0.0;
   for (const auto& t : kTiles) {
@@ -121,7 +123,7 @@ int choose_dma_config(const GemmArgs* gs, int count) {
       ktiles += (double)ti * (gs[i].K / 32);
     }
     if (!ok || tiles == 0) continue;
-    const double cost = t.fixed + (double)((tiles + 255) / 256) * (ktiles / tiles) * t.per_ktile;
+    const double cost = t.start + (double)((tiles + 255) / 256) * ((ktiles / tiles) * t.per_ktile + t.epilogue);
     if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
   }
   return best;
