@@ -90,15 +90,18 @@ namespace k {
 
 namespace {
 int g_gemm_config = -1;
+thread_local double g_gemm_sharing = 0.0;
 }
 void set_gemm_config(int config) { g_gemm_config = config; }
+void set_gemm_sharing(double share) { g_gemm_sharing = share < 0.0 ? 0.0 : (share > 1.0 ? 1.0 : share); }
 
 // Tile choice for the direct-to-LDS kernels by a cost model fitted to timings on MI355X: a launch
 // runs ceil(tiles / 256 CUs) rounds; a round costs one K tile's time per 32 columns of K (0.84 us for
 // 256 x 256 with 8 wavefronts, 0.52 us for 256 x 128, 0.295 us for 128 x 128 with two workgroups
 // sharing a CU) plus an epilogue, and the launch a fixed start-up (pipeline fill grows with the
-// tile).  Large tiles reuse operands better; small ones waste less of the last round.  Returns -1
-// if no configuration takes every problem.
+// tile).  Large tiles reuse operands better; small ones waste less of the last round, which matters
+// less the more the chip is shared with other streams' kernels (set_gemm_sharing).  Returns -1 if no
+// configuration takes every problem.
 int choose_dma_config(const GemmArgs* gs, int count) {
   if (g_gemm_config >= 0 && g_gemm_config != 3) {
     for (int i = 0; i < count; ++i)
@@ -123,7 +126,10 @@ int choose_dma_config(const GemmArgs* gs, int count) {
       ktiles += (double)ti * (gs[i].K / 32);
     }
     if (!ok || tiles == 0) continue;
-    const double cost = t.start + (double)((tiles + 255) / 256) * ((ktiles / tiles) * t.per_ktile + t.epilogue);
+    // Alone on the chip a launch pays for whole rounds; next to kernels of other lanes the CUs its
+    // last round leaves idle are not lost, so the count moves towards tiles / 256.
+    const double rounds = g_gemm_sharing * (double)tiles / 256.0 + (1.0 - g_gemm_sharing) * (double)((tiles + 255) / 256);
+    const double cost = t.start + rounds * ((ktiles / tiles) * t.per_ktile + t.epilogue);
     if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
   }
   return best;

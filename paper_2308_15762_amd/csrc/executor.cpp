@@ -20,6 +20,7 @@
 #include <vector>
 
 #include "internal.h"
+#include "kernels.h"
 
 namespace hanayo {
 int prepare_call(const hanayo_chunk_desc* d, Shape& sh);
@@ -271,6 +272,8 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
       HIP_TRY(hipStreamWaitEvent(stream[l], res->events[n], 0));
     }
   }
+  // measured: with 2 lanes the shortest launch still wins, with 4 the least CU time does
+  k::set_gemm_sharing(lanes <= 2 ? 0.0 : (lanes - 2) * 0.5);
   const size_t work_bytes = work_layout(sh).bytes;
   char* arena = static_cast<char*>(a->stash_arena);
   int live = 0, peak = 0;
@@ -299,6 +302,7 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     if (rc) break;
     if (signals[i]) HIP_TRY(hipEventRecord(res->events[i], st));
   }
+  k::set_gemm_sharing(0.0);
   // join, also after a failed enqueue: the caller's stream ends after every side lane
   for (int l = 1; l < lanes; ++l) {
     HIP_TRY(hipEventRecord(res->events[n + l], stream[l]));

@@ -89,6 +89,10 @@ int gemm_dma(const GemmArgs& g, int config, hipStream_t stream);
 int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream);
 // -1 = automatic choice; 0, 1, 2, 4, 5, 6 = force that direct-to-LDS configuration where it applies; 3 = staged kernel only
 void set_gemm_config(int config);
+// How much of the chip the calling thread's GEMM launches share with kernels of other streams: 0 = a launch
+// runs alone (choose the tile for the shortest launch), 1 = idle CUs are always taken by other work (choose
+// for the least CU time).  The executor sets it from its lane count while it enqueues a list.
+void set_gemm_sharing(double share);
 bool attn_mfma_supported(const AttnArgs& a);
 int attn_forward_mfma(const AttnArgs& a, hipStream_t stream);
 int attn_backward_mfma(const AttnArgs& a, hipStream_t stream);
