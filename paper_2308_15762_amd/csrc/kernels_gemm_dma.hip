@@ -459,9 +459,41 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   float* stage = reinterpret_cast<float*>(smem);
   constexpr int kBandRows = WGM * 32, kVecPerRow = BN / 8, kVecs = kBandRows * kVecPerRow;
   static_assert((size_t)kBandRows * EP * 4 <= (size_t)NSTAGE * STAGE_BYTES, "epilogue band must fit the load ring");
+  // GELU epilogues: Phi (forward) or GELU' (input gradient of FC2) comes from a table of kGeluN
+  // intervals over [-8, 8) built next to the staging band with erff, read with linear interpolation
+  // (error below 1e-5, far under bf16 rounding): 8 VALU operations and one LDS read per element
+  // instead of an exponential, a reciprocal and a polynomial, which at one workgroup per CU nothing
+  // else would overlap.
+  constexpr bool kGelu = EPI == EPI_BIAS_GELU || EPI == EPI_MUL_DGELU;
+  constexpr int kGeluN = 2048;
+  constexpr int kStageBytes = ((WGM * 32 * EP * 4 + 15) / 16) * 16;
+  static_assert(!kGelu || kStageBytes + kGeluN * 8 <= NSTAGE * STAGE_BYTES, "table does not fit behind the band");
+  float2* gelu_tab = reinterpret_cast<float2*>(smem + kStageBytes);
+  auto gelu_lookup = [&](float x) {
+    const float t = fminf(fmaxf(fmaf(x, 128.f, 1024.f), 0.f), 2047.99f);
+    const int k = (int)t;
+    const float2 e = gelu_tab[k];
+    return fmaf(t - (float)k, e.y, e.x);
+  };
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     __syncthreads();  // the ring (first band) or the previous band is no longer being read
+    if constexpr (kGelu) {
+      if (i == 0) {
+        for (int k = threadIdx.x; k < kGeluN; k += NW * 64) {
+          const float x0 = -8.f + (float)k * (1.f / 128.f), x1 = -8.f + (float)(k + 1) * (1.f / 128.f);
+          float f0, f1;
+          if constexpr (EPI == EPI_BIAS_GELU) {
+            f0 = 0.5f * (1.0f + erff(x0 * 0.70710678118654752f));
+            f1 = 0.5f * (1.0f + erff(x1 * 0.70710678118654752f));
+          } else {
+            f0 = gelu_grad_f(x0);
+            f1 = gelu_grad_f(x1);
+          }
+          gelu_tab[k] = make_float2(f0, f1 - f0);
+        }
+      }
+    }
     if (MODE != 2 || khalf == 0) {
       float* dst = stage + (wm * 32 + (lane & 31)) * EP + wn * WN + 4 * (lane >> 5);
 #pragma unroll
@@ -504,12 +536,12 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
           float h[8];
           load8(p.aux + at, h);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_fast(h[e]);
+          for (int e = 0; e < 8; ++e) v[e] *= gelu_lookup(h[e]);
         }
         if constexpr (EPI == EPI_BIAS_GELU) {
           store8(p.aux_out + at, v);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] = gelu_fast(v[e]);
+          for (int e = 0; e < 8; ++e) v[e] *= gelu_lookup(v[e]);
         }
         store8(p.C + at, v);
       }
