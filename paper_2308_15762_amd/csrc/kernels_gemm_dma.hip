@@ -475,6 +475,37 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     const float2 e = gelu_tab[k];
     return fmaf(t - (float)k, e.y, e.x);
   };
+  // The operand an epilogue reads from global memory (residual, pre-activation, or the fp32 sums it
+  // accumulates into) is fetched one band ahead into registers, so that its latency runs under the
+  // staging of the band before instead of in front of every band's arithmetic.
+  constexpr int VPT = kVecs / (NW * 64);  // 8-column vectors per thread per band
+  static_assert(kVecs % (NW * 64) == 0, "band vectors divide among the threads");
+  constexpr bool kReadsAux = EPI == EPI_BIAS_RES || EPI == EPI_ADD || EPI == EPI_MUL_DGELU;
+  constexpr bool kReadsC = EPI == EPI_ACCUM_F32;
+  bf16x8 pre_aux[2][kReadsAux ? VPT : 1];
+  f32x4 pre_c[2][kReadsC ? VPT : 1][2];
+  auto where = [&](int i, int u, int& br, int& c, size_t& at, int& n) {
+    const int vi = threadIdx.x + u * NW * 64;
+    br = vi / kVecPerRow;          // band row
+    c = (vi % kVecPerRow) * 8;     // first column
+    const int m = m0 + (br >> 5) * WM + i * 32 + (br & 31);
+    n = n0 + c;
+    at = (size_t)m * p.ldc + n;
+  };
+  auto prefetch = [&](int i, int buf) {
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+      int br, c, n;
+      size_t at;
+      where(i, u, br, c, at, n);
+      if constexpr (kReadsAux) pre_aux[buf][u] = *reinterpret_cast<const bf16x8*>(p.aux + at);
+      if constexpr (kReadsC) {
+        pre_c[buf][u][0] = *reinterpret_cast<const f32x4*>(p.Cf + at);
+        pre_c[buf][u][1] = *reinterpret_cast<const f32x4*>(p.Cf + at + 4);
+      }
+    }
+  };
+  if constexpr (kReadsAux || kReadsC) prefetch(0, 0);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     __syncthreads();  // the ring (first band) or the previous band is no longer being read
@@ -506,18 +537,24 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
           *reinterpret_cast<f32x4*>(dst + j * 32 + 8 * q) = v;
         }
     }
+    if constexpr (kReadsAux || kReadsC) {
+      if (i + 1 < TM) prefetch(i + 1, (i + 1) & 1);
+    }
     __syncthreads();
-    for (int vi = threadIdx.x; vi < kVecs; vi += NW * 64) {
-      const int br = vi / kVecPerRow, c = (vi % kVecPerRow) * 8;  // band row, first column
-      const int m = m0 + (br >> 5) * WM + i * 32 + (br & 31), n = n0 + c;
-      const size_t at = (size_t)m * p.ldc + n;
+#pragma unroll
+    for (int u = 0; u < VPT; ++u) {
+      int br, c, n;
+      size_t at;
+      where(i, u, br, c, at, n);
       float v[8];
       load8(stage + br * EP + c, v);
       if constexpr (EPI == EPI_ACCUM_F32) {
         float cur[8];
-        load8(p.Cf + at, cur);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) cur[e] += v[e];
+        for (int e = 0; e < 4; ++e) {
+          cur[e] = pre_c[i & 1][u][0][e] + v[e];
+          cur[4 + e] = pre_c[i & 1][u][1][e] + v[4 + e];
+        }
         store8(p.Cf + at, cur);
       } else {
         if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
@@ -527,16 +564,12 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
           for (int e = 0; e < 8; ++e) v[e] += b[e];
         }
         if constexpr (EPI == EPI_BIAS_RES || EPI == EPI_ADD) {
-          float x[8];
-          load8(p.aux + at, x);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] += x[e];
+          for (int e = 0; e < 8; ++e) v[e] += (float)pre_aux[i & 1][u][e];
         }
         if constexpr (EPI == EPI_MUL_DGELU) {
-          float h[8];
-          load8(p.aux + at, h);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) v[e] *= gelu_lookup(h[e]);
+          for (int e = 0; e < 8; ++e) v[e] *= gelu_lookup((float)pre_aux[i & 1][u][e]);
         }
         if constexpr (EPI == EPI_BIAS_GELU) {
           store8(p.aux_out + at, v);
