@@ -95,6 +95,8 @@ __global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict_
     const int row1 = row0 + stride;
     const bool has1 = U == 2 && row1 < rows;
     float xh[U][NV][8], dy[U][NV][8];
+    bf16x8 add_raw[U][NV];    // residual addend in storage form, fetched with the other loads
+    f32x4 add_f32[U][NV][2];  // (fp32 storage)
     float2 st[U];
     st[0] = stats[row0];
     if (U == 2) st[U - 1] = has1 ? stats[row1] : make_float2(0.f, 0.f);
@@ -107,6 +109,14 @@ __global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict_
         if (c < H && (u == 0 || has1)) {
           load8(x + base + c, xh[u][i]);
           load8(dout + base + c, dy[u][i]);
+          if (addend) {
+            if constexpr (sizeof(T) == 2) {
+              add_raw[u][i] = *reinterpret_cast<const bf16x8*>(addend + base + c);
+            } else {
+              add_f32[u][i][0] = *reinterpret_cast<const f32x4*>(addend + base + c);
+              add_f32[u][i][1] = *reinterpret_cast<const f32x4*>(addend + base + c + 4);
+            }
+          }
         }
       }
     }
@@ -140,10 +150,11 @@ __global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict_
 #pragma unroll
           for (int j = 0; j < 8; ++j) o[j] = (dy[u][i][j] * gm[i][j] - c1 - xh[u][i][j] * c2) * st[u].y;
           if (addend) {
-            float a[8];
-            load8(addend + base + c, a);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) o[j] += a[j];
+            for (int j = 0; j < 8; ++j) {
+              if constexpr (sizeof(T) == 2) o[j] += (float)add_raw[u][i][j];
+              else o[j] += add_f32[u][i][j >> 2][j & 3];
+            }
           }
           store8(dz + base + c, o);
         }
