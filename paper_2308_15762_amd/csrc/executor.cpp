@@ -59,6 +59,7 @@ enum { DEP_INPUT, DEP_FORWARD, DEP_SLOT, DEP_GRADS, N_DEPS };
 struct LanePlan {
   std::vector<int32_t> lane;
   std::vector<std::array<int32_t, N_DEPS>> dep;  // task indices, -1 = none
+  std::vector<float> busy;                       // lanes the plan expects to be busy while the task runs (average, >= 1)
 };
 
 // Dependencies of each task on earlier tasks of the list, and a lane for each by list scheduling
@@ -104,6 +105,19 @@ void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank
     }
     lp.lane[i] = best;
     done[i] = lane_free[best] = best_start + (tk.kind == HANAYO_F ? 1.0 : 2.0);
+  }
+  // In the plan's own clock, how many lanes work during each task: the overlap of its interval
+  // with every task's, over its length.
+  lp.busy.assign(n, 1.0f);
+  for (size_t i = 0; i < n; ++i) {
+    const double ci = list[i].kind == HANAYO_F ? 1.0 : 2.0, si = done[i] - ci;
+    double overlap = 0.0;
+    for (size_t j = 0; j < n; ++j) {
+      const double sj = done[j] - (list[j].kind == HANAYO_F ? 1.0 : 2.0);
+      const double lo = si > sj ? si : sj, hi = done[i] < done[j] ? done[i] : done[j];
+      if (hi > lo) overlap += hi - lo;
+    }
+    lp.busy[i] = (float)(overlap / ci);
   }
 }
 
@@ -272,8 +286,6 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
       HIP_TRY(hipStreamWaitEvent(stream[l], res->events[n], 0));
     }
   }
-  // measured: with 2 lanes the shortest launch still wins, with 4 the least CU time does
-  k::set_gemm_sharing(lanes <= 2 ? 0.0 : (lanes - 2) * 0.5);
   const size_t work_bytes = work_layout(sh).bytes;
   char* arena = static_cast<char*>(a->stash_arena);
   int live = 0, peak = 0;
@@ -285,6 +297,9 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     hipStream_t st = stream[lane];
     for (int32_t j : lp.dep[i])
       if (j >= 0 && lp.lane[j] != lane) HIP_TRY(hipStreamWaitEvent(st, res->events[j], 0));
+    // Measured: next to one other busy lane the shortest GEMM launch still wins, next to three the
+    // one with the least CU time does; the plan says how busy the other lanes are during this task.
+    k::set_gemm_sharing((lp.busy[i] - 2.0f) * 0.5f);
     void* entry = arena + (pl.chunk_base[tk.chunk] + (size_t)pl.slot[i]) * entry_bytes;
     const int32_t* vl = a->valid_len ? a->valid_len[tk.mb] : nullptr;
     if (tk.kind == HANAYO_F) {
