@@ -13,8 +13,10 @@
 //   * contraction-strided operand, tile [32][cols]: cols/8 slots per row,
 //       slot' = slot ^ ((row & 3) << 2)          (the 4 rows x 4 slots one half
 //       wavefront touches in a transpose read cover all 64 banks)
-// MFMA, fragment orientation and epilogue are those of the staged kernel
-// (kernels_gemm_mfma.hip).
+// MFMA and fragment orientation are those of the staged kernel (kernels_gemm_mfma.hip).
+// The epilogue goes through LDS (the idle load ring) so that stores are whole rows; a
+// launch may carry several problems of one layout (DmaGemmGroup); workgroups take their
+// tiles in an XCD-aware order (xcd_tile).
 #include <type_traits>
 
 #include "device_util.h"
