@@ -57,14 +57,36 @@ def test_largest_chunk_shape_single_block():
     compare_grads(gpu.grad_dicts(), g_ref, tol, "gpt_4096 block")
 
 
-def test_benchmark_workload_sampled_micro_batch():
-    """Rank 0's full 64-task list of the benchmark workload; micro-batch 5's boundary outputs
-    against the oracle (chunks 1 -> 2 are the local turn-around)."""
+@pytest.fixture(scope="module")
+def benchmark_run():
+    """Rank 0's full 64-task list of the benchmark workload, run once in the launch
+    configuration bench.py times (four lanes)."""
     wl = W["gpt_1024_bf16"]
-    tol = TOL["bf16"]
-    gpu = GpuRank(wl, 0, lanes=4)          # the launch configuration bench.py times
+    gpu = GpuRank(wl, 0, lanes=4)
     peak = gpu.run()
     torch.cuda.synchronize()
+    return wl, gpu, peak
+
+
+def test_benchmark_workload_accumulated_gradients(benchmark_run):
+    """The parameter gradients of the last stage's chunk, accumulated over all 8 micro-batches by
+    backward tasks that ran on different lanes, against the oracle's accumulation of the same 8."""
+    wl, gpu, _ = benchmark_run
+    c = 2 * wl.W - 1                       # stage S-1: input and upstream gradient both come from outside
+    cfg = oracle_cfg(wl)
+    params = synth.chunk_params(wl, c)
+    grads = None
+    for m in range(wl.M):
+        _, st = OB.chunk_forward(params, synth.forward_input(wl, m, c), cfg)
+        _, grads = OB.chunk_backward(cfg, st, synth.upstream_grad(wl, m, c), grads)
+        del st
+    compare_grads(gpu.grad_dicts(c), grads, TOL["bf16"], "chunk %d over %d micro-batches" % (c, wl.M))
+
+
+def test_benchmark_workload_sampled_micro_batch(benchmark_run):
+    """Micro-batch 5's boundary outputs against the oracle (chunks 1 -> 2 are the local turn-around)."""
+    wl, gpu, peak = benchmark_run
+    tol = TOL["bf16"]
     assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0] == 16
     m = 5
     cfg = oracle_cfg(wl)
