@@ -377,7 +377,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_kernel(AttnDev p) {
 }
 
 // ======================================================================================
-// Direct-to-LDS variants for head dims 64 and 128 (DP == d): K/V (forward, dQ) or Q/dC (dK/dV)
+// Direct-to-LDS variants for head dims 64 and 128 (DP == d; 80 and 96 as partly filled DP = 128 rows): K/V (forward, dQ) or Q/dC (dK/dV)
 // tiles of 64 rows go global -> LDS with global_load_lds_dwordx4 through a ring of NST buffers,
 // so the loads of tile t+NST-1 are in flight while tile t is used; one barrier per tile.
 // LDS rows are unpadded and XOR-swizzled in 16-byte slots so that both access patterns are
@@ -433,14 +433,20 @@ struct SwTile {
   __device__ static int swz(int row) {
     return DP == 64 ? ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)) : (((row & 3) << 2) | ((row >> 2) & 3));
   }
-  // This wavefront's share of the tile whose first row is row0 (rows clamped to s-1).
+  // This wavefront's share of the tile whose first row is row0 (rows clamped to s-1).  D = the row
+  // length actually present in memory: for D < DP the slots past it are left as they are (every
+  // instruction still has active lanes, so the load counts per wavefront do not change); their
+  // contents only ever reach output columns >= D, which are not stored.
+  template <int D = DP>
   __device__ static void issue(const bf16* gbase, int ld, int row0, int s, unsigned lds_addr, int wave, int lane) {
+    static_assert(D % 16 == 0 && D <= DP && D > DP / 2, "row length for this layout");
 #pragma unroll
     for (int i = 0; i < kPerWave; ++i) {
       const int q = wave * kPerWave + i;
       const int lr = q * kRowsPerInstr + lane / SPR, sp = lane % SPR;
       const int row = min(row0 + lr, s - 1);
-      dma16(gbase, (unsigned)((row * ld + ((sp ^ swz(lr)) << 3)) * 2), lds_addr + q * 1024);
+      const int src = sp ^ swz(lr);  // the global slot that lands in LDS slot sp of this row
+      if (D == DP || src < D / 8) dma16(gbase, (unsigned)((row * ld + (src << 3)) * 2), lds_addr + q * 1024);
     }
   }
   // Per-lane byte offsets of every fragment read inside a tile, computed once per kernel.  The swizzle
@@ -482,10 +488,10 @@ struct SwTile {
   }
 };
 
-template <int DP, int NST>
+template <int DP, int NST, int D = DP>
 __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
   using Tile = SwTile<DP>;
-  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int BKV = 64, KS = D / 16, DT = (D + 31) / 32;  // D = head dim in memory, DP = LDS row layout
   constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
@@ -503,8 +509,8 @@ __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
 
   auto issue = [&](int t) {
     const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
-    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
-    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+    Tile::template issue<D>(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::template issue<D>(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
   };
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
@@ -588,6 +594,7 @@ __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int col = 32 * dt + 8 * g + 4 * half;
+        if (D % 32 != 0 && col >= D) continue;  // the last column tile of a head dim like 80 is partly padding
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[dt][4 * g + e] * inv);
@@ -745,10 +752,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
-template <int DP, int NST>
+template <int DP, int NST, int D = DP>
 __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
   using Tile = SwTile<DP>;
-  constexpr int BQ = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int BQ = 64, KS = D / 16, DT = (D + 31) / 32;  // D = head dim in memory, DP = LDS row layout
   constexpr int STAGE = 2 * Tile::kBytes + 512;  // Q tile, dC tile, 64 lse, 64 delta
   constexpr int LOADS = 2 * Tile::kPerWave + 1;  // every wavefront also issues one 4-byte-per-lane load
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -772,8 +779,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
   auto issue = [&](int t) {
     const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
     const int q0 = q_begin + t * BQ;
-    Tile::issue(base, ld3, q0, p.s, st, wave, lane);
-    Tile::issue(dcb, H, q0, p.s, st + Tile::kBytes, wave, lane);
+    Tile::template issue<D>(base, ld3, q0, p.s, st, wave, lane);
+    Tile::template issue<D>(dcb, H, q0, p.s, st + Tile::kBytes, wave, lane);
     // wavefronts 0 / 1 fetch the 64 log-sum-exp / delta values; 2 / 3 repeat them (same data, keeps
     // every wavefront's load count equal)
     const int qq = min(q0 + lane, p.s - 1);
@@ -851,6 +858,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int col = 32 * dt + 8 * g + 4 * half;
+        if (D % 32 != 0 && col >= D) continue;
         bf16x4 a, b;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -863,10 +871,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
   }
 }
 
-template <int DP, int NST>
+template <int DP, int NST, int D = DP>
 __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
   using Tile = SwTile<DP>;
-  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int BKV = 64, KS = D / 16, DT = (D + 31) / 32;  // D = head dim in memory, DP = LDS row layout
   constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
@@ -884,8 +892,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
 
   auto issue = [&](int t) {
     const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
-    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
-    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+    Tile::template issue<D>(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::template issue<D>(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
   };
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
@@ -946,6 +954,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int col = 32 * dt + 8 * g + 4 * half;
+        if (D % 32 != 0 && col >= D) continue;
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16)(dq[dt][4 * g + e] * scale);
@@ -1238,7 +1247,7 @@ int raise_lds(K kern, size_t lds) {
 
 // 32-bit lane offsets: the largest byte offset inside one sequence's rows must stay below 2^31
 bool dma_ok(const AttnArgs& a) {
-  return (a.d == 64 || a.d == 128) && (long)a.s * 3 * a.heads * a.d * 2 < (1L << 31);
+  return (a.d == 64 || a.d == 80 || a.d == 96 || a.d == 128) && (long)a.s * 3 * a.heads * a.d * 2 < (1L << 31);
 }
 
 AttnDev to_dev(const AttnArgs& a) {
@@ -1265,9 +1274,11 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
     if (a.d == 64) {
       constexpr size_t lds = 4 * 2 * SwTile<64>::kBytes;
       hipLaunchKernelGGL((attn_fwd_pipe_kernel<64, 4>), grid, block, lds, stream, p);
-    } else {
+    } else {  // head dims 80 and 96 use the 128-wide LDS rows, partly filled
       constexpr size_t lds = 2 * 2 * SwTile<128>::kBytes;
-      hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2>), grid, block, lds, stream, p);
+      if (a.d == 128) hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2>), grid, block, lds, stream, p);
+      else if (a.d == 96) hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 96>), grid, block, lds, stream, p);
+      else hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 80>), grid, block, lds, stream, p);
     }
     return check_launch("attn_fwd_dma");
   }
@@ -1291,11 +1302,18 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<64, 4>), grid, block, lds_dkv, stream, p);
       hipLaunchKernelGGL((attn_bwd_dq_pipe_kernel<64, 4>), grid, block, 4 * 2 * SwTile<64>::kBytes, stream, p);
     } else {
-      constexpr size_t lds_dkv = 2 * (2 * SwTile<128>::kBytes + 512);
-      rc = raise_lds(attn_bwd_dkv_dma_kernel<128, 2>, lds_dkv);
-      if (rc) return rc;
-      hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<128, 2>), grid, block, lds_dkv, stream, p);
-      hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<128, 2>), grid, block, 2 * 2 * SwTile<128>::kBytes, stream, p);
+      constexpr size_t lds_dkv = 2 * (2 * SwTile<128>::kBytes + 512), lds_dq = 2 * 2 * SwTile<128>::kBytes;
+#define LAUNCH_BWD(...)                                                                              \
+  do {                                                                                               \
+    rc = raise_lds(attn_bwd_dkv_dma_kernel<__VA_ARGS__>, lds_dkv);                                   \
+    if (rc) return rc;                                                                               \
+    hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<__VA_ARGS__>), grid, block, lds_dkv, stream, p);     \
+    hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<__VA_ARGS__>), grid, block, lds_dq, stream, p);       \
+  } while (0)
+      if (a.d == 128) LAUNCH_BWD(128, 2);
+      else if (a.d == 96) LAUNCH_BWD(128, 2, 96);
+      else LAUNCH_BWD(128, 2, 80);
+#undef LAUNCH_BWD
     }
     return check_launch("attn_bwd_dma");
   }

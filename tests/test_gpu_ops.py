@@ -188,6 +188,9 @@ ATTN_CASES = [
     (1, 256, 2, 128, True, False),
     (2, 200, 3, 64, True, True),
     (2, 96, 2, 80, True, False),
+    (2, 300, 3, 80, False, True),
+    (1, 264, 2, 96, True, True),
+    (2, 130, 2, 48, True, False),          # a head dim the register-staged kernels take
     (2, 77, 2, 64, False, False),
     (1, 512, 1, 64, True, False),
     (2, 320, 2, 128, False, True),
