@@ -100,7 +100,7 @@ struct AttnDev {
   float* lse;
   const bf16* dctx;
   bf16* dqkv;
-  const float* delta;
+  float* delta;  // written by attn_delta or by the pipelined dQ kernel, read by the others
   int s, heads, d, causal;
 };
 
@@ -1119,7 +1119,8 @@ store:
 }
 
 // dQ, software-pipelined in half tiles of 32 keys: the S and dP MFMAs of the next half tile are
-// issued in the block that does the exponentials, dS and the dQ MFMAs of this one.  Two register
+// issued in the block that does the exponentials, dS and the dQ MFMAs of this one.  Also forms
+// delta = rowsum(dC * C) for its rows and stores it (the dK/dV kernel is launched after this one).  Two register
 // sets alternate; the barrier that admits tile t+1 sits between the two halves of tile t.
 // Arithmetic is that of attn_bwd_dq_dma_kernel.
 template <int DP, int NST>
@@ -1153,13 +1154,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const size_t stat = ((size_t)n * p.heads + h) * p.s + q;
   const float my_lse2 = q < p.s ? p.lse[stat] * kLog2e : 0.f;
-  const float my_delta = q < p.s ? p.delta[stat] : 0.f;
   bf16x8 qf[KS], cf[KS];
+  // delta = rowsum(dC * C) of this lane's query row: each half wavefront holds half of the row's
+  // columns.  Written out for the dK/dV kernel, which runs after this one.
+  float my_delta = 0.f;
 #pragma unroll
   for (int kk = 0; kk < KS; ++kk) {
     qf[kk] = frag_global(base + (size_t)q * ld3, q < p.s, kk, lane, p.d);
     cf[kk] = frag_global(p.dctx + ((size_t)n * p.s + q) * H + h * p.d, q < p.s, kk, lane, p.d);
+    const bf16x8 of = frag_global(p.ctx + ((size_t)n * p.s + q) * H + h * p.d, q < p.s, kk, lane, p.d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) my_delta += (float)cf[kk][e] * (float)of[e];
   }
+  my_delta += __shfl_xor(my_delta, 32, 64);
+  if (q < p.s && half == 0) p.delta[stat] = my_delta;
   f32x16 dq[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dq[dt] = zero16();
@@ -1290,18 +1298,21 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
 
 int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
   if (!attn_mfma_supported(a)) return set_error(HANAYO_EUNSUPPORTED, "attn_mfma: head dim %d", a.d);
-  int rc = attn_delta(HANAYO_BF16, a, stream);
-  if (rc) return rc;
+  int rc;
   const AttnDev p = to_dev(a);
   const dim3 grid(a.heads, a.b, (a.s + 127) / 128), block(256);
+  if (dma_ok(a) && a.d == 64) {  // the dQ kernel forms delta itself and goes first
+    constexpr size_t lds_dkv = 4 * (2 * SwTile<64>::kBytes + 512);
+    rc = raise_lds(attn_bwd_dkv_pipe_kernel<64, 4>, lds_dkv);
+    if (rc) return rc;
+    hipLaunchKernelGGL((attn_bwd_dq_pipe_kernel<64, 4>), grid, block, 4 * 2 * SwTile<64>::kBytes, stream, p);
+    hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<64, 4>), grid, block, lds_dkv, stream, p);
+    return check_launch("attn_bwd_pipe");
+  }
+  rc = attn_delta(HANAYO_BF16, a, stream);
+  if (rc) return rc;
   if (dma_ok(a)) {
-    if (a.d == 64) {
-      constexpr size_t lds_dkv = 4 * (2 * SwTile<64>::kBytes + 512);
-      rc = raise_lds(attn_bwd_dkv_pipe_kernel<64, 4>, lds_dkv);
-      if (rc) return rc;
-      hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<64, 4>), grid, block, lds_dkv, stream, p);
-      hipLaunchKernelGGL((attn_bwd_dq_pipe_kernel<64, 4>), grid, block, 4 * 2 * SwTile<64>::kBytes, stream, p);
-    } else {
+    {
       constexpr size_t lds_dkv = 2 * (2 * SwTile<128>::kBytes + 512), lds_dq = 2 * 2 * SwTile<128>::kBytes;
 #define LAUNCH_BWD(...)                                                                              \
   do {                                                                                               \
