@@ -36,6 +36,24 @@ def test_lists_and_plans_bit_exact(P, W, M):
     assert rep["makespan"] == sim["makespan"]
 
 
+def test_lists_bit_exact_on_a_seeded_sweep():
+    """60 seeded (P, W, M) triples beyond the fixed grid: every rank's list and stash plan equal the oracle's."""
+    rng = np.random.default_rng(20230815)
+    seen = set()
+    while len(seen) < 60:
+        P, W, M = int(rng.integers(1, 9)), int(rng.integers(1, 5)), int(rng.integers(1, 25))
+        if (P, W, M) in seen:
+            continue
+        seen.add((P, W, M))
+        sim = S.simulate(P, W, M)
+        for r in range(P):
+            t = hn.hanayo_schedule(P, W, M, r)
+            assert as_tuples(t) == [tuple(x) for x in sim["lists"][r]], (P, W, M, r)
+            peak, per_chunk, slot = hn.hanayo_stash_plan(t, W)
+            o_peak, o_per_chunk, o_slot = S.stash_plan(sim["lists"][r], W)
+            assert (peak, list(per_chunk), list(slot)) == (o_peak, o_per_chunk, o_slot), (P, W, M, r)
+
+
 def test_placement_helpers_agree():
     for (P, W) in [(1, 1), (2, 1), (4, 2), (8, 4), (16, 2), (5, 3)]:
         for s in range(2 * W * P):
