@@ -1,0 +1,144 @@
+"""Pins for the whole-pipeline oracle (CPU only).
+
+`monolithic` is the definition of what any synchronous pipeline schedule must compute; it is
+pinned by finite differences of the scalar L = sum_m <y_m, dy_m> through ALL stages (a wrong stage
+order, a dropped stage or a gradient routed to the wrong stage fails it) and by the two-stage case
+written out with the block oracle directly.  `run_pipeline` is pinned against `monolithic`:
+bit-identical results for every (P, W, M) tried, whatever order the ranks are polled in, with the
+stash peaks of the plan; lists that violate a dependency deadlock."""
+
+import numpy as np
+import pytest
+
+from oracle import block as OB
+from oracle import pipeline as OP
+from oracle import schedule as OS
+
+
+def tiny(P, W, M, norm="pre", causal=True, padded=False, H=8, heads=2, s=4, b=2, nb=1, seed=0):
+    rng = np.random.default_rng(seed)
+    S = 2 * W * P
+    cfg = OB.BlockCfg(H, heads, 2 * H, norm=norm, causal=causal)
+    F = 2 * H
+
+    def block():
+        p = {"wqkv": rng.normal(0, 0.3, (H, 3 * H)), "bqkv": rng.normal(0, 0.3, 3 * H),
+             "wo": rng.normal(0, 0.3, (H, H)), "bo": rng.normal(0, 0.3, H),
+             "w1": rng.normal(0, 0.3, (H, F)), "b1": rng.normal(0, 0.3, F),
+             "w2": rng.normal(0, 0.3, (F, H)), "b2": rng.normal(0, 0.3, H)}
+        for k in ("ln1_g", "ln2_g"):
+            p[k] = 1.0 + 0.2 * rng.normal(size=H)
+        for k in ("ln1_b", "ln2_b"):
+            p[k] = 0.2 * rng.normal(size=H)
+        return p
+
+    params = [[block() for _ in range(nb)] for _ in range(S)]
+    xs = [rng.normal(size=(b, s, H)) for _ in range(M)]
+    dys = [rng.normal(size=(b, s, H)) for _ in range(M)]
+    lens = [rng.integers(max(1, s // 2), s + 1, size=b) for _ in range(M)] if padded else None
+    vl = (lambda m: lens[m]) if padded else None
+    return cfg, params, xs, dys, vl
+
+
+def loss(cfg, params, xs, dys, vl):
+    ys, _, _ = OP.monolithic(cfg, params, xs, dys, vl)
+    return sum(float((y * dy).sum()) for y, dy in zip(ys, dys))
+
+
+@pytest.mark.parametrize("norm,causal,padded", [("pre", True, False), ("post", False, True)])
+def test_monolithic_by_finite_differences(norm, causal, padded):
+    cfg, params, xs, dys, vl = tiny(2, 1, 2, norm, causal, padded)        # S = 4 stages
+    _, dxs, grads = OP.monolithic(cfg, params, xs, dys, vl)
+    eps = 1e-6
+    rng = np.random.default_rng(5)
+    # input gradient of micro-batch 1: every entry
+    for idx in np.ndindex(xs[1].shape):
+        keep = xs[1][idx]
+        xs[1][idx] = keep + eps
+        up = loss(cfg, params, xs, dys, vl)
+        xs[1][idx] = keep - eps
+        dn = loss(cfg, params, xs, dys, vl)
+        xs[1][idx] = keep
+        assert abs((up - dn) / (2 * eps) - dxs[1][idx]) <= 1e-6 * max(1.0, abs(dxs[1][idx]))
+    # parameters: three random entries of every tensor of every stage (summed over both micro-batches)
+    for s in range(len(params)):
+        for name, w in params[s][0].items():
+            for _ in range(3):
+                idx = tuple(int(rng.integers(0, n)) for n in w.shape)
+                keep = w[idx]
+                w[idx] = keep + eps
+                up = loss(cfg, params, xs, dys, vl)
+                w[idx] = keep - eps
+                dn = loss(cfg, params, xs, dys, vl)
+                w[idx] = keep
+                want = grads[s][0][name][idx]
+                assert abs((up - dn) / (2 * eps) - want) <= 2e-6 * max(1.0, abs(want)), (s, name, idx)
+
+
+def test_monolithic_two_stages_written_out():
+    cfg, params, xs, dys, vl = tiny(1, 1, 1)                               # S = 2
+    ys, dxs, grads = OP.monolithic(cfg, params, xs, dys, vl)
+    a, st0 = OB.chunk_forward(params[0], xs[0], cfg)
+    y, st1 = OB.chunk_forward(params[1], a, cfg)
+    g1, gr1 = OB.chunk_backward(cfg, st1, dys[0])
+    g0, gr0 = OB.chunk_backward(cfg, st0, g1)
+    assert np.array_equal(ys[0], y) and np.array_equal(dxs[0], g0)
+    for got, want in ((grads[0], gr0), (grads[1], gr1)):
+        for k in want[0]:
+            assert np.array_equal(got[0][k], want[0][k])
+
+
+def same(a, b):
+    assert len(a["ys"]) == len(b[0])
+    for x, y in zip(a["ys"], b[0]):
+        assert np.array_equal(x, y)
+    for x, y in zip(a["dxs"], b[1]):
+        assert np.array_equal(x, y)
+    for gs, hs in zip(a["grads"], b[2]):
+        for g, h in zip(gs, hs):
+            for k in h:
+                assert np.array_equal(g[k], h[k]), k
+
+
+@pytest.mark.parametrize("P,W,M", [(2, 1, 4), (1, 2, 3), (3, 2, 5), (4, 1, 4), (2, 2, 1), (4, 2, 8)])
+def test_pipeline_equals_monolithic(P, W, M):
+    """Every parameter's B tasks come in ascending micro-batch order on their rank, which is the order
+    `monolithic` sums in: the results are bit-identical, not just close."""
+    cfg, params, xs, dys, vl = tiny(P, W, M, nb=1, s=3, b=1, seed=P * 100 + W * 10 + M)
+    sim = OS.simulate(P, W, M)
+    ref = OP.monolithic(cfg, params, xs, dys, vl)
+    out = OP.run_pipeline(sim["lists"], P, W, M, cfg, params, xs, dys, vl)
+    same(out, ref)
+    assert out["peak"] == [OS.stash_plan(sim["lists"][r], W)[0] for r in range(P)]
+    # polling the ranks in another order changes the interleaving, not the result
+    out2 = OP.run_pipeline(sim["lists"], P, W, M, cfg, params, xs, dys, vl, rank_order=list(range(P))[::-1])
+    same(out2, ref)
+
+
+def test_pipeline_with_padding_and_post_ln():
+    P, W, M = 2, 2, 3
+    cfg, params, xs, dys, vl = tiny(P, W, M, "post", False, True, nb=2, seed=9)
+    sim = OS.simulate(P, W, M)
+    same(OP.run_pipeline(sim["lists"], P, W, M, cfg, params, xs, dys, vl), OP.monolithic(cfg, params, xs, dys, vl))
+
+
+def test_bad_lists_deadlock_or_are_caught():
+    P, W, M = 2, 1, 2
+    cfg, params, xs, dys, vl = tiny(P, W, M, s=2, b=1)
+    lists = [list(l) for l in OS.simulate(P, W, M)["lists"]]
+    # a backward moved in front of its own forward
+    bad = [list(l) for l in lists]
+    i = next(k for k, t in enumerate(bad[1]) if t[0] == OS.B)
+    bad[1].insert(0, bad[1].pop(i))
+    with pytest.raises(AssertionError):
+        OP.run_pipeline(bad, P, W, M, cfg, params, xs, dys, vl)
+    # a task dropped
+    bad = [list(l) for l in lists]
+    bad[0].pop()
+    with pytest.raises(AssertionError):
+        OP.run_pipeline(bad, P, W, M, cfg, params, xs, dys, vl)
+    # a task on the wrong rank
+    bad = [list(l) for l in lists]
+    bad[0][0], bad[1][0] = bad[1][0], bad[0][0]
+    with pytest.raises(AssertionError):
+        OP.run_pipeline(bad, P, W, M, cfg, params, xs, dys, vl)
