@@ -237,6 +237,60 @@ int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M,
 
 
 /* ------------------------------------------------------------------------- *
+ * The whole pipeline on one device.  Synchronous pipeline training computes
+ * what the model computes without a pipeline (the premise of the paper's
+ * comparison of schedules); hanayo_pipeline_run executes ALL P ranks' lists
+ * with true dataflow, so that this can be checked end to end, and measures the
+ * tasks; hanayo_replay turns measured task durations into the makespan and idle
+ * time the schedule would have on P devices (the paper's bubble analysis with
+ * measured T_F and T_B and T_C = 0).
+ *
+ * Tables are host arrays of device pointers.  S = 2*W*P stages; stage s belongs
+ * to rank hanayo_stage_rank(P, W, s).
+ *   weights, grads   [S]     per stage (grads are ADDED to, fp32)
+ *   x, dy            [M]     stage-0 input / gradient w.r.t. the last stage's output, per micro-batch (read)
+ *   act, grad        [M*S]   index mb*S + stage: output activation of the stage (written; act[mb][S-1] is
+ *                            the model output) and gradient w.r.t. the stage's input (written; grad[mb][0] is dL/dx)
+ *   stash_arena      [P]     one arena per rank, stash_arena_bytes[r] >= hanayo_stash_arena_bytes(lists[r], ...)
+ *   workspace                hanayo_workspace_bytes()
+ * Everything goes to hip_stream, in a dataflow merge of the lists: the ranks are polled in turn and a rank's
+ * head task runs once the task that produces its input has run.
+ * lists[r] / counts[r]: rank r's list.  HANAYO_ESTATE if a list is not its rank's task set in an order that
+ * respects the rank-local dependencies, or if the lists deadlock against each other; nothing is enqueued then.
+ * peak_seen (host [P], may be NULL): stash peak of each rank.
+ * task_ms (host [P] -> host float [counts[r]], may be NULL): if given, every task is bracketed by HIP events,
+ * the call waits for the stream to drain and writes each task's duration in milliseconds.
+ * ------------------------------------------------------------------------- */
+typedef struct hanayo_pipeline_args {
+  const hanayo_chunk_desc* desc;
+  int P, W, M;
+  const void* const* weights;
+  float* const* grads;
+  const void* const* x;
+  const void* const* dy;
+  void* const* act;
+  void* const* grad;
+  const int32_t* const* valid_len; /* host [M] -> device int32 [b], or NULL */
+  void* const* stash_arena;
+  const size_t* stash_arena_bytes;
+  void* workspace;
+  void* hip_stream;
+} hanayo_pipeline_args;
+
+int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, const hanayo_pipeline_args* args,
+                        int* peak_seen, float* const* task_ms);
+
+/*
+ * Host only.  Every rank runs its list strictly in order; a task starts when its rank is free and the task that
+ * produces its input has finished; transfers take no time.  cost[r][i] = duration of task i of rank r in any
+ * unit (NULL: forward 1, backward 2, the paper's model).  *makespan = time the last rank finishes;
+ * idle[r] (may be NULL) = makespan minus rank r's summed durations.  HANAYO_ESTATE on lists that are not the
+ * ranks' task sets or that deadlock.
+ */
+int hanayo_replay(const hanayo_task* const* lists, const size_t* counts, int P, int W, int M, const float* const* cost,
+                  double* makespan, double* idle);
+
+/* ------------------------------------------------------------------------- *
  * Single kernels of the chunk path, exported so that each can be checked and
  * timed on its own (per-kernel parity tests and roofline measurements).  Same
  * conventions as above; `dtype` is HANAYO_FP32 / HANAYO_BF16.

@@ -22,8 +22,11 @@ def _placement(P, W, stage):
     return pos if lap % 2 == 0 else P - 1 - pos
 
 
-def replay(lists, P, W, M, cost_f=1, cost_b=2):
+def replay(lists, P, W, M, cost_f=1, cost_b=2, cost=None):
     """Execute the lists; return dict(makespan, idle, start, finish, peak).
+
+    cost (optional): callable (kind, mb, stage) -> duration of that task, instead of the
+    uniform cost_f / cost_b (used to replay measured task times).
 
     Raises AssertionError on: wrong rank for a stage, a task missing or
     repeated, chunk field inconsistent with the stage, deadlock.
@@ -61,7 +64,7 @@ def replay(lists, P, W, M, cost_f=1, cost_b=2):
                     assert (F, mb, stage) in finish, "backward before its forward"
                 ready_at = 0 if dep is None else finish[dep]
                 t0 = max(free_at[r], ready_at)
-                t1 = t0 + (cost_f if kind == F else cost_b)
+                t1 = t0 + (cost(kind, mb, stage) if cost is not None else (cost_f if kind == F else cost_b))
                 start[(kind, mb, stage)] = t0
                 finish[(kind, mb, stage)] = t1
                 free_at[r] = t1
@@ -69,7 +72,8 @@ def replay(lists, P, W, M, cost_f=1, cost_b=2):
                 progressed = True
     assert all(head[r] == len(lists[r]) for r in range(P)), "deadlock"
     makespan = max(free_at)
-    busy = [sum(cost_f if k == F else cost_b for (k, _, _, _) in lst) for lst in lists]
+    busy = [sum(cost(k, m, s) if cost is not None else (cost_f if k == F else cost_b) for (k, m, _, s) in lst)
+            for lst in lists]
 
     peak = []
     for lst in lists:

@@ -328,4 +328,165 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
   return HANAYO_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// All P ranks of the pipeline on one device, with true dataflow: what synchronous pipeline training
+// computes must equal the model run without a pipeline, and running every rank's list against the
+// others' outputs is how that is checked here.  One stream; the global order is a dataflow merge of
+// the lists (poll the ranks in turn, run a rank's head task once its producer has run).
+int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, const hanayo_pipeline_args* a,
+                        int* peak_seen, float* const* task_ms) {
+  if (!lists || !counts || !a || !a->desc || !a->weights || !a->grads || !a->x || !a->dy || !a->act || !a->grad ||
+      !a->stash_arena || !a->stash_arena_bytes || !a->workspace)
+    return set_error(HANAYO_EINVAL, "pipeline: NULL argument");
+  const int P = a->P, W = a->W, M = a->M;
+  if (P < 1 || W < 1 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "pipeline: bad P=%d W=%d M=%d", P, W, M);
+  Shape sh;
+  int rc = prepare_call(a->desc, sh);
+  if (rc) return rc;
+  const int nchunk = 2 * W, S = nchunk * P;
+  std::vector<Plan> plans(P);
+  const size_t entry_bytes = stash_layout(sh).block_bytes * sh.nb;
+  for (int r = 0; r < P; ++r) {
+    if (!lists[r]) return set_error(HANAYO_EINVAL, "pipeline: rank %d has no list", r);
+    rc = validate(lists[r], counts[r], P, W, M, r);
+    if (rc) return rc;
+    rc = make_plan(lists[r], counts[r], W, plans[r]);
+    if (rc) return rc;
+    if (!a->stash_arena[r] || plans[r].entries * entry_bytes > a->stash_arena_bytes[r])
+      return set_error(HANAYO_ESTATE, "pipeline: rank %d stash arena holds %zu bytes, plan needs %zu", r,
+                       a->stash_arena[r] ? a->stash_arena_bytes[r] : (size_t)0, plans[r].entries * entry_bytes);
+  }
+  for (int s = 0; s < S; ++s)
+    if (!a->weights[s] || !a->grads[s]) return set_error(HANAYO_EINVAL, "pipeline: stage %d has no weights or grads", s);
+  for (int m = 0; m < M; ++m) {
+    if (!a->x[m] || !a->dy[m]) return set_error(HANAYO_EINVAL, "pipeline: micro-batch %d has no input or loss gradient", m);
+    for (int s = 0; s < S; ++s)
+      if (!a->act[(size_t)m * S + s] || !a->grad[(size_t)m * S + s])
+        return set_error(HANAYO_EINVAL, "pipeline: missing boundary buffer for mb %d stage %d", m, s);
+  }
+  // dataflow merge; nothing is enqueued unless every list runs to its end
+  struct Step { int rank; size_t index; };
+  std::vector<Step> order;
+  {
+    std::vector<char> fdone((size_t)M * S, 0), bdone((size_t)M * S, 0);
+    std::vector<size_t> head(P, 0);
+    bool progressed = true;
+    while (progressed) {
+      progressed = false;
+      for (int r = 0; r < P; ++r) {
+        while (head[r] < counts[r]) {
+          const hanayo_task& tk = lists[r][head[r]];
+          const size_t at = (size_t)tk.mb * S + tk.stage;
+          if (tk.kind == HANAYO_F) {
+            if (tk.stage > 0 && !fdone[at - 1]) break;
+            fdone[at] = 1;
+          } else {
+            if (!fdone[at] || ((int)tk.stage < S - 1 && !bdone[at + 1])) break;
+            bdone[at] = 1;
+          }
+          order.push_back({r, head[r]++});
+          progressed = true;
+        }
+      }
+    }
+    for (int r = 0; r < P; ++r)
+      if (head[r] != counts[r])
+        return set_error(HANAYO_ESTATE, "pipeline: the lists deadlock (rank %d stops at task %zu)", r, head[r]);
+  }
+  hipStream_t st = static_cast<hipStream_t>(a->hip_stream);
+  std::vector<hipEvent_t> ev;
+  if (task_ms) {
+    for (int r = 0; r < P; ++r)
+      if (!task_ms[r]) return set_error(HANAYO_EINVAL, "pipeline: task_ms[%d] is NULL", r);
+    ev.resize(2 * order.size());
+    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+  }
+  for (size_t k = 0; k < order.size() && !rc; ++k) {
+    const int r = order[k].rank;
+    const size_t i = order[k].index;
+    const hanayo_task& tk = lists[r][i];
+    const size_t at = (size_t)tk.mb * S + tk.stage;
+    void* entry = static_cast<char*>(a->stash_arena[r]) +
+                  (plans[r].chunk_base[tk.chunk] + (size_t)plans[r].slot[i]) * entry_bytes;
+    const int32_t* vl = a->valid_len ? a->valid_len[tk.mb] : nullptr;
+    if (task_ms) HIP_TRY(hipEventRecord(ev[2 * k], st));
+    if (tk.kind == HANAYO_F) {
+      const void* x = tk.stage == 0 ? a->x[tk.mb] : a->act[at - 1];
+      rc = chunk_forward(sh, a->weights[tk.stage], x, vl, a->act[at], entry, st);
+    } else {
+      const void* dy = (int)tk.stage == S - 1 ? a->dy[tk.mb] : a->grad[at + 1];
+      rc = chunk_backward(sh, a->weights[tk.stage], a->grads[tk.stage], dy, vl, entry, a->grad[at], a->workspace, st);
+    }
+    if (task_ms && !rc) HIP_TRY(hipEventRecord(ev[2 * k + 1], st));
+  }
+  if (task_ms) {
+    if (!rc) {
+      HIP_TRY(hipStreamSynchronize(st));
+      for (size_t k = 0; k < order.size(); ++k)
+        HIP_TRY(hipEventElapsedTime(&task_ms[order[k].rank][order[k].index], ev[2 * k], ev[2 * k + 1]));
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+  }
+  if (rc) return rc;
+  if (peak_seen)
+    for (int r = 0; r < P; ++r) peak_seen[r] = plans[r].peak;
+  return HANAYO_OK;
+}
+
+// Replay of all P lists with given task durations: every rank runs its list strictly in order and a
+// task starts when the rank is free and its producer has finished (transfers take no time).
+int hanayo_replay(const hanayo_task* const* lists, const size_t* counts, int P, int W, int M, const float* const* cost,
+                  double* makespan, double* idle) {
+  if (!lists || !counts || !makespan) return set_error(HANAYO_EINVAL, "replay: NULL argument");
+  if (P < 1 || W < 1 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "replay: bad P=%d W=%d M=%d", P, W, M);
+  const int S = 2 * W * P;
+  for (int r = 0; r < P; ++r) {
+    if (!lists[r] || (cost && !cost[r])) return set_error(HANAYO_EINVAL, "replay: rank %d has no list or costs", r);
+    const int rc = validate(lists[r], counts[r], P, W, M, r);
+    if (rc) return rc;
+  }
+  std::vector<double> ffin((size_t)M * S, -1.0), bfin((size_t)M * S, -1.0), free_at(P, 0.0), busy(P, 0.0);
+  std::vector<size_t> head(P, 0);
+  bool progressed = true;
+  while (progressed) {
+    progressed = false;
+    for (int r = 0; r < P; ++r) {
+      while (head[r] < counts[r]) {
+        const hanayo_task& tk = lists[r][head[r]];
+        const size_t at = (size_t)tk.mb * S + tk.stage;
+        double ready = 0.0;
+        if (tk.kind == HANAYO_F) {
+          if (tk.stage > 0) {
+            if (ffin[at - 1] < 0.0) break;
+            ready = ffin[at - 1];
+          }
+        } else {
+          if (ffin[at] < 0.0) break;
+          ready = ffin[at];
+          if ((int)tk.stage < S - 1) {
+            if (bfin[at + 1] < 0.0) break;
+            if (bfin[at + 1] > ready) ready = bfin[at + 1];
+          }
+        }
+        const double c = cost ? (double)cost[r][head[r]] : (tk.kind == HANAYO_F ? 1.0 : 2.0);
+        if (!(c >= 0.0)) return set_error(HANAYO_EINVAL, "replay: negative or NaN duration");
+        const double t0 = free_at[r] > ready ? free_at[r] : ready;
+        (tk.kind == HANAYO_F ? ffin : bfin)[at] = free_at[r] = t0 + c;
+        busy[r] += c;
+        ++head[r];
+        progressed = true;
+      }
+    }
+  }
+  double end = 0.0;
+  for (int r = 0; r < P; ++r) {
+    if (head[r] != counts[r]) return set_error(HANAYO_ESTATE, "replay: the lists deadlock (rank %d stops at task %zu)", r, head[r]);
+    if (free_at[r] > end) end = free_at[r];
+  }
+  *makespan = end;
+  if (idle)
+    for (int r = 0; r < P; ++r) idle[r] = end - busy[r];
+  return HANAYO_OK;
+}
+
 }  // extern "C"

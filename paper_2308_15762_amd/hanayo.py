@@ -60,6 +60,17 @@ class GemmProblem(ctypes.Structure):
                 ("colsum", ctypes.c_void_p), ("colsum_scratch", ctypes.c_void_p)]
 
 
+class PipelineArgs(ctypes.Structure):
+    _fields_ = [("desc", ctypes.POINTER(ChunkDesc)),
+                ("P", ctypes.c_int), ("W", ctypes.c_int), ("M", ctypes.c_int),
+                ("weights", ctypes.POINTER(ctypes.c_void_p)), ("grads", ctypes.POINTER(ctypes.c_void_p)),
+                ("x", ctypes.POINTER(ctypes.c_void_p)), ("dy", ctypes.POINTER(ctypes.c_void_p)),
+                ("act", ctypes.POINTER(ctypes.c_void_p)), ("grad", ctypes.POINTER(ctypes.c_void_p)),
+                ("valid_len", ctypes.POINTER(ctypes.c_void_p)),
+                ("stash_arena", ctypes.POINTER(ctypes.c_void_p)), ("stash_arena_bytes", ctypes.POINTER(ctypes.c_size_t)),
+                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p)]
+
+
 class HanayoError(RuntimeError):
     def __init__(self, code):
         self.code = code
@@ -70,7 +81,7 @@ class HanayoError(RuntimeError):
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
-           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_device_info",
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_device_info",
            "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
@@ -95,6 +106,8 @@ _lib.hanayo_stash_arena_bytes.restype = _sz
 _lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
 _lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp]
+_lib.hanayo_pipeline_run.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), _vp, _vp]
+_lib.hanayo_replay.argtypes = [_vp, _vp, _int, _int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
 _lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_op_gemm_group.argtypes = [_int, _int, _int, _int, _vp, _int, _vp]
@@ -336,6 +349,49 @@ def hanayo_executor_run(tasks, desc, P, W, M, rank, weights, grads, act_in, grad
     peak = _int()
     _check(_lib.hanayo_executor_run(tasks.ctypes.data, tasks.size, ctypes.byref(args), ctypes.byref(peak)))
     return peak.value
+
+
+def _list_tables(lists):
+    lists = [np.ascontiguousarray(t, dtype=TASK_DTYPE) for t in lists]
+    ptrs = (ctypes.c_void_p * len(lists))(*[t.ctypes.data for t in lists])
+    counts = (ctypes.c_size_t * len(lists))(*[t.size for t in lists])
+    return lists, ptrs, counts
+
+
+def hanayo_pipeline_run(lists, desc, P, W, M, weights, grads, x, dy, act, grad, valid_len, stash_arenas, workspace,
+                        stream=None, timing=False):
+    """All P ranks' lists on this device with true dataflow.  Tables are Python lists of tensors:
+    weights, grads [S]; x, dy [M]; act, grad [M*S] indexed mb*S+stage; valid_len [M] or None;
+    stash_arenas [P].  Returns (stash peaks [P], per-rank arrays of task durations in ms or None)."""
+    lists, ptrs, counts = _list_tables(lists)
+    tabs = [_table(t) for t in (weights, grads, x, dy, act, grad)]
+    vl = _table(valid_len) if valid_len is not None else None
+    arenas = _table(stash_arenas)
+    arena_bytes = (ctypes.c_size_t * P)(*[t.numel() * t.element_size() for t in stash_arenas])
+    args = PipelineArgs(ctypes.pointer(desc), P, W, M, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5], vl,
+                        arenas, arena_bytes, _ptr(workspace), stream)
+    peaks = (ctypes.c_int * P)()
+    ms = [np.zeros(t.size, dtype=np.float32) for t in lists] if timing else None
+    ms_tab = (ctypes.c_void_p * P)(*[a.ctypes.data for a in ms]) if timing else None
+    _check(_lib.hanayo_pipeline_run(ptrs, counts, ctypes.byref(args), peaks, ms_tab))
+    return list(peaks), ms
+
+
+def hanayo_replay(lists, P, W, M, cost=None):
+    """Replay of all ranks' lists with per-task durations cost[r][i] (None: forward 1, backward 2).
+    Returns (makespan, idle per rank).  Host only."""
+    lists, ptrs, counts = _list_tables(lists)
+    cost_tab = None
+    if cost is not None:
+        cost = [np.ascontiguousarray(c, dtype=np.float32) for c in cost]
+        for c, t in zip(cost, lists):
+            if c.size != t.size:
+                raise HanayoError(EINVAL)
+        cost_tab = (ctypes.c_void_p * P)(*[c.ctypes.data for c in cost])
+    makespan = ctypes.c_double()
+    idle = np.zeros(P, dtype=np.float64)
+    _check(_lib.hanayo_replay(ptrs, counts, P, W, M, cost_tab, ctypes.byref(makespan), idle.ctypes.data))
+    return makespan.value, idle
 
 
 # ------------------------------------------------------------------ packing (layout marshalling only)

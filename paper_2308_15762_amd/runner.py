@@ -109,3 +109,44 @@ class GpuRank:
 
     def grad_dicts(self, chunk):
         return hn.unpack_params(self.desc, self.grads[chunk].cpu().numpy(), self.params[chunk])
+
+
+class GpuPipeline:
+    """Device state of ALL ranks of a workload on one GPU: per-stage weights/grads, model inputs and loss
+    gradients per micro-batch, every stage-boundary buffer, one stash arena per rank; runs the P task
+    lists with true dataflow through hanayo_pipeline_run."""
+
+    def __init__(self, wl):
+        self.wl = wl
+        self.desc = hn.desc_for(wl)
+        P, W, M = wl.P, wl.W, wl.M
+        self.S = S = 2 * W * P
+        self.lists = [hn.hanayo_schedule(P, W, M, r) for r in range(P)]
+        self.params = [synth.stage_params(wl, s) for s in range(S)]
+        self.weights = [dev(hn.pack_params(self.desc, p), wl.dtype) for p in self.params]
+        self.grads = [torch.zeros(hn.hanayo_grad_bytes(self.desc) // 4, dtype=torch.float32, device="cuda")
+                      for _ in range(S)]
+        self.work = dev_bytes(hn.hanayo_workspace_bytes(self.desc))
+        self.arenas = [dev_bytes(hn.hanayo_stash_arena_bytes(t, W, self.desc)) for t in self.lists]
+        tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        shape = (wl.mb, wl.seq, wl.hidden)
+        self.x = [dev(synth.model_input(wl, m), wl.dtype) for m in range(M)]
+        self.dy = [dev(synth.loss_grad(wl, m), wl.dtype) for m in range(M)]
+        self.act = [torch.empty(shape, dtype=tdt, device="cuda") for _ in range(M * S)]
+        self.grad = [torch.empty(shape, dtype=tdt, device="cuda") for _ in range(M * S)]
+        self.valid_len = None
+        if wl.valid_len_range is not None:
+            self.valid_len = [torch.from_numpy(synth.valid_lengths(wl, m)).cuda() for m in range(M)]
+
+    def zero_grads(self):
+        for g in self.grads:
+            g.zero_()
+
+    def run(self, lists=None, timing=False, stream=None):
+        wl = self.wl
+        return hn.hanayo_pipeline_run(self.lists if lists is None else lists, self.desc, wl.P, wl.W, wl.M,
+                                      self.weights, self.grads, self.x, self.dy, self.act, self.grad, self.valid_len,
+                                      self.arenas, self.work, stream, timing)
+
+    def grad_dicts(self, stage):
+        return hn.unpack_params(self.desc, self.grads[stage].cpu().numpy(), self.params[stage])

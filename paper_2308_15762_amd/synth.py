@@ -110,6 +110,22 @@ def chunk_params(wl, chunk, ln_random=False):
     return [block_params(rng, wl.hidden, wl.ffn, wl.dtype, ln_random) for _ in range(wl.n_blocks)]
 
 
+def stage_params(wl, stage, ln_random=False):
+    """Parameters of global stage `stage` (whole-pipeline runs): list of n_blocks dicts."""
+    rng = rng_for(wl.seed, 4, stage)
+    return [block_params(rng, wl.hidden, wl.ffn, wl.dtype, ln_random) for _ in range(wl.n_blocks)]
+
+
+def model_input(wl, mb):
+    """Input of stage 0 for micro-batch `mb` (whole-pipeline runs)."""
+    return activation(wl, 5, mb, 0)
+
+
+def loss_grad(wl, mb):
+    """Gradient of the loss w.r.t. the last stage's output for micro-batch `mb` (whole-pipeline runs)."""
+    return activation(wl, 6, mb, 0)
+
+
 def activation(wl, tag, mb, chunk):
     """N(0,1) tensor [mb_size, seq, hidden]; tag 2 = forward input, 3 = upstream gradient."""
     rng = rng_for(wl.seed, tag, mb, chunk)

@@ -1,0 +1,94 @@
+"""GPU parity of hanayo_pipeline_run: ALL ranks' task lists executed on one device with true
+dataflow, against the oracle's non-pipelined model (`oracle.pipeline.monolithic`): model outputs,
+input gradients and every stage's accumulated parameter gradients.  This is the end-to-end statement
+that the wave schedule computes what the model computes."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import pipeline as OP
+from oracle import schedule as OS
+from paper_2308_15762_amd import hanayo as hn
+from paper_2308_15762_amd import synth
+from paper_2308_15762_amd.runner import GpuPipeline
+from helpers import TOL, compare_grads, host, nerr, oracle_cfg
+from test_host_pipeline import deadlocking_lists
+
+pytestmark = pytest.mark.gpu
+
+W = synth.WORKLOADS
+
+CASES = {
+    # BASELINE configuration 1 in full: both ranks, 4 stages, 4 micro-batches, fp32
+    "tiny_gpt_fp32": W["tiny_gpt_fp32"],
+    # the other configurations' pipelines on reduced chunk shapes
+    "gpt_1024_small": W["gpt_1024_bf16"].scaled(hidden=128, heads=2, ffn=512, seq=128, mb=1),            # 16 stages
+    "bert_small": W["bert_1024_bf16"].scaled(hidden=128, heads=2, ffn=512, seq=96, mb=2, n_blocks=1, M=6,
+                                             valid_len_range=(48, 96)),                                   # post-LN, padding
+    "wave4_small": W["gpt_2560_wave4_bf16"].scaled(hidden=160, heads=2, ffn=640, seq=64, mb=1, P=3, M=5),   # d = 80, 24 stages
+}
+
+
+def reference(wl):
+    S = 2 * wl.W * wl.P
+    params = [synth.stage_params(wl, s) for s in range(S)]
+    xs = [synth.model_input(wl, m) for m in range(wl.M)]
+    dys = [synth.loss_grad(wl, m) for m in range(wl.M)]
+    vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
+    return OP.monolithic(oracle_cfg(wl), params, xs, dys, vl)
+
+
+def depth_tolerance(wl):
+    """The stated tolerance (1e-4 fp32, 2e-2 bf16) is for one chunk call, a few blocks deep.  Here a
+    tensor has passed through every block of the model: 2 W P n_blocks of them.  The roundings of
+    successive blocks are independent, so the error grows like the square root of the depth; the
+    bound is the stated one up to 4 blocks (the configurations' chunks have 1 to 3) and scales with
+    sqrt(depth / 4) beyond."""
+    depth = 2 * wl.W * wl.P * wl.n_blocks
+    return TOL[wl.dtype] * max(1.0, (depth / 4.0) ** 0.5)
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_pipeline_matches_the_model_without_a_pipeline(name):
+    wl = CASES[name]
+    tol = depth_tolerance(wl)
+    gpu = GpuPipeline(wl)
+    peaks, ms = gpu.run(timing=True)
+    torch.cuda.synchronize()
+    assert peaks == [OS.stash_plan(OS.schedule(wl.P, wl.W, wl.M, r), wl.W)[0] for r in range(wl.P)]
+    assert all((m > 0).all() for m in ms)
+    ys, dxs, grads = reference(wl)
+    S = gpu.S
+    for m in range(wl.M):
+        e = nerr(host(gpu.act[m * S + S - 1]), ys[m])
+        assert e <= tol, "output of micro-batch %d: %.3g" % (m, e)
+        e = nerr(host(gpu.grad[m * S]), dxs[m])
+        assert e <= tol, "input gradient of micro-batch %d: %.3g" % (m, e)
+    for s in range(S):
+        compare_grads(gpu.grad_dicts(s), grads[s], tol, "%s stage %d" % (name, s))
+    # an untimed second run over the same buffers gives the same boundary tensors
+    out = gpu.act[S - 1].clone()
+    gpu.zero_grads()
+    gpu.run()
+    torch.cuda.synchronize()
+    assert torch.equal(out, gpu.act[S - 1])
+
+
+def test_pipeline_rejects_deadlocking_lists_without_running():
+    P, Wv, M, bad = deadlocking_lists()
+    wl = W["tiny_gpt_fp32"]
+    assert (wl.P, wl.W, wl.M) == (P, Wv, M)
+    gpu = GpuPipeline(wl)
+    for t in gpu.act + gpu.grad:
+        t.fill_(7.0)
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run(lists=bad)
+    assert e.value.code == hn.ESTATE
+    torch.cuda.synchronize()
+    assert all(bool((t == 7.0).all()) for t in gpu.act + gpu.grad)
+    small = gpu.arenas[0]
+    gpu.arenas[0] = small[: small.numel() // 2]
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run()
+    assert e.value.code == hn.ESTATE
