@@ -1,0 +1,89 @@
+#!/usr/bin/env python3
+"""Emulated bubble ratio of a wave pipeline from task times measured on one GPU.
+
+All P ranks' task lists of a workload are executed on this GPU with true dataflow
+(hanayo_pipeline_run), every task bracketed by HIP events; the measured durations are
+then replayed as P devices would run them (hanayo_replay: each rank in its own order,
+a task starts when its producer has finished, transfers take no time).  That is the
+paper's bubble analysis with measured T_F and T_B instead of the assumed T_B = 2 T_F,
+and T_C = 0.  Printed next to it: the same schedule under the assumed costs, and the
+closed form the paper gives for one unit of P micro-batches.
+
+    python -m paper_2308_15762_amd.bubble --workload gpt_1024_bf16 [--M 4] [--repeat 3]
+
+Prints one JSON line.
+"""
+
+import argparse
+import json
+import sys
+
+import numpy as np
+
+
+def printed_ratio(P, W):
+    """The paper's simplified bubble ratio for M = P micro-batches, T_B = 2 T_F, T_C = 0."""
+    return (2.0 * P - 2.0) / (3.0 * P * W + P - 1.0)
+
+
+def consistent_ratio(P, W):
+    """Idle (P - 1) T_B / W per rank (the numerator of the paper's bubble equation) over idle plus the
+    rank's own compute P (T_F + T_B), with T_B = 2 T_F: the ratio that equation gives once numerator and
+    denominator use the same idle time."""
+    return (2.0 * P - 2.0) / (3.0 * P * W + 2.0 * P - 2.0)
+
+
+def measure(wl, repeat=3):
+    """Task durations [rank][task] in ms: the median over `repeat` timed runs after one warm-up."""
+    import torch
+    from .runner import GpuPipeline
+    gpu = GpuPipeline(wl)
+    gpu.run()
+    torch.cuda.synchronize()
+    runs = []
+    for _ in range(repeat):
+        gpu.zero_grads()
+        _, ms = gpu.run(timing=True)
+        runs.append(ms)
+    return gpu.lists, [np.median(np.stack([r[k] for r in runs]), axis=0) for k in range(wl.P)]
+
+
+def report(wl, repeat=3):
+    from . import hanayo as hn
+    P, W, M = wl.P, wl.W, wl.M
+    lists, ms = measure(wl, repeat)
+    makespan, idle = hn.hanayo_replay(lists, P, W, M, ms)
+    unit_makespan, unit_idle = hn.hanayo_replay(lists, P, W, M)
+    f = np.concatenate([m[t["kind"] == 0] for m, t in zip(ms, lists)])
+    b = np.concatenate([m[t["kind"] == 1] for m, t in zip(ms, lists)])
+    out = {
+        "workload": wl.name, "P": P, "W": W, "M": M, "stages": 2 * W * P,
+        "t_f_ms": float(f.mean()), "t_b_ms": float(b.mean()), "t_b_over_t_f": float(b.mean() / f.mean()),
+        "makespan_ms": makespan, "idle_ms_per_rank": [float(v) for v in idle],
+        "bubble_ratio_measured_times": float(np.mean(idle) / makespan),
+        "bubble_ratio_assumed_costs": float(np.mean(unit_idle) / unit_makespan),
+        "bubble_ratio_paper_closed_form_M_eq_P": printed_ratio(P, W),
+        "bubble_ratio_numerator_form_M_eq_P": consistent_ratio(P, W),
+        "one_gpu_total_ms": float(sum(m.sum() for m in ms)),
+    }
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="gpt_1024_bf16")
+    ap.add_argument("--M", type=int, default=None, help="micro-batches (default: the workload's)")
+    ap.add_argument("--repeat", type=int, default=3)
+    args = ap.parse_args()
+    import torch
+    from . import synth
+    if not torch.cuda.is_available():
+        sys.exit("bubble: no GPU")
+    wl = synth.WORKLOADS[args.workload]
+    if args.M is not None:
+        wl = wl.scaled(M=args.M)
+    print(json.dumps(report(wl, args.repeat)))
+
+
+if __name__ == "__main__":
+    main()

@@ -92,3 +92,16 @@ def test_pipeline_rejects_deadlocking_lists_without_running():
     with pytest.raises(hn.HanayoError) as e:
         gpu.run()
     assert e.value.code == hn.ESTATE
+
+
+def test_bubble_report_on_a_small_pipeline():
+    """Measured task times replayed: a ratio between 0 and 1, close to the schedule's under the assumed
+    costs when T_B / T_F is close to 2, and the one-GPU total equal to the sum of the tasks."""
+    from paper_2308_15762_amd import bubble
+    wl = W["gpt_1024_bf16"].scaled(hidden=256, heads=4, ffn=1024, seq=256, mb=2, M=4)
+    rep = bubble.report(wl, repeat=2)
+    assert rep["stages"] == 16 and rep["t_f_ms"] > 0 and rep["t_b_ms"] > rep["t_f_ms"]
+    assert 0.0 < rep["bubble_ratio_measured_times"] < 1.0
+    assert abs(rep["bubble_ratio_assumed_costs"] - 13.0 / 61.0) < 1e-12          # idle 13 of makespan 61 (P=4, W=2, M=4)
+    assert rep["makespan_ms"] < rep["one_gpu_total_ms"]
+    assert abs(rep["bubble_ratio_paper_closed_form_M_eq_P"] - 6.0 / 27.0) < 1e-12
