@@ -5,6 +5,9 @@
 // buffers in HBM; the turn-around between two stages that share this rank is a
 // pointer hand-off.
 //
+// hanayo_pipeline_run (end of the file) runs ALL ranks' lists on one device with true dataflow;
+// hanayo_replay turns task durations into the makespan and idle time P devices would see.
+//
 // With one lane everything goes to the caller's stream in list order.  With
 // more, tasks that do not depend on each other run side by side on HIP streams
 // of the library's own (lane 0 is the caller's stream): a GEMM's store-heavy

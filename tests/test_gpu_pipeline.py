@@ -105,3 +105,26 @@ def test_bubble_report_on_a_small_pipeline():
     assert abs(rep["bubble_ratio_assumed_costs"] - 13.0 / 61.0) < 1e-12          # idle 13 of makespan 61 (P=4, W=2, M=4)
     assert rep["makespan_ms"] < rep["one_gpu_total_ms"]
     assert abs(rep["bubble_ratio_paper_closed_form_M_eq_P"] - 6.0 / 27.0) < 1e-12
+
+
+def test_full_size_pipeline_sampled_output():
+    """The benchmark workload's whole pipeline (4 ranks, 16 stages of 2 blocks, 8 micro-batches, full
+    chunk shapes) on one GPU: the model output of one sampled micro-batch against the oracle's forward
+    chain through all 16 stages; every gradient buffer finite and non-trivial."""
+    from oracle import block as OB
+    wl = W["gpt_1024_bf16"]
+    gpu = GpuPipeline(wl)
+    peaks, _ = gpu.run()
+    torch.cuda.synchronize()
+    assert peaks == [16, 14, 16, 16]
+    S, m = gpu.S, 3
+    cfg = oracle_cfg(wl)
+    a = synth.model_input(wl, m)
+    for s in range(S):
+        a, _ = OB.chunk_forward(synth.stage_params(wl, s), a, cfg, dtype=np.float32)
+    e = nerr(host(gpu.act[m * S + S - 1]), a)
+    assert e <= depth_tolerance(wl), "model output of micro-batch %d: %.3g" % (m, e)
+    for g in gpu.grads:
+        assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
+    for mm in range(wl.M):
+        assert bool(torch.isfinite(gpu.grad[mm * S].float()).all())
