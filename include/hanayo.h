@@ -237,6 +237,48 @@ int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M,
 
 
 /* ------------------------------------------------------------------------- *
+ * Action lists (runtime section of the paper): the scheduler's output at the
+ * granularity the workers interpret, i.e. compute actions carrying the local
+ * module (chunk) index plus send / receive actions carrying the target rank.
+ * Rank r's action list is its task list with, around every task, the
+ * communication it needs: a receive immediately in front of a compute whose
+ * input is produced on another rank, a send immediately behind a compute whose
+ * output is consumed on another rank.  The turns of the wave (two consecutive
+ * stages on one rank) have no communication actions.  For a communication
+ * action `stage`, `chunk` and `mb` are those of the local compute it serves and
+ * `peer` is the other rank (always a neighbour); for a compute action `peer` is
+ * the rank itself.  Same calling convention as hanayo_schedule (*n receives the
+ * count, HANAYO_EBUFSIZE if cap is too small).
+ * ------------------------------------------------------------------------- */
+enum { HANAYO_SEND_ACT = 2, HANAYO_RECV_ACT = 3, HANAYO_SEND_GRAD = 4, HANAYO_RECV_GRAD = 5 };
+
+typedef struct hanayo_action {
+  uint8_t kind;   /* HANAYO_F, HANAYO_B or one of the four above */
+  uint8_t chunk;
+  uint16_t peer;
+  uint32_t mb;
+  uint32_t stage;
+} hanayo_action;  /* 12 bytes, no padding */
+
+int hanayo_actions(int P, int W, int M, int rank, hanayo_action* out, size_t cap, size_t* n);
+
+/*
+ * Host only: the P interpreters simulated.  Sends are asynchronous (no time on the sender); a transfer starts
+ * once the message has been sent AND its receive has been posted, and takes t_c; a rank waits at a receive until
+ * the message has arrived.  prefetch = 0: a receive is posted when the interpreter reaches it.  prefetch = 1 (the
+ * paper's look-ahead): before starting a compute action the interpreter posts the receive that feeds the
+ * following compute action.  cost[r][i] (may be NULL: forward t_f, backward t_b) = duration of action i of rank r
+ * if it is a compute action (entries of communication actions are ignored).
+ * *makespan = time the last rank finishes; idle[r], waited[r] (may be NULL) = makespan minus rank r's compute
+ * time, and the time rank r spent blocked in receives.  HANAYO_ESTATE if the compute actions of a list are not
+ * its rank's task set in a valid order, a communication action does not belong to the compute next to it, or
+ * the lists deadlock.
+ */
+int hanayo_replay_actions(const hanayo_action* const* lists, const size_t* counts, int P, int W, int M, double t_f,
+                          double t_b, double t_c, int prefetch, const float* const* cost, double* makespan,
+                          double* idle, double* waited);
+
+/* ------------------------------------------------------------------------- *
  * The whole pipeline on one device.  Synchronous pipeline training computes
  * what the model computes without a pipeline (the premise of the paper's
  * comparison of schedules); hanayo_pipeline_run executes ALL P ranks' lists

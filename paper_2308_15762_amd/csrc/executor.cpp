@@ -492,4 +492,126 @@ int hanayo_replay(const hanayo_task* const* lists, const size_t* counts, int P, 
   return HANAYO_OK;
 }
 
+int hanayo_replay_actions(const hanayo_action* const* lists, const size_t* counts, int P, int W, int M, double t_f,
+                          double t_b, double t_c, int prefetch, const float* const* cost, double* makespan,
+                          double* idle, double* waited) {
+  if (!lists || !counts || !makespan) return set_error(HANAYO_EINVAL, "replay_actions: NULL argument");
+  if (P < 1 || W < 1 || M < 1 || 2 * W > 255 || !(t_f >= 0.0) || !(t_b >= 0.0) || !(t_c >= 0.0))
+    return set_error(HANAYO_EINVAL, "replay_actions: bad P=%d W=%d M=%d or negative time", P, W, M);
+  const int S = 2 * W * P;
+  // structure: the compute actions are the rank's tasks; each communication action belongs to its neighbour
+  for (int r = 0; r < P; ++r) {
+    if (!lists[r] || (cost && !cost[r])) return set_error(HANAYO_EINVAL, "replay_actions: rank %d has no list or costs", r);
+    std::vector<hanayo_task> tasks;
+    for (size_t i = 0; i < counts[r]; ++i) {
+      const hanayo_action& a = lists[r][i];
+      if (a.kind <= HANAYO_B) {
+        tasks.push_back({a.kind, a.chunk, 0, a.mb, a.stage});
+        continue;
+      }
+      if (a.kind > HANAYO_RECV_GRAD) return set_error(HANAYO_ESTATE, "replay_actions: rank %d action %zu: kind %u", r, i, a.kind);
+      const bool is_recv = a.kind == HANAYO_RECV_ACT || a.kind == HANAYO_RECV_GRAD;
+      const bool is_act = a.kind == HANAYO_SEND_ACT || a.kind == HANAYO_RECV_ACT;
+      const size_t j = is_recv ? i + 1 : i - 1;  // the compute it serves
+      if ((is_recv && i + 1 >= counts[r]) || (!is_recv && i == 0) || lists[r][j].kind != (is_act ? HANAYO_F : HANAYO_B) ||
+          lists[r][j].mb != a.mb || lists[r][j].stage != a.stage)
+        return set_error(HANAYO_ESTATE, "replay_actions: rank %d action %zu is not next to the compute it serves", r, i);
+      const int other = (int)a.stage + ((is_act == is_recv) ? -1 : 1);  // act recv / grad send: stage - 1
+      if (other < 0 || other >= S || stage_rank(P, other) != (int)a.peer || (int)a.peer == r)
+        return set_error(HANAYO_ESTATE, "replay_actions: rank %d action %zu: wrong peer", r, i);
+    }
+    const int rc = validate(tasks.data(), tasks.size(), P, W, M, r);
+    if (rc) return rc;
+  }
+  // message id: activations and gradients of (mb, producing stage)
+  auto message = [&](const hanayo_action& a) -> size_t {
+    const bool is_act = a.kind == HANAYO_SEND_ACT || a.kind == HANAYO_RECV_ACT;
+    const bool is_recv = a.kind == HANAYO_RECV_ACT || a.kind == HANAYO_RECV_GRAD;
+    const int producer = (int)a.stage + (is_recv ? (is_act ? -1 : 1) : 0);
+    return ((size_t)(is_act ? 0 : 1) * M + a.mb) * S + producer;
+  };
+  const size_t n_msg = (size_t)2 * M * S;
+  std::vector<double> sent(n_msg, -1.0), posted(n_msg, -1.0), arrived(n_msg, -1.0);
+  std::vector<double> ffin((size_t)M * S, -1.0), bfin((size_t)M * S, -1.0), now(P, 0.0), busy(P, 0.0), blocked(P, 0.0);
+  std::vector<size_t> head(P, 0);
+  auto try_arrive = [&](size_t m) {
+    if (sent[m] >= 0.0 && posted[m] >= 0.0 && arrived[m] < 0.0) arrived[m] = (sent[m] > posted[m] ? sent[m] : posted[m]) + t_c;
+  };
+  bool progressed = true;
+  while (progressed) {
+    progressed = false;
+    for (int r = 0; r < P; ++r) {
+      while (head[r] < counts[r]) {
+        const size_t i = head[r];
+        const hanayo_action& a = lists[r][i];
+        const size_t at = (size_t)a.mb * S + a.stage;
+        if (a.kind <= HANAYO_B) {
+          double ready = now[r];
+          if (a.kind == HANAYO_F) {
+            if (a.stage > 0 && stage_rank(P, (int)a.stage - 1) == r) {
+              if (ffin[at - 1] < 0.0) break;
+              if (ffin[at - 1] > ready) ready = ffin[at - 1];
+            }
+          } else {
+            if (ffin[at] < 0.0) break;
+            if (ffin[at] > ready) ready = ffin[at];
+            if ((int)a.stage < S - 1 && stage_rank(P, (int)a.stage + 1) == r) {
+              if (bfin[at + 1] < 0.0) break;
+              if (bfin[at + 1] > ready) ready = bfin[at + 1];
+            }
+          }
+          if (prefetch) {  // look ahead to the receive of the following compute action
+            for (size_t j = i + 1; j < counts[r] && lists[r][j].kind > HANAYO_B; ++j) {
+              const hanayo_action& nx = lists[r][j];
+              if (nx.kind == HANAYO_RECV_ACT || nx.kind == HANAYO_RECV_GRAD) {
+                const size_t m = message(nx);
+                if (posted[m] < 0.0) {
+                  posted[m] = now[r];
+                  try_arrive(m);
+                }
+                break;
+              }
+            }
+          }
+          const double c = cost ? (double)cost[r][i] : (a.kind == HANAYO_F ? t_f : t_b);
+          if (!(c >= 0.0)) return set_error(HANAYO_EINVAL, "replay_actions: negative or NaN duration");
+          now[r] = ready + c;
+          busy[r] += c;
+          (a.kind == HANAYO_F ? ffin : bfin)[at] = now[r];
+        } else if (a.kind == HANAYO_SEND_ACT || a.kind == HANAYO_SEND_GRAD) {
+          const size_t m = message(a);
+          if (sent[m] >= 0.0) return set_error(HANAYO_ESTATE, "replay_actions: message sent twice");
+          sent[m] = now[r];
+          try_arrive(m);
+        } else {
+          const size_t m = message(a);
+          if (posted[m] < 0.0) {
+            posted[m] = now[r];
+            try_arrive(m);
+          }
+          if (arrived[m] < 0.0) break;  // the peer has not sent yet
+          if (arrived[m] > now[r]) {
+            blocked[r] += arrived[m] - now[r];
+            now[r] = arrived[m];
+          }
+        }
+        ++head[r];
+        progressed = true;
+      }
+    }
+  }
+  double end = 0.0;
+  for (int r = 0; r < P; ++r) {
+    if (head[r] != counts[r])
+      return set_error(HANAYO_ESTATE, "replay_actions: the lists deadlock (rank %d stops at action %zu)", r, head[r]);
+    if (now[r] > end) end = now[r];
+  }
+  *makespan = end;
+  for (int r = 0; r < P; ++r) {
+    if (idle) idle[r] = end - busy[r];
+    if (waited) waited[r] = blocked[r];
+  }
+  return HANAYO_OK;
+}
+
 }  // extern "C"

@@ -193,6 +193,45 @@ int hanayo_schedule(int P, int W, int M, int rank, hanayo_task* out, size_t cap,
   return HANAYO_OK;
 }
 
+// The rank's list at the granularity of the paper's runtime section: its tasks, each with the
+// communication it needs around it (a receive in front of a compute whose input comes from another
+// rank, a send behind a compute whose output goes to another rank).
+int hanayo_actions(int P, int W, int M, int rank, hanayo_action* out, size_t cap, size_t* n) {
+  if (!n) return hanayo::set_error(HANAYO_EINVAL, "actions: n is NULL");
+  if (P < 1 || W < 1 || M < 1 || rank < 0 || rank >= P || 2 * W > 255 || (cap && !out))
+    return hanayo::set_error(HANAYO_EINVAL, "actions: bad argument P=%d W=%d M=%d rank=%d", P, W, M, rank);
+  std::vector<hanayo_task> tasks;
+  hanayo::generate(P, W, M, rank, tasks);
+  const int S = 2 * W * P;
+  std::vector<hanayo_action> v;
+  v.reserve(tasks.size() * 3);
+  for (const hanayo_task& t : tasks) {
+    const int stage = (int)t.stage;
+    // the stage whose output this task reads, and the stage that reads this task's output
+    const int from = t.kind == HANAYO_F ? stage - 1 : stage + 1, to = t.kind == HANAYO_F ? stage + 1 : stage - 1;
+    const int src = (from >= 0 && from < S) ? hanayo::stage_rank(P, from) : rank;
+    const int dst = (to >= 0 && to < S) ? hanayo::stage_rank(P, to) : rank;
+    hanayo_action a = {t.kind, t.chunk, (uint16_t)rank, t.mb, t.stage};
+    if (src != rank) {
+      hanayo_action r = a;
+      r.kind = t.kind == HANAYO_F ? HANAYO_RECV_ACT : HANAYO_RECV_GRAD;
+      r.peer = (uint16_t)src;
+      v.push_back(r);
+    }
+    v.push_back(a);
+    if (dst != rank) {
+      hanayo_action snd = a;
+      snd.kind = t.kind == HANAYO_F ? HANAYO_SEND_ACT : HANAYO_SEND_GRAD;
+      snd.peer = (uint16_t)dst;
+      v.push_back(snd);
+    }
+  }
+  *n = v.size();
+  if (cap < v.size()) return hanayo::set_error(HANAYO_EBUFSIZE, "actions: need %zu records, capacity %zu", v.size(), cap);
+  std::memcpy(out, v.data(), v.size() * sizeof(hanayo_action));
+  return HANAYO_OK;
+}
+
 int hanayo_stash_plan(const hanayo_task* list, size_t n, int W, int* peak_total, int* per_chunk, int32_t* slot) {
   if ((!list && n) || W < 1 || 2 * W > 255) return hanayo::set_error(HANAYO_EINVAL, "stash_plan: bad argument");
   return hanayo::plan_stash(list, n, W, peak_total, per_chunk, slot);

@@ -81,7 +81,7 @@ class HanayoError(RuntimeError):
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
-           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_device_info",
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_device_info",
            "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
@@ -108,6 +108,9 @@ _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.
 _lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp]
 _lib.hanayo_pipeline_run.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), _vp, _vp]
 _lib.hanayo_replay.argtypes = [_vp, _vp, _int, _int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
+_lib.hanayo_actions.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
+_lib.hanayo_replay_actions.argtypes = [_vp, _vp, _int, _int, _int, ctypes.c_double, ctypes.c_double, ctypes.c_double, _int,
+                                       _vp, ctypes.POINTER(ctypes.c_double), _vp, _vp]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
 _lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_op_gemm_group.argtypes = [_int, _int, _int, _int, _vp, _int, _vp]
@@ -375,6 +378,40 @@ def hanayo_pipeline_run(lists, desc, P, W, M, weights, grads, x, dy, act, grad, 
     ms_tab = (ctypes.c_void_p * P)(*[a.ctypes.data for a in ms]) if timing else None
     _check(_lib.hanayo_pipeline_run(ptrs, counts, ctypes.byref(args), peaks, ms_tab))
     return list(peaks), ms
+
+
+ACTION_DTYPE = np.dtype([("kind", np.uint8), ("chunk", np.uint8), ("peer", np.uint16), ("mb", np.uint32),
+                         ("stage", np.uint32)])
+F, B, SEND_ACT, RECV_ACT, SEND_GRAD, RECV_GRAD = range(6)
+
+
+def hanayo_actions(P, W, M, rank):
+    """Rank's action list (compute + send / receive actions) as a structured array."""
+    n = _sz()
+    rc = _lib.hanayo_actions(P, W, M, rank, None, 0, ctypes.byref(n))
+    if rc != EBUFSIZE:
+        _check(rc if rc != OK else ESTATE)
+    out = np.zeros(n.value, dtype=ACTION_DTYPE)
+    _check(_lib.hanayo_actions(P, W, M, rank, out.ctypes.data, out.size, ctypes.byref(n)))
+    return out
+
+
+def hanayo_replay_actions(lists, P, W, M, t_f=1.0, t_b=2.0, t_c=0.0, prefetch=False, cost=None):
+    """The P interpreters simulated (see include/hanayo.h).  Returns (makespan, idle [P], waited [P])."""
+    lists = [np.ascontiguousarray(t, dtype=ACTION_DTYPE) for t in lists]
+    ptrs = (ctypes.c_void_p * len(lists))(*[t.ctypes.data for t in lists])
+    counts = (ctypes.c_size_t * len(lists))(*[t.size for t in lists])
+    cost_tab = None
+    if cost is not None:
+        cost = [np.ascontiguousarray(c, dtype=np.float32) for c in cost]
+        if any(c.size != t.size for c, t in zip(cost, lists)):
+            raise HanayoError(EINVAL)
+        cost_tab = (ctypes.c_void_p * P)(*[c.ctypes.data for c in cost])
+    makespan = ctypes.c_double()
+    idle, waited = np.zeros(P), np.zeros(P)
+    _check(_lib.hanayo_replay_actions(ptrs, counts, P, W, M, t_f, t_b, t_c, int(bool(prefetch)), cost_tab,
+                                      ctypes.byref(makespan), idle.ctypes.data, waited.ctypes.data))
+    return makespan.value, idle, waited
 
 
 def hanayo_replay(lists, P, W, M, cost=None):
