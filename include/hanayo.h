@@ -332,6 +332,37 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
 int hanayo_replay(const hanayo_task* const* lists, const size_t* counts, int P, int W, int M, const float* const* cost,
                   double* makespan, double* idle);
 
+/*
+ * The whole pipeline on one device from ACTION lists, with the communication carried out: every rank has
+ * receive buffers of its own, and a send / receive pair is one device copy from the producer's output buffer
+ * into the consumer's receive buffer (the emulated link).  Tables as for hanayo_pipeline_run, plus
+ *   act_recv  [M*S]  index mb*S + stage: where rank(stage+1) receives the output of (mb, stage);
+ *                    used only where stage+1 lives on another rank (may be NULL elsewhere)
+ *   grad_recv [M*S]  index mb*S + stage: where rank(stage-1) receives the input gradient of (mb, stage);
+ *                    used only where stage-1 lives on another rank
+ *   async = 0        a transfer runs on hip_stream at the position of its receive action: a blocking receive,
+ *                    nothing overlaps it
+ *   async = 1        a transfer runs on a stream of the library's own (default priority, created once per
+ *                    device) as soon as the message has been sent and its receive posted; receives are posted
+ *                    with the paper's look-ahead (before a compute is enqueued, the receive of the following
+ *                    compute is posted); only the consuming compute waits for the arrival
+ *   link_workgroups  workgroups of the copy kernel (0 = as many as the size allows): a few workgroups move
+ *                    data at a small, fixed fraction of the memory bandwidth, which stands in for a slow link
+ * action_ms (host [P] -> host float [counts[r]], may be NULL): durations of the compute actions and, stored at
+ * the receive action, of the transfers; send actions get 0; the call then waits for the stream to drain.
+ * Results equal those of hanayo_pipeline_run.  Same list checks as hanayo_replay_actions; nothing is enqueued
+ * if they fail.
+ */
+typedef struct hanayo_link_args {
+  void* const* act_recv;
+  void* const* grad_recv;
+  int async;
+  int link_workgroups;
+} hanayo_link_args;
+
+int hanayo_pipeline_run_actions(const hanayo_action* const* lists, const size_t* counts, const hanayo_pipeline_args* args,
+                                const hanayo_link_args* link, int* peak_seen, float* const* action_ms);
+
 /* ------------------------------------------------------------------------- *
  * Single kernels of the chunk path, exported so that each can be checked and
  * timed on its own (per-kernel parity tests and roofline measurements).  Same

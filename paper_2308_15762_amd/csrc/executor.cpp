@@ -614,4 +614,198 @@ int hanayo_replay_actions(const hanayo_action* const* lists, const size_t* count
   return HANAYO_OK;
 }
 
+// The whole pipeline from ACTION lists: every rank has receive buffers of its own and a send /
+// receive pair is one device copy from the producer's output buffer into the consumer's receive
+// buffer, the emulated link.  link->async = 0: the copy runs on the compute stream at the position of
+// the receive (a blocking receive: nothing overlaps it).  link->async = 1: the copy runs on a second
+// stream as soon as the message has been sent and its receive posted, with the paper's look-ahead
+// (the receive of the following compute is posted before the current compute is enqueued), and only
+// the consumer waits for it, so transfers overlap the computes enqueued in between.
+int hanayo_pipeline_run_actions(const hanayo_action* const* lists, const size_t* counts, const hanayo_pipeline_args* a,
+                                const hanayo_link_args* link, int* peak_seen, float* const* action_ms) {
+  if (!lists || !counts || !a || !link || !a->desc || !a->weights || !a->grads || !a->x || !a->dy || !a->act || !a->grad ||
+      !a->stash_arena || !a->stash_arena_bytes || !a->workspace || !link->act_recv || !link->grad_recv)
+    return set_error(HANAYO_EINVAL, "pipeline_actions: NULL argument");
+  const int P = a->P, W = a->W, M = a->M;
+  if (P < 1 || W < 1 || M < 1 || 2 * W > 255 || link->link_workgroups < 0)
+    return set_error(HANAYO_EINVAL, "pipeline_actions: bad P=%d W=%d M=%d or link", P, W, M);
+  Shape sh;
+  int rc = prepare_call(a->desc, sh);
+  if (rc) return rc;
+  const int nchunk = 2 * W, S = nchunk * P;
+  // the lists themselves (structure, matching, no deadlock) are checked by the interpreter simulation
+  double dummy = 0.0;
+  rc = hanayo_replay_actions(lists, counts, P, W, M, 1.0, 2.0, 0.0, 0, nullptr, &dummy, nullptr, nullptr);
+  if (rc) return rc;
+  const size_t entry_bytes = stash_layout(sh).block_bytes * sh.nb;
+  const size_t act_bytes = (size_t)sh.T * sh.H * sh.esz;
+  std::vector<Plan> plans(P);
+  std::vector<std::vector<int32_t>> slot_of(P);  // stash slot per action (compute actions only)
+  for (int r = 0; r < P; ++r) {
+    std::vector<hanayo_task> tasks;
+    std::vector<size_t> where;
+    for (size_t i = 0; i < counts[r]; ++i)
+      if (lists[r][i].kind <= HANAYO_B) {
+        tasks.push_back({lists[r][i].kind, lists[r][i].chunk, 0, lists[r][i].mb, lists[r][i].stage});
+        where.push_back(i);
+      }
+    rc = make_plan(tasks.data(), tasks.size(), W, plans[r]);
+    if (rc) return rc;
+    slot_of[r].assign(counts[r], -1);
+    for (size_t k = 0; k < where.size(); ++k) slot_of[r][where[k]] = plans[r].slot[k];
+    if (!a->stash_arena[r] || plans[r].entries * entry_bytes > a->stash_arena_bytes[r])
+      return set_error(HANAYO_ESTATE, "pipeline_actions: rank %d stash arena too small", r);
+    if (action_ms && !action_ms[r]) return set_error(HANAYO_EINVAL, "pipeline_actions: action_ms[%d] is NULL", r);
+  }
+  for (int s = 0; s < S; ++s)
+    if (!a->weights[s] || !a->grads[s]) return set_error(HANAYO_EINVAL, "pipeline_actions: stage %d has no weights or grads", s);
+  for (int m = 0; m < M; ++m) {
+    if (!a->x[m] || !a->dy[m]) return set_error(HANAYO_EINVAL, "pipeline_actions: micro-batch %d has no input or loss gradient", m);
+    for (int s = 0; s < S; ++s) {
+      const size_t at = (size_t)m * S + s;
+      if (!a->act[at] || !a->grad[at]) return set_error(HANAYO_EINVAL, "pipeline_actions: missing boundary buffer for mb %d stage %d", m, s);
+      if (s < S - 1 && stage_rank(P, s + 1) != stage_rank(P, s) && !link->act_recv[at])
+        return set_error(HANAYO_EINVAL, "pipeline_actions: missing activation receive buffer for mb %d stage %d", m, s);
+      if (s > 0 && stage_rank(P, s - 1) != stage_rank(P, s) && !link->grad_recv[at])
+        return set_error(HANAYO_EINVAL, "pipeline_actions: missing gradient receive buffer for mb %d stage %d", m, s);
+    }
+  }
+  // message m of (type, mb, producing stage): index as in the simulation
+  auto message = [&](const hanayo_action& x) -> size_t {
+    const bool is_act = x.kind == HANAYO_SEND_ACT || x.kind == HANAYO_RECV_ACT;
+    const bool is_recv = x.kind == HANAYO_RECV_ACT || x.kind == HANAYO_RECV_GRAD;
+    const int producer = (int)x.stage + (is_recv ? (is_act ? -1 : 1) : 0);
+    return ((size_t)(is_act ? 0 : 1) * M + x.mb) * S + producer;
+  };
+  const size_t n_msg = (size_t)2 * M * S;
+  size_t n_actions = 0;
+  for (int r = 0; r < P; ++r) n_actions += counts[r];
+
+  std::unique_lock<std::mutex> lock(g_lane_mutex);  // the copy stream and the event pool are shared per device
+  LaneResources* res = nullptr;
+  rc = lane_resources(2, 2 * n_msg + 1, &res);
+  if (rc) return rc;
+  hipStream_t compute = static_cast<hipStream_t>(a->hip_stream), copy = res->side[0];
+  std::vector<hipEvent_t> tev;  // timing events, two per action
+  if (action_ms) {
+    tev.resize(2 * n_actions);
+    for (auto& e : tev) HIP_TRY(hipEventCreate(&e));
+  }
+  HIP_TRY(hipEventRecord(res->events[2 * n_msg], compute));  // fork: the copy stream starts after the caller's work
+  HIP_TRY(hipStreamWaitEvent(copy, res->events[2 * n_msg], 0));
+
+  enum : char { NOT_YET = 0, YES = 1 };
+  std::vector<char> was_sent(n_msg, NOT_YET), was_posted(n_msg, NOT_YET), copy_enqueued(n_msg, NOT_YET);
+  std::vector<size_t> tslot(n_msg, 0);  // timing slot of the receive action of a message
+  std::vector<char> fdone((size_t)M * S, 0), bdone((size_t)M * S, 0);
+  std::vector<size_t> head(P, 0), base(P, 0);
+  for (int r = 1; r < P; ++r) base[r] = base[r - 1] + counts[r - 1];
+  // source and destination of a message
+  auto endpoints = [&](size_t m, const void*& src, void*& dst) {
+    const bool is_act = m < (size_t)M * S;
+    const size_t at = is_act ? m : m - (size_t)M * S;  // mb * S + producing stage
+    src = is_act ? a->act[at] : a->grad[at];
+    dst = is_act ? link->act_recv[at] : link->grad_recv[at];
+  };
+  // enqueue the transfer once the message has been sent and its receive posted
+  auto maybe_copy = [&](size_t m) -> int {
+    if (!was_sent[m] || !was_posted[m] || copy_enqueued[m]) return HANAYO_OK;
+    const void* src;
+    void* dst;
+    endpoints(m, src, dst);
+    hipStream_t st = link->async ? copy : compute;
+    if (link->async) HIP_TRY(hipStreamWaitEvent(copy, res->events[2 * m], 0));  // sent
+    if (action_ms) HIP_TRY(hipEventRecord(tev[2 * tslot[m]], st));
+    const int crc = k::copy_bytes(dst, src, act_bytes, st, link->link_workgroups);
+    if (crc) return crc;
+    if (action_ms) HIP_TRY(hipEventRecord(tev[2 * tslot[m] + 1], st));
+    if (link->async) HIP_TRY(hipEventRecord(res->events[2 * m + 1], copy));  // arrived
+    copy_enqueued[m] = YES;
+    return HANAYO_OK;
+  };
+  // every receive action's timing slot is known up front
+  for (int r = 0; r < P; ++r)
+    for (size_t i = 0; i < counts[r]; ++i)
+      if (lists[r][i].kind == HANAYO_RECV_ACT || lists[r][i].kind == HANAYO_RECV_GRAD) tslot[message(lists[r][i])] = base[r] + i;
+
+  bool progressed = true;
+  while (progressed && !rc) {
+    progressed = false;
+    for (int r = 0; r < P && !rc; ++r) {
+      while (head[r] < counts[r] && !rc) {
+        const size_t i = head[r];
+        const hanayo_action& x = lists[r][i];
+        const size_t at = (size_t)x.mb * S + x.stage;
+        if (x.kind <= HANAYO_B) {
+          const bool prev_local = x.stage > 0 && stage_rank(P, (int)x.stage - 1) == r;
+          const bool next_local = (int)x.stage < S - 1 && stage_rank(P, (int)x.stage + 1) == r;
+          if (x.kind == HANAYO_F && prev_local && !fdone[at - 1]) break;
+          if (x.kind == HANAYO_B && (!fdone[at] || (next_local && !bdone[at + 1]))) break;
+          if (link->async) {  // look ahead: post the receive of the following compute
+            for (size_t j = i + 1; j < counts[r] && lists[r][j].kind > HANAYO_B; ++j)
+              if (lists[r][j].kind == HANAYO_RECV_ACT || lists[r][j].kind == HANAYO_RECV_GRAD) {
+                const size_t m = message(lists[r][j]);
+                was_posted[m] = YES;
+                rc = maybe_copy(m);
+                break;
+              }
+            if (rc) break;
+          }
+          void* entry = static_cast<char*>(a->stash_arena[r]) +
+                        (plans[r].chunk_base[x.chunk] + (size_t)slot_of[r][i]) * entry_bytes;
+          const int32_t* vl = a->valid_len ? a->valid_len[x.mb] : nullptr;
+          if (action_ms) HIP_TRY(hipEventRecord(tev[2 * (base[r] + i)], compute));
+          if (x.kind == HANAYO_F) {
+            const void* in = x.stage == 0 ? a->x[x.mb] : (prev_local ? a->act[at - 1] : link->act_recv[at - 1]);
+            rc = chunk_forward(sh, a->weights[x.stage], in, vl, a->act[at], entry, compute);
+            fdone[at] = 1;
+          } else {
+            const void* dy = (int)x.stage == S - 1 ? a->dy[x.mb] : (next_local ? a->grad[at + 1] : link->grad_recv[at + 1]);
+            rc = chunk_backward(sh, a->weights[x.stage], a->grads[x.stage], dy, vl, entry, a->grad[at], a->workspace, compute);
+            bdone[at] = 1;
+          }
+          if (rc) break;
+          if (action_ms) HIP_TRY(hipEventRecord(tev[2 * (base[r] + i) + 1], compute));
+        } else if (x.kind == HANAYO_SEND_ACT || x.kind == HANAYO_SEND_GRAD) {
+          const size_t m = message(x);
+          if (link->async) HIP_TRY(hipEventRecord(res->events[2 * m], compute));  // the message exists from here on
+          was_sent[m] = YES;
+          rc = maybe_copy(m);
+          if (rc) break;
+        } else {
+          const size_t m = message(x);
+          if (!was_sent[m]) break;  // the peer has not got there yet
+          was_posted[m] = YES;
+          rc = maybe_copy(m);
+          if (rc) break;
+          if (link->async) HIP_TRY(hipStreamWaitEvent(compute, res->events[2 * m + 1], 0));  // wait for the arrival
+        }
+        ++head[r];
+        progressed = true;
+      }
+    }
+  }
+  // join: the caller's stream ends after the copy stream
+  HIP_TRY(hipEventRecord(res->events[2 * n_msg], copy));
+  HIP_TRY(hipStreamWaitEvent(compute, res->events[2 * n_msg], 0));
+  if (action_ms) {
+    if (!rc) {
+      HIP_TRY(hipStreamSynchronize(compute));
+      for (int r = 0; r < P; ++r)
+        for (size_t i = 0; i < counts[r]; ++i) {
+          const bool is_send = lists[r][i].kind == HANAYO_SEND_ACT || lists[r][i].kind == HANAYO_SEND_GRAD;
+          action_ms[r][i] = 0.f;
+          if (!is_send) HIP_TRY(hipEventElapsedTime(&action_ms[r][i], tev[2 * (base[r] + i)], tev[2 * (base[r] + i) + 1]));
+        }
+    }
+    for (auto& e : tev) (void)hipEventDestroy(e);
+  }
+  if (rc) return rc;
+  for (int r = 0; r < P; ++r)
+    if (head[r] != counts[r]) return set_error(HANAYO_ESTATE, "pipeline_actions: stopped at rank %d action %zu", r, head[r]);
+  if (peak_seen)
+    for (int r = 0; r < P; ++r) peak_seen[r] = plans[r].peak;
+  return HANAYO_OK;
+}
+
 }  // extern "C"

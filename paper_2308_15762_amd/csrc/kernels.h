@@ -98,7 +98,9 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream);
 int attn_backward_mfma(const AttnArgs& a, hipStream_t stream);
 
 // ---- misc ------------------------------------------------------------------------
-int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream);
+// max_workgroups > 0 caps the grid: a copy that uses only a few CUs and so runs at a chosen fraction of the
+// memory bandwidth (the emulated link of the pipeline runs).
+int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream, int max_workgroups = 0);
 
 // Checks the last launch; returns HANAYO_EHIP with the HIP message on failure.
 int check_launch(const char* what);

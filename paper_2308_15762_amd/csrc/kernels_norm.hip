@@ -335,12 +335,13 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
 }
 }  // namespace
 
-int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream) {
+int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream, int max_workgroups) {
   if (bytes % 16 || ((uintptr_t)dst | (uintptr_t)src) % 16) return set_error(HANAYO_EINVAL, "copy: 16-byte granularity");
   const size_t n16 = bytes / 16;
   if (!n16) return HANAYO_OK;
   const size_t want = (n16 + 255) / 256;
-  const unsigned blocks = (unsigned)(want < 256 * 16 ? want : 256 * 16);  // up to 16 workgroups per CU
+  const size_t cap = max_workgroups > 0 ? (size_t)max_workgroups : (size_t)256 * 16;  // default: up to 16 workgroups per CU
+  const unsigned blocks = (unsigned)(want < cap ? want : cap);
   hipLaunchKernelGGL(copy_kernel, dim3(blocks), dim3(256), 0, stream, (const uint4*)src, (uint4*)dst, n16);
   return check_launch("copy");
 }

@@ -71,6 +71,11 @@ class PipelineArgs(ctypes.Structure):
                 ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p)]
 
 
+class LinkArgs(ctypes.Structure):
+    _fields_ = [("act_recv", ctypes.POINTER(ctypes.c_void_p)), ("grad_recv", ctypes.POINTER(ctypes.c_void_p)),
+                ("async_", ctypes.c_int), ("link_workgroups", ctypes.c_int)]
+
+
 class HanayoError(RuntimeError):
     def __init__(self, code):
         self.code = code
@@ -81,7 +86,7 @@ class HanayoError(RuntimeError):
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
-           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_device_info",
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_pipeline_run_actions", "hanayo_device_info",
            "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
@@ -111,6 +116,7 @@ _lib.hanayo_replay.argtypes = [_vp, _vp, _int, _int, _int, _vp, ctypes.POINTER(c
 _lib.hanayo_actions.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
 _lib.hanayo_replay_actions.argtypes = [_vp, _vp, _int, _int, _int, ctypes.c_double, ctypes.c_double, ctypes.c_double, _int,
                                        _vp, ctypes.POINTER(ctypes.c_double), _vp, _vp]
+_lib.hanayo_pipeline_run_actions.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), ctypes.POINTER(LinkArgs), _vp, _vp]
 _lib.hanayo_device_info.argtypes = [ctypes.c_char_p, _sz]
 _lib.hanayo_op_gemm.argtypes = [_int, _vp, _vp, _vp] + [_int] * 9 + [_vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_op_gemm_group.argtypes = [_int, _int, _int, _int, _vp, _int, _vp]
@@ -412,6 +418,29 @@ def hanayo_replay_actions(lists, P, W, M, t_f=1.0, t_b=2.0, t_c=0.0, prefetch=Fa
     _check(_lib.hanayo_replay_actions(ptrs, counts, P, W, M, t_f, t_b, t_c, int(bool(prefetch)), cost_tab,
                                       ctypes.byref(makespan), idle.ctypes.data, waited.ctypes.data))
     return makespan.value, idle, waited
+
+
+def hanayo_pipeline_run_actions(lists, desc, P, W, M, weights, grads, x, dy, act, grad, valid_len, stash_arenas,
+                                workspace, act_recv, grad_recv, async_copies=True, link_workgroups=0, stream=None,
+                                timing=False):
+    """All P ranks' ACTION lists on this device, transfers carried out as device copies (see include/hanayo.h).
+    act_recv, grad_recv: lists [M*S] of tensors or None.  Returns (stash peaks [P], per-rank arrays of action
+    durations in ms or None)."""
+    lists = [np.ascontiguousarray(t, dtype=ACTION_DTYPE) for t in lists]
+    ptrs = (ctypes.c_void_p * len(lists))(*[t.ctypes.data for t in lists])
+    counts = (ctypes.c_size_t * len(lists))(*[t.size for t in lists])
+    tabs = [_table(t) for t in (weights, grads, x, dy, act, grad)]
+    vl = _table(valid_len) if valid_len is not None else None
+    arenas = _table(stash_arenas)
+    arena_bytes = (ctypes.c_size_t * P)(*[t.numel() * t.element_size() for t in stash_arenas])
+    args = PipelineArgs(ctypes.pointer(desc), P, W, M, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5], vl,
+                        arenas, arena_bytes, _ptr(workspace), stream)
+    link = LinkArgs(_table(act_recv), _table(grad_recv), int(bool(async_copies)), int(link_workgroups))
+    peaks = (ctypes.c_int * P)()
+    ms = [np.zeros(t.size, dtype=np.float32) for t in lists] if timing else None
+    ms_tab = (ctypes.c_void_p * P)(*[a.ctypes.data for a in ms]) if timing else None
+    _check(_lib.hanayo_pipeline_run_actions(ptrs, counts, ctypes.byref(args), ctypes.byref(link), peaks, ms_tab))
+    return list(peaks), ms
 
 
 def hanayo_replay(lists, P, W, M, cost=None):

@@ -150,3 +150,25 @@ class GpuPipeline:
 
     def grad_dicts(self, stage):
         return hn.unpack_params(self.desc, self.grads[stage].cpu().numpy(), self.params[stage])
+
+    def enable_links(self):
+        """Action lists and per-rank receive buffers for every stage boundary that crosses ranks."""
+        wl, S = self.wl, self.S
+        self.actions = [hn.hanayo_actions(wl.P, wl.W, wl.M, r) for r in range(wl.P)]
+        rank = [hn.hanayo_stage_rank(wl.P, wl.W, s) for s in range(S)]
+        like = self.act[0]
+        self.act_recv = [None] * (wl.M * S)
+        self.grad_recv = [None] * (wl.M * S)
+        for m in range(wl.M):
+            for s in range(S):
+                if s < S - 1 and rank[s + 1] != rank[s]:
+                    self.act_recv[m * S + s] = torch.empty_like(like)
+                if s > 0 and rank[s - 1] != rank[s]:
+                    self.grad_recv[m * S + s] = torch.empty_like(like)
+
+    def run_actions(self, async_copies=True, link_workgroups=0, timing=False, lists=None, stream=None):
+        wl = self.wl
+        return hn.hanayo_pipeline_run_actions(self.actions if lists is None else lists, self.desc, wl.P, wl.W, wl.M,
+                                              self.weights, self.grads, self.x, self.dy, self.act, self.grad,
+                                              self.valid_len, self.arenas, self.work, self.act_recv, self.grad_recv,
+                                              async_copies, link_workgroups, stream, timing)

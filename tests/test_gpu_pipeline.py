@@ -128,3 +128,64 @@ def test_full_size_pipeline_sampled_output():
         assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
     for mm in range(wl.M):
         assert bool(torch.isfinite(gpu.grad[mm * S].float()).all())
+
+
+@pytest.mark.parametrize("mode", ["blocking", "async", "async_slow_link"])
+@pytest.mark.parametrize("name", ["tiny_gpt_fp32", "gpt_1024_small", "bert_small"])
+def test_pipeline_from_action_lists(name, mode):
+    """The same end-to-end parity with the communication carried out: per-rank receive buffers, a copy
+    per send / receive pair, on the compute stream (blocking receives) or overlapped on the copy stream
+    with look-ahead posting, at full speed or through a link throttled to two workgroups."""
+    wl = CASES[name]
+    tol = depth_tolerance(wl)
+    gpu = GpuPipeline(wl)
+    gpu.enable_links()
+    kw = {"blocking": dict(async_copies=False), "async": dict(async_copies=True),
+          "async_slow_link": dict(async_copies=True, link_workgroups=2)}[mode]
+    peaks, ms = gpu.run_actions(timing=True, **kw)
+    torch.cuda.synchronize()
+    assert peaks == [OS.stash_plan(OS.schedule(wl.P, wl.W, wl.M, r), wl.W)[0] for r in range(wl.P)]
+    ys, dxs, grads = reference(wl)
+    S = gpu.S
+    for m in range(wl.M):
+        assert nerr(host(gpu.act[m * S + S - 1]), ys[m]) <= tol
+        assert nerr(host(gpu.grad[m * S]), dxs[m]) <= tol
+    for s in range(S):
+        compare_grads(gpu.grad_dicts(s), grads[s], tol, "%s stage %d" % (name, s))
+    # every receive buffer holds exactly what its producer wrote
+    for i, t in enumerate(gpu.act_recv):
+        if t is not None:
+            assert torch.equal(t, gpu.act[i])
+    for i, t in enumerate(gpu.grad_recv):
+        if t is not None:
+            assert torch.equal(t, gpu.grad[i])
+    # timings: computes and transfers positive, sends zero
+    for a, t in zip(gpu.actions, ms):
+        sends = (a["kind"] == hn.SEND_ACT) | (a["kind"] == hn.SEND_GRAD)
+        assert (t[sends] == 0).all() and (t[~sends] > 0).all()
+    # a second, untimed run in the same mode reproduces the outputs bit for bit
+    out = gpu.act[S - 1].clone()
+    gpu.zero_grads()
+    gpu.run_actions(**kw)
+    torch.cuda.synchronize()
+    assert torch.equal(out, gpu.act[S - 1])
+
+
+def test_action_pipeline_rejects_bad_lists():
+    wl = CASES["tiny_gpt_fp32"]
+    gpu = GpuPipeline(wl)
+    gpu.enable_links()
+    bad = [t.copy() for t in gpu.actions]
+    bad[1] = np.delete(bad[1], int(np.nonzero(bad[1]["kind"] == hn.SEND_ACT)[0][0]))
+    for t in gpu.act:
+        t.fill_(7.0)
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run_actions(lists=bad)
+    assert e.value.code == hn.ESTATE
+    torch.cuda.synchronize()
+    assert all(bool((t == 7.0).all()) for t in gpu.act)
+    keep = gpu.act_recv
+    gpu.act_recv = [None] * len(keep)
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run_actions()
+    assert e.value.code == hn.EINVAL
