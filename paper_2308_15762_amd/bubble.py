@@ -10,6 +10,7 @@ and T_C = 0.  Printed next to it: the same schedule under the assumed costs, and
 closed form the paper gives for one unit of P micro-batches.
 
     python -m paper_2308_15762_amd.bubble --workload gpt_1024_bf16 [--M 4] [--repeat 3]
+    python -m paper_2308_15762_amd.bubble --links [--link-workgroups 2]      (see report_links)
 
 Prints one JSON line.
 """
@@ -69,11 +70,55 @@ def report(wl, repeat=3):
     return out
 
 
+def report_links(wl, link_workgroups=0, repeat=3):
+    """The pipeline run from action lists with every send / receive pair carried out as a device copy
+    (link_workgroups workgroups: the emulated link).  Measures the transfers, the whole run on this
+    one GPU with blocking receives against overlapped ones, and replays the measured compute times
+    and transfer time through the interpreter simulation with and without the paper's prefetch."""
+    import time
+    import torch
+    from . import hanayo as hn
+    from .runner import GpuPipeline
+    P, W, M = wl.P, wl.W, wl.M
+    gpu = GpuPipeline(wl)
+    gpu.enable_links()
+    wall = {}
+    for mode, async_copies in (("blocking", False), ("overlapped", True)):
+        gpu.run_actions(async_copies=async_copies, link_workgroups=link_workgroups)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(repeat):
+            gpu.run_actions(async_copies=async_copies, link_workgroups=link_workgroups)
+        torch.cuda.synchronize()
+        wall[mode] = (time.perf_counter() - t0) / repeat * 1e3
+    _, ms_block = gpu.run_actions(async_copies=False, link_workgroups=link_workgroups, timing=True)
+    _, ms = gpu.run_actions(async_copies=True, link_workgroups=link_workgroups, timing=True)
+    recv = [(a["kind"] == hn.RECV_ACT) | (a["kind"] == hn.RECV_GRAD) for a in gpu.actions]
+    t_c_alone = float(np.concatenate([m[r] for m, r in zip(ms_block, recv)]).mean())
+    t_c_overlapped = float(np.concatenate([m[r] for m, r in zip(ms, recv)]).mean())
+    # compute durations from the blocking run (nothing shares the chip with them there)
+    out = {"workload": wl.name, "P": P, "W": W, "M": M, "link_workgroups": link_workgroups,
+           "message_mib": wl.mb * wl.seq * wl.hidden * (2 if wl.dtype == "bf16" else 4) / 2 ** 20,
+           "messages": int(sum(r.sum() for r in recv)),
+           "t_c_ms_alone": t_c_alone, "t_c_ms_overlapped": t_c_overlapped,
+           "one_gpu_ms_blocking_receives": wall["blocking"], "one_gpu_ms_overlapped_transfers": wall["overlapped"]}
+    for name, pre in (("no_prefetch", False), ("prefetch", True)):
+        makespan, idle, waited = hn.hanayo_replay_actions(gpu.actions, P, W, M, 0.0, 0.0, t_c_alone, pre, ms_block)
+        out["makespan_ms_" + name] = makespan
+        out["bubble_ratio_" + name] = float(np.mean(idle) / makespan)
+        out["waited_ms_per_rank_" + name] = [float(v) for v in waited]
+    makespan0, idle0, _ = hn.hanayo_replay_actions(gpu.actions, P, W, M, 0.0, 0.0, 0.0, False, ms_block)
+    out["makespan_ms_t_c_zero"] = makespan0
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workload", default="gpt_1024_bf16")
     ap.add_argument("--M", type=int, default=None, help="micro-batches (default: the workload's)")
     ap.add_argument("--repeat", type=int, default=3)
+    ap.add_argument("--links", action="store_true", help="run from action lists with the transfers carried out")
+    ap.add_argument("--link-workgroups", type=int, default=0, help="workgroups of a transfer's copy kernel (0 = unrestricted)")
     args = ap.parse_args()
     import torch
     from . import synth
@@ -82,7 +127,7 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     if args.M is not None:
         wl = wl.scaled(M=args.M)
-    print(json.dumps(report(wl, args.repeat)))
+    print(json.dumps(report_links(wl, args.link_workgroups, args.repeat) if args.links else report(wl, args.repeat)))
 
 
 if __name__ == "__main__":

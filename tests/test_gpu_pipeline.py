@@ -189,3 +189,17 @@ def test_action_pipeline_rejects_bad_lists():
     with pytest.raises(hn.HanayoError) as e:
         gpu.run_actions()
     assert e.value.code == hn.EINVAL
+
+
+def test_links_report_on_a_small_pipeline():
+    """report_links: transfers through a one-workgroup link are slower than unrestricted ones; the replay
+    with prefetch is never longer than without, and both are at least the zero-transfer-time makespan."""
+    from paper_2308_15762_amd import bubble
+    wl = W["gpt_1024_bf16"].scaled(hidden=256, heads=4, ffn=1024, seq=256, mb=2, M=4)
+    fast = bubble.report_links(wl, link_workgroups=0, repeat=1)
+    slow = bubble.report_links(wl, link_workgroups=1, repeat=1)
+    assert fast["messages"] == slow["messages"] == 2 * 4 * (15 - 3)
+    assert slow["t_c_ms_alone"] > fast["t_c_ms_alone"] > 0
+    for rep in (fast, slow):
+        assert rep["makespan_ms_t_c_zero"] <= rep["makespan_ms_prefetch"] * (1 + 1e-9)
+        assert rep["makespan_ms_prefetch"] <= rep["makespan_ms_no_prefetch"] * (1 + 1e-9)
