@@ -160,6 +160,25 @@ int lane_resources(int lanes, size_t n_events, LaneResources** out) {
   return HANAYO_OK;
 }
 
+// Timing events of one call: created on demand, destroyed when the call returns, also on an error path.
+struct TimingEvents {
+  std::vector<hipEvent_t> ev;
+  ~TimingEvents() {
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  }
+  int create(size_t n) {
+    ev.reserve(n);
+    for (size_t i = 0; i < n; ++i) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess)
+        return set_error(HANAYO_EHIP, "executor: cannot create an event: %s", hipGetErrorString(hipGetLastError()));
+      ev.push_back(e);
+    }
+    return HANAYO_OK;
+  }
+  hipEvent_t operator[](size_t i) const { return ev[i]; }
+};
+
 #define HIP_TRY(call)                                                                                  \
   do {                                                                                                 \
     const hipError_t e_ = (call);                                                                      \
@@ -397,12 +416,12 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
         return set_error(HANAYO_ESTATE, "pipeline: the lists deadlock (rank %d stops at task %zu)", r, head[r]);
   }
   hipStream_t st = static_cast<hipStream_t>(a->hip_stream);
-  std::vector<hipEvent_t> ev;
+  TimingEvents ev;
   if (task_ms) {
     for (int r = 0; r < P; ++r)
       if (!task_ms[r]) return set_error(HANAYO_EINVAL, "pipeline: task_ms[%d] is NULL", r);
-    ev.resize(2 * order.size());
-    for (auto& e : ev) HIP_TRY(hipEventCreate(&e));
+    rc = ev.create(2 * order.size());
+    if (rc) return rc;
   }
   for (size_t k = 0; k < order.size() && !rc; ++k) {
     const int r = order[k].rank;
@@ -428,7 +447,6 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
       for (size_t k = 0; k < order.size(); ++k)
         HIP_TRY(hipEventElapsedTime(&task_ms[order[k].rank][order[k].index], ev[2 * k], ev[2 * k + 1]));
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
   }
   if (rc) return rc;
   if (peak_seen)
@@ -686,10 +704,10 @@ int hanayo_pipeline_run_actions(const hanayo_action* const* lists, const size_t*
   rc = lane_resources(2, 2 * n_msg + 1, &res);
   if (rc) return rc;
   hipStream_t compute = static_cast<hipStream_t>(a->hip_stream), copy = res->side[0];
-  std::vector<hipEvent_t> tev;  // timing events, two per action
+  TimingEvents tev;  // two per action
   if (action_ms) {
-    tev.resize(2 * n_actions);
-    for (auto& e : tev) HIP_TRY(hipEventCreate(&e));
+    rc = tev.create(2 * n_actions);
+    if (rc) return rc;
   }
   HIP_TRY(hipEventRecord(res->events[2 * n_msg], compute));  // fork: the copy stream starts after the caller's work
   HIP_TRY(hipStreamWaitEvent(copy, res->events[2 * n_msg], 0));
@@ -798,7 +816,6 @@ int hanayo_pipeline_run_actions(const hanayo_action* const* lists, const size_t*
           if (!is_send) HIP_TRY(hipEventElapsedTime(&action_ms[r][i], tev[2 * (base[r] + i)], tev[2 * (base[r] + i) + 1]));
         }
     }
-    for (auto& e : tev) (void)hipEventDestroy(e);
   }
   if (rc) return rc;
   for (int r = 0; r < P; ++r)
