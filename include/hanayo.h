@@ -200,7 +200,22 @@ typedef struct hanayo_exec_args {
   void* workspace;                 /* device, lanes * hanayo_workspace_bytes() */
   void* hip_stream;
   int lanes;                       /* 0 or 1: everything on hip_stream; 2..4: see below */
+  int stash_mode;                  /* HANAYO_STASH_FULL or HANAYO_STASH_INPUT, see below */
+  void* recompute_scratch;         /* device; HANAYO_STASH_INPUT only: max(lanes, 1) * hanayo_recompute_scratch_bytes() */
 } hanayo_exec_args;
+
+/*
+ * Stash modes.  HANAYO_STASH_FULL (0): a stash entry holds every tensor the forward pass materialises
+ * (hanayo_stash_bytes() per entry); backward recomputes only the attention probabilities.
+ * HANAYO_STASH_INPUT (1): an entry holds the chunk's input only (hanayo_act_bytes() rounded up to 256 per
+ * entry, arena size from hanayo_stash_arena_bytes_input()); a backward task first runs the chunk's forward
+ * again from that input into a scratch entry (one per lane, recompute_scratch) and then the backward.
+ * Same results (the recomputed forward is the same kernels on the same data); about one forward more per
+ * backward in time, two orders of magnitude less stash.
+ */
+enum { HANAYO_STASH_FULL = 0, HANAYO_STASH_INPUT = 1 };
+size_t hanayo_stash_arena_bytes_input(const hanayo_task* list, size_t n, int W, const hanayo_chunk_desc* d);
+size_t hanayo_recompute_scratch_bytes(const hanayo_chunk_desc* d);
 
 /* Arena size the executor needs for `list`; 0 on error. */
 size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const hanayo_chunk_desc* d);

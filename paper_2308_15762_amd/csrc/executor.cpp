@@ -229,6 +229,20 @@ size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const 
   return pl.entries * (stash_layout(sh).block_bytes * sh.nb);
 }
 
+size_t hanayo_stash_arena_bytes_input(const hanayo_task* list, size_t n, int W, const hanayo_chunk_desc* d) {
+  Shape sh;
+  if (make_shape(d, sh) || W < 1 || 2 * W > 255 || (!list && n)) return 0;
+  Plan pl;
+  if (make_plan(list, n, W, pl)) return 0;
+  return pl.entries * align_up((size_t)sh.T * sh.H * sh.esz, 256);
+}
+
+size_t hanayo_recompute_scratch_bytes(const hanayo_chunk_desc* d) {
+  Shape sh;
+  if (make_shape(d, sh)) return 0;
+  return stash_layout(sh).block_bytes * sh.nb + align_up((size_t)sh.T * sh.H * sh.esz, 256);
+}
+
 int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int32_t* lane,
                          int32_t* deps) {
   if (!list || !lane || !deps) return set_error(HANAYO_EINVAL, "executor_plan: NULL argument");
@@ -263,7 +277,13 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
   Plan pl;
   rc = make_plan(list, n, W, pl);
   if (rc) return rc;
-  const size_t entry_bytes = stash_layout(sh).block_bytes * sh.nb;
+  if (a->stash_mode != HANAYO_STASH_FULL && a->stash_mode != HANAYO_STASH_INPUT)
+    return set_error(HANAYO_EINVAL, "executor: stash_mode %d", a->stash_mode);
+  const bool recompute = a->stash_mode == HANAYO_STASH_INPUT;
+  if (recompute && !a->recompute_scratch) return set_error(HANAYO_EINVAL, "executor: stash_mode input needs recompute_scratch");
+  const size_t full_entry_bytes = stash_layout(sh).block_bytes * sh.nb;
+  const size_t act_bytes = (size_t)sh.T * sh.H * sh.esz;
+  const size_t entry_bytes = recompute ? align_up(act_bytes, 256) : full_entry_bytes;  // what a stash slot holds
   if (pl.entries * entry_bytes > a->stash_arena_bytes)
     return set_error(HANAYO_ESTATE, "executor: stash arena holds %zu bytes, plan needs %zu", a->stash_arena_bytes,
                      pl.entries * entry_bytes);
@@ -324,16 +344,29 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     k::set_gemm_sharing((lp.busy[i] - 2.0f) * 0.5f);
     void* entry = arena + (pl.chunk_base[tk.chunk] + (size_t)pl.slot[i]) * entry_bytes;
     const int32_t* vl = a->valid_len ? a->valid_len[tk.mb] : nullptr;
+    // input-only stash: the lane's scratch entry takes what the forward materialises, then an output scratch
+    char* scratch = recompute ? static_cast<char*>(a->recompute_scratch) + (size_t)lane * (full_entry_bytes + align_up(act_bytes, 256))
+                              : nullptr;
     if (tk.kind == HANAYO_F) {
       const bool local = stage > 0 && stage_rank(P, stage - 1) == rank;
       const void* x = local ? a->act_out[at - 1] : a->act_in[at];
-      rc = chunk_forward(sh, a->weights[tk.chunk], x, vl, a->act_out[at], entry, st);
+      if (recompute) {
+        rc = k::copy_bytes(entry, x, act_bytes, st);
+        if (!rc) rc = chunk_forward(sh, a->weights[tk.chunk], x, vl, a->act_out[at], scratch, st);
+      } else {
+        rc = chunk_forward(sh, a->weights[tk.chunk], x, vl, a->act_out[at], entry, st);
+      }
       if (++live > peak) peak = live;
     } else {
       const bool local = stage < S - 1 && stage_rank(P, stage + 1) == rank;
       const void* dy = local ? a->grad_out[at + 1] : a->grad_in[at];
       void* work = static_cast<char*>(a->workspace) + (size_t)lane * work_bytes;  // one workspace per lane
-      rc = chunk_backward(sh, a->weights[tk.chunk], a->grads[tk.chunk], dy, vl, entry, a->grad_out[at], work, st);
+      const void* stash = entry;
+      if (recompute) {  // the forward again, from the stashed input
+        rc = chunk_forward(sh, a->weights[tk.chunk], entry, vl, scratch + full_entry_bytes, scratch, st);
+        stash = scratch;
+      }
+      if (!rc) rc = chunk_backward(sh, a->weights[tk.chunk], a->grads[tk.chunk], dy, vl, stash, a->grad_out[at], work, st);
       --live;
     }
     if (rc) break;

@@ -49,7 +49,8 @@ class ExecArgs(ctypes.Structure):
                 ("act_out", ctypes.POINTER(ctypes.c_void_p)), ("grad_out", ctypes.POINTER(ctypes.c_void_p)),
                 ("valid_len", ctypes.POINTER(ctypes.c_void_p)),
                 ("stash_arena", ctypes.c_void_p), ("stash_arena_bytes", ctypes.c_size_t),
-                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p), ("lanes", ctypes.c_int)]
+                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p), ("lanes", ctypes.c_int),
+                ("stash_mode", ctypes.c_int), ("recompute_scratch", ctypes.c_void_p)]
 
 
 class GemmProblem(ctypes.Structure):
@@ -86,7 +87,8 @@ class HanayoError(RuntimeError):
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
-           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_pipeline_run_actions", "hanayo_device_info",
+           "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_stash_arena_bytes_input",
+           "hanayo_recompute_scratch_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_pipeline_run_actions", "hanayo_device_info",
            "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward")
 
@@ -109,6 +111,10 @@ _lib.hanayo_chunk_forward.argtypes = [_descp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_chunk_backward.argtypes = [_descp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_stash_arena_bytes.restype = _sz
 _lib.hanayo_stash_arena_bytes.argtypes = [_vp, _sz, _int, _descp]
+_lib.hanayo_stash_arena_bytes_input.restype = _sz
+_lib.hanayo_stash_arena_bytes_input.argtypes = [_vp, _sz, _int, _descp]
+_lib.hanayo_recompute_scratch_bytes.restype = _sz
+_lib.hanayo_recompute_scratch_bytes.argtypes = [_descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
 _lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp]
 _lib.hanayo_pipeline_run.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), _vp, _vp]
@@ -237,6 +243,21 @@ def hanayo_stash_arena_bytes(tasks, W, desc):
     return v
 
 
+STASH_FULL, STASH_INPUT = 0, 1
+
+
+def hanayo_stash_arena_bytes_input(tasks, W, desc):
+    tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
+    v = _lib.hanayo_stash_arena_bytes_input(tasks.ctypes.data, tasks.size, W, ctypes.byref(desc))
+    if v == 0:
+        raise HanayoError(ESTATE)
+    return v
+
+
+def hanayo_recompute_scratch_bytes(desc):
+    return _lib.hanayo_recompute_scratch_bytes(ctypes.byref(desc))
+
+
 def hanayo_device_info():
     buf = ctypes.create_string_buffer(256)
     _check(_lib.hanayo_device_info(buf, 256))
@@ -347,14 +368,16 @@ def hanayo_executor_plan(tasks, P, W, M, rank, lanes):
 
 
 def hanayo_executor_run(tasks, desc, P, W, M, rank, weights, grads, act_in, grad_in, act_out, grad_out,
-                        valid_len, stash_arena, stash_arena_bytes, workspace, stream=None, lanes=1):
+                        valid_len, stash_arena, stash_arena_bytes, workspace, stream=None, lanes=1,
+                        stash_mode=0, recompute_scratch=None):
     """Tables are Python lists of tensors / None: weights, grads [2W]; act_*, grad_* [M*2W]
     indexed mb*2W+chunk; valid_len [M] or None.  Returns the stash peak seen."""
     tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
     tabs = [_table(t) for t in (weights, grads, act_in, grad_in, act_out, grad_out)]
     vl = _table(valid_len) if valid_len is not None else None
     args = ExecArgs(ctypes.pointer(desc), P, W, M, rank, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5],
-                    vl, _ptr(stash_arena), stash_arena_bytes, _ptr(workspace), stream, lanes)
+                    vl, _ptr(stash_arena), stash_arena_bytes, _ptr(workspace), stream, lanes, stash_mode,
+                    _ptr(recompute_scratch))
     peak = _int()
     _check(_lib.hanayo_executor_run(tasks.ctypes.data, tasks.size, ctypes.byref(args), ctypes.byref(peak)))
     return peak.value

@@ -64,8 +64,8 @@ class GpuRank:
     """Device state of one rank of a workload: per-chunk weights/grads, boundary
     tables, stash arena, workspace; runs a task list through hanayo_executor_run."""
 
-    def __init__(self, wl, rank=0, tasks=None, unique_outputs=True, lanes=1):
-        self.wl, self.rank, self.lanes = wl, rank, lanes
+    def __init__(self, wl, rank=0, tasks=None, unique_outputs=True, lanes=1, stash_mode=0):
+        self.wl, self.rank, self.lanes, self.stash_mode = wl, rank, lanes, stash_mode
         self.desc = hn.desc_for(wl)
         P, W, M = wl.P, wl.W, wl.M
         self.nchunk = 2 * W
@@ -75,7 +75,12 @@ class GpuRank:
         self.grads = [torch.zeros(hn.hanayo_grad_bytes(self.desc) // 4, dtype=torch.float32, device="cuda")
                       for _ in range(self.nchunk)]
         self.work = dev_bytes(lanes * hn.hanayo_workspace_bytes(self.desc))
-        self.arena_bytes = hn.hanayo_stash_arena_bytes(self.tasks, W, self.desc)
+        self.scratch = None
+        if stash_mode == hn.STASH_INPUT:
+            self.arena_bytes = hn.hanayo_stash_arena_bytes_input(self.tasks, W, self.desc)
+            self.scratch = dev_bytes(max(lanes, 1) * hn.hanayo_recompute_scratch_bytes(self.desc))
+        else:
+            self.arena_bytes = hn.hanayo_stash_arena_bytes(self.tasks, W, self.desc)
         self.arena = dev_bytes(self.arena_bytes)
         S = 2 * W * P
         n = M * self.nchunk
@@ -105,7 +110,8 @@ class GpuRank:
         wl = self.wl
         return hn.hanayo_executor_run(self.tasks if tasks is None else tasks, self.desc, wl.P, wl.W, wl.M, self.rank,
                                       self.weights, self.grads, self.act_in, self.grad_in, self.act_out,
-                                      self.grad_out, self.valid_len, self.arena, self.arena_bytes, self.work, stream, self.lanes)
+                                      self.grad_out, self.valid_len, self.arena, self.arena_bytes, self.work, stream, self.lanes,
+                                      self.stash_mode, self.scratch)
 
     def grad_dicts(self, chunk):
         return hn.unpack_params(self.desc, self.grads[chunk].cpu().numpy(), self.params[chunk])

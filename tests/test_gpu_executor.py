@@ -101,6 +101,44 @@ def test_lanes_do_not_change_results(name):
             assert nerr(b.cpu().numpy(), a.cpu().numpy()) <= 1e-5
 
 
+@pytest.mark.parametrize("lanes", [1, 3])
+@pytest.mark.parametrize("name", ["tiny_gpt_fp32_rank0", "gpt_1024_sched_small", "bert_sched_small"])
+def test_input_only_stash_recomputes_to_the_same_result(name, lanes):
+    """Stash mode "input": entries hold the chunk input only and every backward recomputes its forward.
+    The boundary outputs are bit-identical to the full-stash run, the gradients equal up to the order of
+    the bias-gradient atomics, and the arena is the plan's entry count times one activation tensor."""
+    wl, rank = CASES[name]
+    full = GpuRank(wl, rank, lanes=lanes)
+    full.run()
+    lean = GpuRank(wl, rank, lanes=lanes, stash_mode=hn.STASH_INPUT)
+    peak = lean.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(lean.tasks, wl.W)[0]
+    per_chunk = hn.hanayo_stash_plan(lean.tasks, wl.W)[1]
+    act = hn.hanayo_act_bytes(lean.desc)
+    assert lean.arena_bytes == sum(per_chunk) * ((act + 255) // 256 * 256) < full.arena_bytes
+    for a, b in zip(full.act_out + full.grad_out, lean.act_out + lean.grad_out):
+        assert torch.equal(a, b)
+    for a, b in zip(full.grads, lean.grads):
+        assert nerr(b.cpu().numpy(), a.cpu().numpy()) <= 1e-5
+    ref = oracle_of(name, lean.tasks)
+    for c in range(2 * wl.W):
+        compare_grads(lean.grad_dicts(c), ref["grads"][c], TOL[wl.dtype], "%s chunk %d" % (name, c))
+
+
+def test_input_only_stash_needs_its_scratch():
+    wl, rank = CASES["gpt_1024_sched_small"]
+    gpu = GpuRank(wl, rank, stash_mode=hn.STASH_INPUT)
+    gpu.scratch = None
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run()
+    assert e.value.code == hn.EINVAL
+    gpu.stash_mode = 7
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run()
+    assert e.value.code == hn.EINVAL
+
+
 def test_executor_rejects_too_many_lanes():
     wl, rank = CASES["gpt_1024_sched_small"]
     gpu = GpuRank(wl, rank, lanes=4)
