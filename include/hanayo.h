@@ -167,6 +167,74 @@ int hanayo_chunk_backward(const hanayo_chunk_desc* d, const void* weights, float
                           void* hip_stream);
 
 /* ------------------------------------------------------------------------- *
+ * The two ends of the model and the optimizer step.  The paper trains GPT-style
+ * and BERT-style language models with synchronous pipeline parallelism (its
+ * background section: one flush and one parameter update per iteration, from
+ * the gradients summed over the micro-batches) and prints none of these pieces,
+ * so they are the standard ones:
+ *   embedding  x[n][i][:] = wte[token[n][i]][:] + wpe[i][:]     (in front of stage 0)
+ *   head       logits = LN_f(y) head^T, head a [V][H] table (LN_f optional);
+ *              loss = mean over the labelled positions of -log softmax(logits)[label]
+ *   Adam       with bias correction and decoupled weight decay
+ * In a wave placement stage 0 and the last stage share rank 0, so a head tied to
+ * the token table (head == wte, d_head == d_wte) needs no exchange between ranks.
+ * Tables are row-major in the storage type, gradients fp32 and ADDED to.
+ * ------------------------------------------------------------------------- */
+typedef struct hanayo_ends_desc {
+  int vocab;    /* V; multiple of 8 (multiples of 128 take the fast bf16 GEMM kernels) */
+  int max_pos;  /* rows of the position table wpe, >= seq */
+  int final_ln; /* 1: LayerNorm (gamma[H] then beta[H], the chunk's ln_eps) in front of the head */
+} hanayo_ends_desc;
+
+/*
+ * tokens  device int32 [b][s]; a token outside [0, V) contributes no table row
+ *         (forward) and receives no gradient (backward)
+ * x       device [b][s][H], fully overwritten
+ * d_wte   device fp32 [V][H]: rows of equal tokens are added with fp32 atomics, in no fixed order
+ * d_wpe   device fp32 [max_pos][H]
+ */
+int hanayo_embed_forward(const hanayo_chunk_desc* d, const hanayo_ends_desc* e, const void* wte, const void* wpe,
+                         const int32_t* tokens, void* x, void* hip_stream);
+int hanayo_embed_backward(const hanayo_chunk_desc* d, const hanayo_ends_desc* e, const int32_t* tokens, const void* dx,
+                          float* d_wte, float* d_wpe, void* hip_stream);
+
+/*
+ * Loss of one micro-batch and, in the same call, the gradients of loss_scale * loss (loss_scale = 1 / M
+ * makes the iteration's loss the mean over its micro-batches).
+ *   lnf, d_lnf  device [2][H] (gamma, beta) and fp32 [2][H]; read only with final_ln
+ *   head        device [V][H];  d_head fp32 [V][H]
+ *   y           device [b][s][H], output of the last stage (read)
+ *   labels      device int32 [b][s]; a label outside [0, V) (e.g. -1) marks a position that does not count
+ *   loss        device float [1], written: the mean over the counted positions, 0 if there is none
+ *   dy          device [b][s][H], fully overwritten; may not alias y
+ *   workspace   device, hanayo_head_workspace_bytes(); holds the [b*s][V] logits
+ */
+size_t hanayo_head_workspace_bytes(const hanayo_chunk_desc* d, const hanayo_ends_desc* e); /* 0 on a bad descriptor */
+int hanayo_head_loss(const hanayo_chunk_desc* d, const hanayo_ends_desc* e, const void* lnf, const void* head,
+                     const void* y, const int32_t* labels, float loss_scale, float* loss, void* dy, float* d_lnf,
+                     float* d_head, void* workspace, void* hip_stream);
+
+/*
+ * One Adam update (Kingma & Ba, Algorithm 1; decay as in Loshchilov & Hutter, Algorithm 2), in place:
+ *   m = beta1 m + (1 - beta1) g;   v = beta2 v + (1 - beta2) g^2
+ *   p = p - lr ( (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps) + weight_decay p )
+ * params is the storage type; for bf16 storage `master` (fp32, same element count) is the copy that is
+ * updated and params receives its rounding; for fp32 storage master is ignored (may be NULL).  grads, m, v
+ * are fp32.  zero_grads = 1 clears the gradients in the same pass (the next iteration starts from zero).
+ * count: multiple of 4.  hanayo_chunk_adam_step updates a chunk's packed parameters and applies the decay
+ * to its four matrices only (not to biases and LayerNorm parameters).
+ */
+typedef struct hanayo_adam {
+  float lr, beta1, beta2, eps, weight_decay;
+  int step;       /* 1 for the first update */
+  int zero_grads;
+} hanayo_adam;
+int hanayo_adam_step(const hanayo_adam* o, int dtype, void* params, float* master, float* grads, float* m, float* v,
+                     size_t count, void* hip_stream);
+int hanayo_chunk_adam_step(const hanayo_adam* o, const hanayo_chunk_desc* d, void* weights, float* master, float* grads,
+                           float* m, float* v, void* hip_stream);
+
+/* ------------------------------------------------------------------------- *
  * Per-rank task executor (the worker-side interpreter of the runtime section,
  * compute actions only).  Runs `list` in order (on one stream unless lanes
  * are asked for, see below).  All chunks of

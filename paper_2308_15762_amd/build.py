@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhanayo.so")
 
 SOURCES = [
-    "schedule.cpp", "layout.cpp", "chunk.cpp", "executor.cpp", "ops.cpp",
+    "schedule.cpp", "layout.cpp", "chunk.cpp", "executor.cpp", "ops.cpp", "ends.cpp", "kernels_ends.hip",
     "kernels_norm.hip", "kernels_generic.hip", "kernels_gemm_mfma.hip", "kernels_gemm_dma.hip", "kernels_attn_mfma.hip",
 ]
 

@@ -290,6 +290,8 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
   return HANAYO_OK;
 }
 
+int device_ok() { return check_device(); }
+
 int prepare_call(const hanayo_chunk_desc* d, Shape& sh) {
   TRY(make_shape(d, sh));
   return check_device();

@@ -97,6 +97,38 @@ bool attn_mfma_supported(const AttnArgs& a);
 int attn_forward_mfma(const AttnArgs& a, hipStream_t stream);
 int attn_backward_mfma(const AttnArgs& a, hipStream_t stream);
 
+// ---- the model's ends and the optimizer --------------------------------------------
+// x[n][i][:] = wte[tokens[n][i]][:] + wpe[i][:]; tokens outside [0, vocab) contribute nothing.
+int embed_forward(int dtype, const void* wte, const void* wpe, const int32_t* tokens, void* x, int b, int s, int H,
+                  int vocab, hipStream_t stream);
+// d_wte[tokens[n][i]][:] += dx[n][i][:] (fp32 atomics); d_wpe[i][:] += sum_n dx[n][i][:].
+int embed_backward(int dtype, const int32_t* tokens, const void* dx, float* d_wte, float* d_wpe, int b, int s, int H,
+                   int vocab, hipStream_t stream);
+// count[0] = number of labels inside [0, vocab).
+int count_labels(const int32_t* labels, int rows, int vocab, float* count, hipStream_t stream);
+// In place on logits [rows][V]: the gradient of loss_scale * (mean over counted rows of the negative
+// log-likelihood); nll[row] = the row's negative log-likelihood (0 if its label is outside [0, V)).
+int softmax_xent(int dtype, void* logits, const int32_t* labels, const float* count, float loss_scale, float* nll,
+                 int rows, int V, hipStream_t stream);
+// loss[0] = sum(nll) / count[0] (0 if count is 0).
+int loss_finish(const float* nll, const float* count, int rows, float* loss, hipStream_t stream);
+struct AdamArgs {
+  void* params;   // storage type, updated
+  float* master;  // bf16 storage: fp32 copy of the parameters, updated; ignored for fp32 storage
+  float* grads;
+  float* m;
+  float* v;
+  size_t count;   // multiple of 4
+  float lr, beta1, beta2, eps, weight_decay;
+  int step;       // t >= 1
+  int zero_grads;
+  // weight decay applies everywhere (block_elems = 0) or only where (index mod block_elems) falls in one of
+  // the four ranges [lo, hi)
+  size_t block_elems;
+  size_t lo[4], hi[4];
+};
+int adam(int dtype, const AdamArgs& a, hipStream_t stream);
+
 // ---- misc ------------------------------------------------------------------------
 // max_workgroups > 0 caps the grid: a copy that uses only a few CUs and so runs at a chosen fraction of the
 // memory bandwidth (the emulated link of the pipeline runs).

@@ -613,6 +613,7 @@ template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE>
 int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
   if (!g.a_t && g.b_t) {
     switch (g.epi) {
+      case EPI_NONE: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_NONE>(grp, stream);
       case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS>(grp, stream);
       case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_GELU>(grp, stream);
       case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_RES>(grp, stream);
@@ -643,7 +644,7 @@ void gemm_dma_tile(int config, int& bm, int& bn) {
 }
 
 bool gemm_dma_supported(const GemmArgs& g, int config) {
-  const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
+  const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_NONE || g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
                      (!g.a_t && !g.b_t && (g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD)) ||
                      (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32);
   int bm, bn;

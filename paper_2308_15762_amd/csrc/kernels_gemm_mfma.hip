@@ -308,6 +308,7 @@ template <int BM, int BN, int BK>
 int launch_layout(const GemmArgs& g, const GemmDev& p, int splits, hipStream_t stream) {
   if (!g.a_t && g.b_t) {
     switch (g.epi) {
+      case EPI_NONE: return launch<BM, BN, BK, false, true, EPI_NONE>(p, splits, stream);
       case EPI_BIAS: return launch<BM, BN, BK, false, true, EPI_BIAS>(p, splits, stream);
       case EPI_BIAS_GELU: return launch<BM, BN, BK, false, true, EPI_BIAS_GELU>(p, splits, stream);
       case EPI_BIAS_RES: return launch<BM, BN, BK, false, true, EPI_BIAS_RES>(p, splits, stream);
@@ -327,7 +328,7 @@ int launch_layout(const GemmArgs& g, const GemmDev& p, int splits, hipStream_t s
 }
 
 bool combo_built(const GemmArgs& g) {
-  if (!g.a_t && g.b_t) return g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES;
+  if (!g.a_t && g.b_t) return g.epi == EPI_NONE || g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES;
   if (!g.a_t && !g.b_t) return g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD;
   return g.a_t && g.b_t && g.epi == EPI_ACCUM_F32;
 }

@@ -53,6 +53,15 @@ class ExecArgs(ctypes.Structure):
                 ("stash_mode", ctypes.c_int), ("recompute_scratch", ctypes.c_void_p)]
 
 
+class EndsDesc(ctypes.Structure):
+    _fields_ = [("vocab", ctypes.c_int), ("max_pos", ctypes.c_int), ("final_ln", ctypes.c_int)]
+
+
+class Adam(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float), ("eps", ctypes.c_float),
+                ("weight_decay", ctypes.c_float), ("step", ctypes.c_int), ("zero_grads", ctypes.c_int)]
+
+
 class GemmProblem(ctypes.Structure):
     _fields_ = [("A", ctypes.c_void_p), ("B", ctypes.c_void_p), ("C", ctypes.c_void_p), ("bias", ctypes.c_void_p),
                 ("aux", ctypes.c_void_p), ("aux_out", ctypes.c_void_p),
@@ -90,7 +99,9 @@ EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_
            "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_stash_arena_bytes_input",
            "hanayo_recompute_scratch_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_pipeline_run_actions", "hanayo_device_info",
            "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
-           "hanayo_op_attention_forward", "hanayo_op_attention_backward")
+           "hanayo_op_attention_forward", "hanayo_op_attention_backward",
+           "hanayo_embed_forward", "hanayo_embed_backward", "hanayo_head_workspace_bytes", "hanayo_head_loss",
+           "hanayo_adam_step", "hanayo_chunk_adam_step")
 
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 _descp = ctypes.POINTER(ChunkDesc)
@@ -133,6 +144,14 @@ _lib.hanayo_op_layernorm_backward.argtypes = [_int] + [_vp] * 9 + [_int, _int, _
 _lib.hanayo_op_colsum_add.argtypes = [_int, _vp, _int, _int, _vp, _vp, _vp]
 _lib.hanayo_op_attention_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _int, _int, _int, _int, _int, _vp]
 _lib.hanayo_op_attention_backward.argtypes = [_int] + [_vp] * 7 + [_int] * 5 + [_vp]
+_endsp, _adamp = ctypes.POINTER(EndsDesc), ctypes.POINTER(Adam)
+_lib.hanayo_embed_forward.argtypes = [_descp, _endsp, _vp, _vp, _vp, _vp, _vp]
+_lib.hanayo_embed_backward.argtypes = [_descp, _endsp, _vp, _vp, _vp, _vp, _vp]
+_lib.hanayo_head_workspace_bytes.restype = _sz
+_lib.hanayo_head_workspace_bytes.argtypes = [_descp, _endsp]
+_lib.hanayo_head_loss.argtypes = [_descp, _endsp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.hanayo_adam_step.argtypes = [_adamp, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.hanayo_chunk_adam_step.argtypes = [_adamp, _descp, _vp, _vp, _vp, _vp, _vp, _vp]
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RES, EPI_MUL_DGELU, EPI_ADD, EPI_ACCUM_F32 = range(7)
 
 
@@ -274,6 +293,38 @@ def hanayo_chunk_forward(desc, weights, x, valid_len, y, stash_entry, workspace,
 def hanayo_chunk_backward(desc, weights, grads, dy, valid_len, stash_entry, dx, workspace, stream=None):
     _check(_lib.hanayo_chunk_backward(ctypes.byref(desc), _ptr(weights), _ptr(grads), _ptr(dy), _ptr(valid_len),
                                       _ptr(stash_entry), _ptr(dx), _ptr(workspace), stream))
+
+
+def hanayo_embed_forward(desc, ends, wte, wpe, tokens, x, stream=None):
+    _check(_lib.hanayo_embed_forward(ctypes.byref(desc), ctypes.byref(ends), _ptr(wte), _ptr(wpe), _ptr(tokens), _ptr(x),
+                                     stream))
+
+
+def hanayo_embed_backward(desc, ends, tokens, dx, d_wte, d_wpe, stream=None):
+    _check(_lib.hanayo_embed_backward(ctypes.byref(desc), ctypes.byref(ends), _ptr(tokens), _ptr(dx), _ptr(d_wte),
+                                      _ptr(d_wpe), stream))
+
+
+def hanayo_head_workspace_bytes(desc, ends):
+    v = _lib.hanayo_head_workspace_bytes(ctypes.byref(desc), ctypes.byref(ends))
+    if v == 0:
+        raise HanayoError(EINVAL)
+    return v
+
+
+def hanayo_head_loss(desc, ends, lnf, head, y, labels, loss_scale, loss, dy, d_lnf, d_head, workspace, stream=None):
+    _check(_lib.hanayo_head_loss(ctypes.byref(desc), ctypes.byref(ends), _ptr(lnf), _ptr(head), _ptr(y), _ptr(labels),
+                                 loss_scale, _ptr(loss), _ptr(dy), _ptr(d_lnf), _ptr(d_head), _ptr(workspace), stream))
+
+
+def hanayo_adam_step(adam, dtype, params, master, grads, m, v, count, stream=None):
+    _check(_lib.hanayo_adam_step(ctypes.byref(adam), dtype, _ptr(params), _ptr(master), _ptr(grads), _ptr(m), _ptr(v),
+                                 count, stream))
+
+
+def hanayo_chunk_adam_step(adam, desc, weights, master, grads, m, v, stream=None):
+    _check(_lib.hanayo_chunk_adam_step(ctypes.byref(adam), ctypes.byref(desc), _ptr(weights), _ptr(master), _ptr(grads),
+                                       _ptr(m), _ptr(v), stream))
 
 
 def hanayo_op_gemm(dtype, A, B, C, M, N, K, lda, ldb, ldc, a_t, b_t, epilogue, bias=None, aux=None, aux_out=None,

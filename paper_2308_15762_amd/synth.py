@@ -12,6 +12,16 @@ and beta = 0, activations and upstream gradients N(0, 1), valid lengths
 uniform integers on [lo, hi]; for bf16 workloads every generated value is
 rounded to bf16 (round to nearest even) once, here, so both sides consume
 identical numbers.
+
+The model's ends (embedding, head, loss): vocabulary 50304 for the GPT-like
+workloads (GPT-2's 50257 rounded up to a multiple of 128), 30592 for the
+BERT-like one (BERT's 30522 likewise), 512 for the tiny one; token and position
+tables N(0, 0.02^2), head tied to the token table, final LayerNorm (gamma 1,
+beta 0) for pre-LN models only.  Token ids follow a Zipf law (probability
+proportional to 1 / (id + 1)), so frequent tokens repeat inside a micro-batch as
+they do in text.  GPT-like labels are the next token (none for the last
+position); BERT-like labels are a random token on a seeded 15 % of the valid
+positions and -1 (not counted) elsewhere.
 """
 
 import numpy as np
@@ -21,13 +31,14 @@ SEED_BASE = 0x48414E41
 
 class Workload:
     def __init__(self, name, index, dtype, norm, causal, hidden, heads, ffn, seq, mb,
-                 n_blocks, P, W, M, valid_len_range=None):
+                 n_blocks, P, W, M, valid_len_range=None, vocab=None):
         self.name, self.index, self.dtype = name, index, dtype
         self.norm, self.causal = norm, causal
         self.hidden, self.heads, self.ffn = hidden, heads, ffn
         self.seq, self.mb, self.n_blocks = seq, mb, n_blocks
         self.P, self.W, self.M = P, W, M
         self.valid_len_range = valid_len_range
+        self.vocab = vocab if vocab is not None else (50304 if causal else 30592)
         self.seed = SEED_BASE + index
 
     @property
@@ -38,14 +49,14 @@ class Workload:
         """A copy with some fields replaced (reduced shapes for tests)."""
         w = Workload(self.name, self.index, self.dtype, self.norm, self.causal, self.hidden,
                      self.heads, self.ffn, self.seq, self.mb, self.n_blocks, self.P, self.W,
-                     self.M, self.valid_len_range)
+                     self.M, self.valid_len_range, self.vocab)
         for k, v in kw.items():
             setattr(w, k, v)
         return w
 
 
 WORKLOADS = {
-    "tiny_gpt_fp32": Workload("tiny_gpt_fp32", 0, "fp32", "pre", True, 256, 4, 1024, 128, 2, 1, 2, 1, 4),
+    "tiny_gpt_fp32": Workload("tiny_gpt_fp32", 0, "fp32", "pre", True, 256, 4, 1024, 128, 2, 1, 2, 1, 4, vocab=512),
     "gpt_1024_bf16": Workload("gpt_1024_bf16", 1, "bf16", "pre", True, 1024, 16, 4096, 1024, 4, 2, 4, 2, 8),
     "bert_1024_bf16": Workload("bert_1024_bf16", 2, "bf16", "post", False, 1024, 16, 4096, 512, 8, 3, 4, 1, 16,
                                valid_len_range=(256, 512)),
@@ -147,3 +158,45 @@ def valid_lengths(wl, mb):
     lo, hi = wl.valid_len_range
     rng = rng_for(wl.seed, 4, mb)
     return rng.integers(lo, hi + 1, size=wl.mb).astype(np.int32)
+
+
+# ------------------------------------------------------------------ the model's ends
+
+def ends_params(wl, ln_random=False):
+    """dict(wte [V, H], wpe [seq, H], lnf (gamma, beta) or None); the head is tied to wte."""
+    rng = rng_for(wl.seed, 7)
+    H = wl.hidden
+    p = {"wte": _finish(rng.normal(0.0, 0.02, size=(wl.vocab, H)), wl.dtype),
+         "wpe": _finish(rng.normal(0.0, 0.02, size=(wl.seq, H)), wl.dtype), "lnf": None}
+    if wl.norm == "pre":
+        p["lnf"] = ((_finish(1.0 + 0.1 * rng.normal(size=H), wl.dtype), _finish(0.1 * rng.normal(size=H), wl.dtype))
+                    if ln_random else (np.ones(H, np.float32), np.zeros(H, np.float32)))
+    return p
+
+
+def untied_head(wl):
+    """A separate [V, H] head table, for the runs that do not tie it to the token table."""
+    return _finish(rng_for(wl.seed, 10).normal(0.0, 0.02, size=(wl.vocab, wl.hidden)), wl.dtype)
+
+
+def token_ids(wl, mb):
+    """int32 [mb_size, seq], Zipf-distributed over the vocabulary."""
+    rng = rng_for(wl.seed, 8, mb)
+    w = 1.0 / np.arange(1, wl.vocab + 1)
+    cdf = np.cumsum(w / w.sum())
+    return np.minimum(np.searchsorted(cdf, rng.random(size=(wl.mb, wl.seq))), wl.vocab - 1).astype(np.int32)
+
+
+def labels(wl, mb):
+    """int32 [mb_size, seq]; -1 = position not counted."""
+    tok = token_ids(wl, mb)
+    if wl.causal:
+        out = np.full_like(tok, -1)
+        out[:, :-1] = tok[:, 1:]
+        return out
+    rng = rng_for(wl.seed, 9, mb)
+    picked = rng.random(size=tok.shape) < 0.15
+    vl = valid_lengths(wl, mb)
+    if vl is not None:
+        picked &= np.arange(wl.seq)[None, :] < vl[:, None]
+    return np.where(picked, rng.integers(0, wl.vocab, size=tok.shape), -1).astype(np.int32)
