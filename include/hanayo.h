@@ -270,7 +270,33 @@ typedef struct hanayo_exec_args {
   int lanes;                       /* 0 or 1: everything on hip_stream; 2..4: see below */
   int stash_mode;                  /* HANAYO_STASH_FULL or HANAYO_STASH_INPUT, see below */
   void* recompute_scratch;         /* device; HANAYO_STASH_INPUT only: max(lanes, 1) * hanayo_recompute_scratch_bytes() */
+  const struct hanayo_ends_args* ends; /* NULL, or the model's ends on rank 0 (see below) */
 } hanayo_exec_args;
+
+/*
+ * The model's ends in the executor.  With args->ends set, rank 0 (which holds stage 0 and the last stage in
+ * every wave placement; other ranks ignore the field) builds the input of stage 0 of micro-batch m from
+ * tokens[m] instead of reading act_in, and right after the forward task of the last stage computes loss[m]
+ * and the gradients of loss_scale * loss: the head's and final LayerNorm's are added to d_head / d_lnf, the
+ * one w.r.t. the stage's output goes to loss_grad[m], which that stage's backward task reads instead of
+ * grad_in.  The backward task of stage 0 is followed by the embedding's backward into d_wte / d_wpe.
+ * head may be wte and d_head d_wte (tied weights).  With lanes, the tasks that add to these gradients wait
+ * for one another in list order.
+ */
+typedef struct hanayo_ends_args {
+  hanayo_ends_desc desc;
+  const void* wte;  float* d_wte;        /* device [V][H] */
+  const void* wpe;  float* d_wpe;        /* device [max_pos][H] */
+  const void* head; float* d_head;       /* device [V][H] */
+  const void* lnf;  float* d_lnf;        /* device [2][H]; NULL without final_ln */
+  const int32_t* const* tokens;          /* host [M] -> device int32 [b][s] */
+  const int32_t* const* labels;          /* host [M] -> device int32 [b][s] */
+  float* loss;                           /* device float [M], written */
+  void* const* loss_grad;                /* host [M] -> device [b][s][H], written then read */
+  float loss_scale;
+  void* workspace;                       /* device, max(lanes, 1) * hanayo_ends_workspace_bytes() */
+} hanayo_ends_args;
+size_t hanayo_ends_workspace_bytes(const hanayo_chunk_desc* d, const hanayo_ends_desc* e); /* 0 on a bad descriptor */
 
 /*
  * Stash modes.  HANAYO_STASH_FULL (0): a stash entry holds every tensor the forward pass materialises
@@ -309,14 +335,17 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
  *
  * hanayo_executor_plan reports that plan without touching the GPU:
  *   lane  host [n]     lane of each task
- *   deps  host [n][4]  indices of earlier tasks that task i waits for, -1 = none:
+ *   ends  1: plan as hanayo_executor_run does when args->ends is set
+ *   deps  host [n][5]  indices of earlier tasks that task i waits for, -1 = none:
  *         [0] the local stage producing its input, [1] (B) its own forward,
  *         [2] (F) the backward that last read the stash entry it overwrites,
- *         [3] (B) the previous backward of the same chunk.
+ *         [3] (B) the previous backward of the same chunk,
+ *         [4] (with ends, on rank 0: forward of the last stage, backward of stage 0) the previous task
+ *             that added to the gradients of the embedding tables and the head.
  * Same list checks and error codes as hanayo_executor_run.
  */
-int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int32_t* lane,
-                         int32_t* deps);
+int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int ends,
+                         int32_t* lane, int32_t* deps);
 
 
 /* ------------------------------------------------------------------------- *

@@ -22,6 +22,7 @@
 #include <mutex>
 #include <vector>
 
+#include "ends.h"
 #include "internal.h"
 #include "kernels.h"
 
@@ -58,7 +59,7 @@ int make_plan(const hanayo_task* list, size_t n, int W, Plan& pl) {
 }
 
 // What a task must wait for besides the tasks before it on its own lane.
-enum { DEP_INPUT, DEP_FORWARD, DEP_SLOT, DEP_GRADS, N_DEPS };
+enum { DEP_INPUT, DEP_FORWARD, DEP_SLOT, DEP_GRADS, DEP_ENDS, N_DEPS };
 struct LanePlan {
   std::vector<int32_t> lane;
   std::vector<std::array<int32_t, N_DEPS>> dep;  // task indices, -1 = none
@@ -72,11 +73,14 @@ struct LanePlan {
 //   DEP_FORWARD  (backward) its own forward, which filled the stash entry
 //   DEP_SLOT     (forward) the backward that last read the stash entry it is about to overwrite
 //   DEP_GRADS    (backward) the previous backward of the same chunk: one accumulation at a time
-void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, const Plan& pl,
+//   DEP_ENDS     (with the model's ends: forward of the last stage, backward of stage 0) the previous task that
+//                added to the gradients of the embedding tables and the head, which may be one table
+void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, bool ends, const Plan& pl,
                 LanePlan& lp) {
   const int nchunk = 2 * W, S = 2 * W * P;
   lp.lane.assign(n, 0);
-  lp.dep.assign(n, {-1, -1, -1, -1});
+  lp.dep.assign(n, {-1, -1, -1, -1, -1});
+  int32_t last_ends = -1;
   std::vector<int32_t> f_at((size_t)M * nchunk, -1), b_at((size_t)M * nchunk, -1), last_b(nchunk, -1);
   std::vector<std::vector<int32_t>> slot_reader(nchunk);
   for (int c = 0; c < nchunk; ++c) slot_reader[c].assign(pl.per_chunk[c], -1);
@@ -90,12 +94,14 @@ void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank
       if (stage > 0 && stage_rank(P, stage - 1) == rank) d[DEP_INPUT] = f_at[at - 1];
       d[DEP_SLOT] = slot_reader[tk.chunk][pl.slot[i]];
       f_at[at] = (int32_t)i;
+      if (ends && stage == S - 1) d[DEP_ENDS] = last_ends, last_ends = (int32_t)i;
     } else {
       if (stage < S - 1 && stage_rank(P, stage + 1) == rank) d[DEP_INPUT] = b_at[at + 1];
       d[DEP_FORWARD] = f_at[at];
       d[DEP_GRADS] = last_b[tk.chunk];
       b_at[at] = last_b[tk.chunk] = (int32_t)i;
       slot_reader[tk.chunk][pl.slot[i]] = (int32_t)i;
+      if (ends && stage == 0) d[DEP_ENDS] = last_ends, last_ends = (int32_t)i;
     }
     double ready = 0.0;
     for (int32_t j : d)
@@ -243,8 +249,14 @@ size_t hanayo_recompute_scratch_bytes(const hanayo_chunk_desc* d) {
   return stash_layout(sh).block_bytes * sh.nb + align_up((size_t)sh.T * sh.H * sh.esz, 256);
 }
 
-int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int32_t* lane,
-                         int32_t* deps) {
+size_t hanayo_ends_workspace_bytes(const hanayo_chunk_desc* d, const hanayo_ends_desc* e) {
+  Shape sh;
+  if (make_shape(d, sh) || check_ends(sh, e)) return 0;
+  return align_up((size_t)sh.T * sh.H * sh.esz, 256) + head_workspace_bytes(sh, e->vocab);
+}
+
+int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int ends,
+                         int32_t* lane, int32_t* deps) {
   if (!list || !lane || !deps) return set_error(HANAYO_EINVAL, "executor_plan: NULL argument");
   if (P < 1 || W < 1 || M < 1 || rank < 0 || rank >= P || 2 * W > 255 || lanes < 1 || lanes > kMaxLanes)
     return set_error(HANAYO_EINVAL, "executor_plan: bad P=%d W=%d M=%d rank=%d lanes=%d", P, W, M, rank, lanes);
@@ -254,7 +266,7 @@ int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M,
   rc = make_plan(list, n, W, pl);
   if (rc) return rc;
   LanePlan lp;
-  plan_lanes(list, n, P, W, M, rank, lanes, pl, lp);
+  plan_lanes(list, n, P, W, M, rank, lanes, ends != 0 && rank == 0, pl, lp);
   for (size_t i = 0; i < n; ++i) {
     lane[i] = lp.lane[i];
     for (int k = 0; k < N_DEPS; ++k) deps[i * N_DEPS + k] = lp.dep[i][k];
@@ -288,6 +300,18 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     return set_error(HANAYO_ESTATE, "executor: stash arena holds %zu bytes, plan needs %zu", a->stash_arena_bytes,
                      pl.entries * entry_bytes);
   const int nchunk = 2 * W, S = 2 * W * P;
+  // the model's ends sit on rank 0: stage 0 and stage S - 1
+  const hanayo_ends_args* en = rank == 0 ? a->ends : nullptr;
+  if (en) {
+    rc = check_ends(sh, &en->desc);
+    if (rc) return rc;
+    if (!en->wte || !en->d_wte || !en->wpe || !en->d_wpe || !en->head || !en->d_head || !en->tokens || !en->labels ||
+        !en->loss || !en->loss_grad || !en->workspace || (en->desc.final_ln && (!en->lnf || !en->d_lnf)))
+      return set_error(HANAYO_EINVAL, "executor: ends: NULL argument");
+    for (int m = 0; m < M; ++m)
+      if (!en->tokens[m] || !en->labels[m] || !en->loss_grad[m])
+        return set_error(HANAYO_EINVAL, "executor: ends: micro-batch %d has no tokens, labels or loss-gradient buffer", m);
+  }
   // every pointer the walk will dereference, checked before anything is enqueued
   for (size_t i = 0; i < n; ++i) {
     const hanayo_task& tk = list[i];
@@ -295,19 +319,19 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     const int stage = (int)tk.stage;
     if (!a->weights[tk.chunk] || !a->grads[tk.chunk]) return set_error(HANAYO_EINVAL, "executor: chunk %d has no weights or grads", tk.chunk);
     if (tk.kind == HANAYO_F) {
-      const bool local = stage > 0 && stage_rank(P, stage - 1) == rank;
-      if (!a->act_out[at] || (!local && !a->act_in[at]))
+      const bool given = (stage > 0 && stage_rank(P, stage - 1) == rank) || (en && stage == 0);
+      if (!a->act_out[at] || (!given && !a->act_in[at]))
         return set_error(HANAYO_EINVAL, "executor: missing activation buffer for mb %u chunk %d", tk.mb, tk.chunk);
     } else {
-      const bool local = stage < S - 1 && stage_rank(P, stage + 1) == rank;
-      if (!a->grad_out[at] || (!local && !a->grad_in[at]))
+      const bool given = (stage < S - 1 && stage_rank(P, stage + 1) == rank) || (en && stage == S - 1);
+      if (!a->grad_out[at] || (!given && !a->grad_in[at]))
         return set_error(HANAYO_EINVAL, "executor: missing gradient buffer for mb %u chunk %d", tk.mb, tk.chunk);
     }
   }
   const int lanes = a->lanes < 1 ? 1 : a->lanes;
   if (lanes > kMaxLanes) return set_error(HANAYO_EINVAL, "executor: at most %d lanes", kMaxLanes);
   LanePlan lp;
-  plan_lanes(list, n, P, W, M, rank, lanes, pl, lp);
+  plan_lanes(list, n, P, W, M, rank, lanes, en != nullptr, pl, lp);
   // a task records an event if a task on another lane waits for it
   std::vector<char> signals(n, 0);
   for (size_t i = 0; i < n; ++i)
@@ -329,6 +353,7 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     }
   }
   const size_t work_bytes = work_layout(sh).bytes;
+  const size_t ends_bytes = en ? align_up(act_bytes, 256) + head_workspace_bytes(sh, en->desc.vocab) : 0;
   char* arena = static_cast<char*>(a->stash_arena);
   int live = 0, peak = 0;
   for (size_t i = 0; i < n; ++i) {
@@ -350,16 +375,22 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     if (tk.kind == HANAYO_F) {
       const bool local = stage > 0 && stage_rank(P, stage - 1) == rank;
       const void* x = local ? a->act_out[at - 1] : a->act_in[at];
-      if (recompute) {
-        rc = k::copy_bytes(entry, x, act_bytes, st);
-        if (!rc) rc = chunk_forward(sh, a->weights[tk.chunk], x, vl, a->act_out[at], scratch, st);
-      } else {
-        rc = chunk_forward(sh, a->weights[tk.chunk], x, vl, a->act_out[at], entry, st);
+      // the lane's share of the ends workspace: the embedding's output, then the head's scratch
+      char* ends_ws = en ? static_cast<char*>(en->workspace) + (size_t)lane * ends_bytes : nullptr;
+      if (en && stage == 0) {
+        rc = embed_forward(sh, &en->desc, en->wte, en->wpe, en->tokens[tk.mb], ends_ws, st);
+        x = ends_ws;  // the chunk's forward copies its input into the stash, so the buffer is free after the task
       }
+      if (!rc && recompute) rc = k::copy_bytes(entry, x, act_bytes, st);
+      if (!rc) rc = chunk_forward(sh, a->weights[tk.chunk], x, vl, a->act_out[at], recompute ? scratch : entry, st);
+      if (!rc && en && stage == S - 1)
+        rc = head_loss(sh, &en->desc, en->lnf, en->head, a->act_out[at], en->labels[tk.mb], en->loss_scale,
+                       en->loss + tk.mb, en->loss_grad[tk.mb], en->d_lnf, en->d_head, ends_ws + align_up(act_bytes, 256), st);
       if (++live > peak) peak = live;
     } else {
       const bool local = stage < S - 1 && stage_rank(P, stage + 1) == rank;
       const void* dy = local ? a->grad_out[at + 1] : a->grad_in[at];
+      if (en && stage == S - 1) dy = en->loss_grad[tk.mb];
       void* work = static_cast<char*>(a->workspace) + (size_t)lane * work_bytes;  // one workspace per lane
       const void* stash = entry;
       if (recompute) {  // the forward again, from the stashed input
@@ -367,6 +398,8 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
         stash = scratch;
       }
       if (!rc) rc = chunk_backward(sh, a->weights[tk.chunk], a->grads[tk.chunk], dy, vl, stash, a->grad_out[at], work, st);
+      if (!rc && en && stage == 0)
+        rc = embed_backward(sh, &en->desc, en->tokens[tk.mb], a->grad_out[at], en->d_wte, en->d_wpe, st);
       --live;
     }
     if (rc) break;

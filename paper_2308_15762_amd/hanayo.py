@@ -41,6 +41,19 @@ class ChunkDesc(ctypes.Structure):
                 ("ln_eps", ctypes.c_float)]
 
 
+class EndsDesc(ctypes.Structure):
+    _fields_ = [("vocab", ctypes.c_int), ("max_pos", ctypes.c_int), ("final_ln", ctypes.c_int)]
+
+
+class EndsArgs(ctypes.Structure):
+    _fields_ = [("desc", EndsDesc),
+                ("wte", ctypes.c_void_p), ("d_wte", ctypes.c_void_p), ("wpe", ctypes.c_void_p), ("d_wpe", ctypes.c_void_p),
+                ("head", ctypes.c_void_p), ("d_head", ctypes.c_void_p), ("lnf", ctypes.c_void_p), ("d_lnf", ctypes.c_void_p),
+                ("tokens", ctypes.POINTER(ctypes.c_void_p)), ("labels", ctypes.POINTER(ctypes.c_void_p)),
+                ("loss", ctypes.c_void_p), ("loss_grad", ctypes.POINTER(ctypes.c_void_p)),
+                ("loss_scale", ctypes.c_float), ("workspace", ctypes.c_void_p)]
+
+
 class ExecArgs(ctypes.Structure):
     _fields_ = [("desc", ctypes.POINTER(ChunkDesc)),
                 ("P", ctypes.c_int), ("W", ctypes.c_int), ("M", ctypes.c_int), ("rank", ctypes.c_int),
@@ -50,11 +63,8 @@ class ExecArgs(ctypes.Structure):
                 ("valid_len", ctypes.POINTER(ctypes.c_void_p)),
                 ("stash_arena", ctypes.c_void_p), ("stash_arena_bytes", ctypes.c_size_t),
                 ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p), ("lanes", ctypes.c_int),
-                ("stash_mode", ctypes.c_int), ("recompute_scratch", ctypes.c_void_p)]
-
-
-class EndsDesc(ctypes.Structure):
-    _fields_ = [("vocab", ctypes.c_int), ("max_pos", ctypes.c_int), ("final_ln", ctypes.c_int)]
+                ("stash_mode", ctypes.c_int), ("recompute_scratch", ctypes.c_void_p),
+                ("ends", ctypes.POINTER(EndsArgs))]
 
 
 class Adam(ctypes.Structure):
@@ -101,7 +111,7 @@ EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_
            "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward",
            "hanayo_embed_forward", "hanayo_embed_backward", "hanayo_head_workspace_bytes", "hanayo_head_loss",
-           "hanayo_adam_step", "hanayo_chunk_adam_step")
+           "hanayo_adam_step", "hanayo_chunk_adam_step", "hanayo_ends_workspace_bytes")
 
 _vp, _sz, _int = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
 _descp = ctypes.POINTER(ChunkDesc)
@@ -127,7 +137,7 @@ _lib.hanayo_stash_arena_bytes_input.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_recompute_scratch_bytes.restype = _sz
 _lib.hanayo_recompute_scratch_bytes.argtypes = [_descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
-_lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp]
+_lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _int, _vp, _vp]
 _lib.hanayo_pipeline_run.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), _vp, _vp]
 _lib.hanayo_replay.argtypes = [_vp, _vp, _int, _int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
 _lib.hanayo_actions.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
@@ -149,6 +159,8 @@ _lib.hanayo_embed_forward.argtypes = [_descp, _endsp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_embed_backward.argtypes = [_descp, _endsp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_head_workspace_bytes.restype = _sz
 _lib.hanayo_head_workspace_bytes.argtypes = [_descp, _endsp]
+_lib.hanayo_ends_workspace_bytes.restype = _sz
+_lib.hanayo_ends_workspace_bytes.argtypes = [_descp, _endsp]
 _lib.hanayo_head_loss.argtypes = [_descp, _endsp, _vp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.hanayo_adam_step.argtypes = [_adamp, _int, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.hanayo_chunk_adam_step.argtypes = [_adamp, _descp, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -312,6 +324,23 @@ def hanayo_head_workspace_bytes(desc, ends):
     return v
 
 
+def hanayo_ends_workspace_bytes(desc, ends):
+    v = _lib.hanayo_ends_workspace_bytes(ctypes.byref(desc), ctypes.byref(ends))
+    if v == 0:
+        raise HanayoError(EINVAL)
+    return v
+
+
+def make_ends_args(ends, wte, d_wte, wpe, d_wpe, head, d_head, lnf, d_lnf, tokens, labels, loss, loss_grad, loss_scale,
+                   workspace):
+    """hanayo_ends_args from tensors; tokens, labels, loss_grad are Python lists [M] of tensors."""
+    tabs = [_table(t) for t in (tokens, labels, loss_grad)]
+    a = EndsArgs(ends, _ptr(wte), _ptr(d_wte), _ptr(wpe), _ptr(d_wpe), _ptr(head), _ptr(d_head), _ptr(lnf), _ptr(d_lnf),
+                 tabs[0], tabs[1], _ptr(loss), tabs[2], loss_scale, _ptr(workspace))
+    a._keep = tabs
+    return a
+
+
 def hanayo_head_loss(desc, ends, lnf, head, y, labels, loss_scale, loss, dy, d_lnf, d_head, workspace, stream=None):
     _check(_lib.hanayo_head_loss(ctypes.byref(desc), ctypes.byref(ends), _ptr(lnf), _ptr(head), _ptr(y), _ptr(labels),
                                  loss_scale, _ptr(loss), _ptr(dy), _ptr(d_lnf), _ptr(d_head), _ptr(workspace), stream))
@@ -408,19 +437,19 @@ def _table(items):
     return arr
 
 
-def hanayo_executor_plan(tasks, P, W, M, rank, lanes):
-    """(lane [n], deps [n][4]) of the executor's lane plan; host only."""
+def hanayo_executor_plan(tasks, P, W, M, rank, lanes, ends=False):
+    """(lane [n], deps [n][5]) of the executor's lane plan; host only."""
     tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
     lane = np.zeros(tasks.size, dtype=np.int32)
-    deps = np.zeros((tasks.size, 4), dtype=np.int32)
-    _check(_lib.hanayo_executor_plan(tasks.ctypes.data, tasks.size, P, W, M, rank, lanes, lane.ctypes.data,
+    deps = np.zeros((tasks.size, 5), dtype=np.int32)
+    _check(_lib.hanayo_executor_plan(tasks.ctypes.data, tasks.size, P, W, M, rank, lanes, int(ends), lane.ctypes.data,
                                      deps.ctypes.data))
     return lane, deps
 
 
 def hanayo_executor_run(tasks, desc, P, W, M, rank, weights, grads, act_in, grad_in, act_out, grad_out,
                         valid_len, stash_arena, stash_arena_bytes, workspace, stream=None, lanes=1,
-                        stash_mode=0, recompute_scratch=None):
+                        stash_mode=0, recompute_scratch=None, ends=None):
     """Tables are Python lists of tensors / None: weights, grads [2W]; act_*, grad_* [M*2W]
     indexed mb*2W+chunk; valid_len [M] or None.  Returns the stash peak seen."""
     tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
@@ -428,7 +457,7 @@ def hanayo_executor_run(tasks, desc, P, W, M, rank, weights, grads, act_in, grad
     vl = _table(valid_len) if valid_len is not None else None
     args = ExecArgs(ctypes.pointer(desc), P, W, M, rank, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5],
                     vl, _ptr(stash_arena), stash_arena_bytes, _ptr(workspace), stream, lanes, stash_mode,
-                    _ptr(recompute_scratch))
+                    _ptr(recompute_scratch), ctypes.pointer(ends) if ends is not None else None)
     peak = _int()
     _check(_lib.hanayo_executor_run(tasks.ctypes.data, tasks.size, ctypes.byref(args), ctypes.byref(peak)))
     return peak.value

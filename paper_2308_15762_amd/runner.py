@@ -64,7 +64,9 @@ class GpuRank:
     """Device state of one rank of a workload: per-chunk weights/grads, boundary
     tables, stash arena, workspace; runs a task list through hanayo_executor_run."""
 
-    def __init__(self, wl, rank=0, tasks=None, unique_outputs=True, lanes=1, stash_mode=0):
+    def __init__(self, wl, rank=0, tasks=None, unique_outputs=True, lanes=1, stash_mode=0, ends=False, tied=True):
+        """ends: rank 0 embeds tokens in front of stage 0 and ends the last stage in the loss (tied: the
+        head is the token table itself)."""
         self.wl, self.rank, self.lanes, self.stash_mode = wl, rank, lanes, stash_mode
         self.desc = hn.desc_for(wl)
         P, W, M = wl.P, wl.W, wl.M
@@ -101,20 +103,89 @@ class GpuRank:
         self.valid_len = None
         if wl.valid_len_range is not None:
             self.valid_len = [torch.from_numpy(synth.valid_lengths(wl, m)).cuda() for m in range(M)]
+        self.ends = None
+        if ends and rank == 0:
+            self._init_ends(tied)
+        self.opt = None
+
+    def _init_ends(self, tied):
+        wl, M = self.wl, self.wl.M
+        self.ends_params = p = synth.ends_params(wl)
+        self.ends_desc = e = hn.EndsDesc(wl.vocab, wl.seq, int(p["lnf"] is not None))
+        f32 = lambda shape: torch.zeros(shape, dtype=torch.float32, device="cuda")
+        self.wte, self.wpe = dev(p["wte"], wl.dtype), dev(p["wpe"], wl.dtype)
+        self.d_wte, self.d_wpe = f32(p["wte"].shape), f32(p["wpe"].shape)
+        self.tied = tied
+        if tied:
+            self.head, self.d_head = self.wte, self.d_wte
+        else:
+            self.head_host = synth.untied_head(wl)
+            self.head, self.d_head = dev(self.head_host, wl.dtype), f32(p["wte"].shape)
+        self.lnf = dev(np.concatenate(p["lnf"]), wl.dtype) if p["lnf"] is not None else None
+        self.d_lnf = f32(2 * wl.hidden) if p["lnf"] is not None else None
+        self.tokens = [torch.from_numpy(synth.token_ids(wl, m)).cuda() for m in range(M)]
+        self.labels = [torch.from_numpy(synth.labels(wl, m)).cuda() for m in range(M)]
+        self.loss = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
+        self.loss_grad = [torch.empty_like(self.act_out[0]) for _ in range(M)]
+        self.ends_work = dev_bytes(max(self.lanes, 1) * hn.hanayo_ends_workspace_bytes(self.desc, e))
+        # with ends the executor must not read the synthetic stage-0 inputs and last-stage gradients
+        for m in range(M):
+            self.act_in[m * self.nchunk] = None
+            self.grad_in[m * self.nchunk + self.nchunk - 1] = None
+        self.ends = hn.make_ends_args(e, self.wte, self.d_wte, self.wpe, self.d_wpe, self.head, self.d_head, self.lnf,
+                                      self.d_lnf, self.tokens, self.labels, self.loss, self.loss_grad, 1.0 / M,
+                                      self.ends_work)
+
+    def ends_tensors(self):
+        """[(name, parameter tensor, fp32 gradient tensor)] of the embedding tables, head and final LayerNorm."""
+        out = [("wte", self.wte, self.d_wte), ("wpe", self.wpe, self.d_wpe)]
+        if not self.tied:
+            out.append(("head", self.head, self.d_head))
+        if self.lnf is not None:
+            out.append(("lnf", self.lnf, self.d_lnf))
+        return out
 
     def zero_grads(self):
         for g in self.grads:
             g.zero_()
+        if self.ends is not None:
+            for _, _, g in self.ends_tensors():
+                g.zero_()
 
     def run(self, tasks=None, stream=None):
         wl = self.wl
         return hn.hanayo_executor_run(self.tasks if tasks is None else tasks, self.desc, wl.P, wl.W, wl.M, self.rank,
                                       self.weights, self.grads, self.act_in, self.grad_in, self.act_out,
                                       self.grad_out, self.valid_len, self.arena, self.arena_bytes, self.work, stream, self.lanes,
-                                      self.stash_mode, self.scratch)
+                                      self.stash_mode, self.scratch, self.ends)
 
     def grad_dicts(self, chunk):
         return hn.unpack_params(self.desc, self.grads[chunk].cpu().numpy(), self.params[chunk])
+
+    # ---- the parameter update at the flush
+
+    def init_optimizer(self):
+        """Adam state for every parameter of the rank: fp32 moments, and fp32 master copies for bf16 storage."""
+        bf16 = self.wl.dtype == "bf16"
+        groups = [("chunk", w, g) for w, g in zip(self.weights, self.grads)]
+        if self.ends is not None:
+            groups += [(n, w.view(-1), g.view(-1)) for n, w, g in self.ends_tensors()]
+        self.opt = [dict(kind=k, w=w, g=g, master=w.float() if bf16 else None, m=torch.zeros_like(g),
+                         v=torch.zeros_like(g)) for k, w, g in groups]
+        self.opt_step = 0
+
+    def adam_step(self, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, zero_grads=True, stream=None):
+        """One update of everything the rank owns, to be called after run(): the flush of the iteration.
+        Decay goes to the chunks' matrices and the tables, not to biases and LayerNorm parameters."""
+        self.opt_step += 1
+        dt = hn.BF16 if self.wl.dtype == "bf16" else hn.FP32
+        for o in self.opt:
+            wd = 0.0 if o["kind"] == "lnf" else weight_decay
+            adam = hn.Adam(lr, beta1, beta2, eps, wd, self.opt_step, int(zero_grads))
+            if o["kind"] == "chunk":
+                hn.hanayo_chunk_adam_step(adam, self.desc, o["w"], o["master"], o["g"], o["m"], o["v"], stream)
+            else:
+                hn.hanayo_adam_step(adam, dt, o["w"], o["master"], o["g"], o["m"], o["v"], o["g"].numel(), stream)
 
 
 class GpuPipeline:

@@ -30,11 +30,22 @@ def compare_grads(got, ref, tol, label=""):
     return worst
 
 
-def oracle_rank(wl, rank, tasks):
+def oracle_ends(wl, tied=True):
+    """The `ends` argument of the oracle's rank walk for a workload (float64 copies of the seeded tables)."""
+    p = synth.ends_params(wl)
+    f = lambda a: np.asarray(a, dtype=np.float64)
+    return {"wte": f(p["wte"]), "wpe": f(p["wpe"]), "head": None if tied else f(synth.untied_head(wl)),
+            "lnf": None if p["lnf"] is None else (f(p["lnf"][0]), f(p["lnf"][1])),
+            "tokens": lambda m: synth.token_ids(wl, m), "labels": lambda m: synth.labels(wl, m),
+            "loss_scale": 1.0 / wl.M}
+
+
+def oracle_rank(wl, rank, tasks, ends=None):
     """The oracle's execution of the same list on the same seeded inputs."""
     from oracle import executor as OE
     params = [synth.chunk_params(wl, c) for c in range(2 * wl.W)]
     vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
     lst = [(int(t["kind"]), int(t["mb"]), int(t["chunk"]), int(t["stage"])) for t in tasks]
     return OE.run_rank(lst, wl.P, wl.W, rank, oracle_cfg(wl), params,
-                       lambda m, c: synth.forward_input(wl, m, c), lambda m, c: synth.upstream_grad(wl, m, c), vl)
+                       lambda m, c: synth.forward_input(wl, m, c), lambda m, c: synth.upstream_grad(wl, m, c), vl,
+                       ends=ends if rank == 0 else None)

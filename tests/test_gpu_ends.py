@@ -205,3 +205,168 @@ def test_bad_arguments_are_rejected():
         hn.hanayo_adam_step(hn.Adam(1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 0), hn.BF16, buf, None, buf, buf, buf, 16)      # no master
     with pytest.raises(hn.HanayoError):
         hn.hanayo_adam_step(hn.Adam(1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 0), hn.FP32, buf, None, buf, buf, buf, 18)      # count % 4
+
+
+# ------------------------------------------------------------------ the ends inside the executor
+
+from oracle import ends as _OE  # noqa: E402
+from helpers import GpuRank, compare_grads, oracle_ends, oracle_rank  # noqa: E402
+
+W = synth.WORKLOADS
+RANK_CASES = {
+    # BASELINE configuration 1 in full (P=2, W=1, M=4; vocabulary 512)
+    "tiny_gpt_fp32": W["tiny_gpt_fp32"],
+    # the benchmark schedule (P=4, W=2, M=8) on a reduced chunk, ragged vocabulary
+    "gpt_sched_small": W["gpt_1024_bf16"].scaled(hidden=128, heads=2, ffn=512, seq=128, mb=1, vocab=1000),
+    # post-LN, key padding, masked-LM labels, no final LayerNorm
+    "bert_sched_small": W["bert_1024_bf16"].scaled(hidden=128, heads=2, ffn=512, seq=96, mb=2, n_blocks=2,
+                                                   valid_len_range=(48, 96), vocab=512),
+    # all stages on one rank
+    "single_rank": W["tiny_gpt_fp32"].scaled(P=1, W=2, M=3, hidden=64, heads=1, ffn=256, seq=32, vocab=64),
+}
+
+
+def check_rank_with_ends(gpu, ref, tol, label):
+    wl = gpu.wl
+    nchunk = 2 * wl.W
+    for (m, c), y in ref["act_out"].items():
+        e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+        assert e <= tol, "%s act_out mb %d chunk %d: %.3g" % (label, m, c, e)
+    for (m, c), dx in ref["grad_out"].items():
+        e = nerr(host(gpu.grad_out[m * nchunk + c]), dx)
+        assert e <= tol, "%s grad_out mb %d chunk %d: %.3g" % (label, m, c, e)
+    for c in range(nchunk):
+        compare_grads(gpu.grad_dicts(c), ref["grads"][c], tol, "%s chunk %d" % (label, c))
+    loss = host(gpu.loss)
+    for m in range(wl.M):
+        assert abs(loss[m] - ref["loss"][m]) <= tol * abs(ref["loss"][m]), (label, m, loss[m], ref["loss"][m])
+    eg = ref["ends_grads"]
+    assert nerr(host(gpu.d_wte), eg["wte"]) <= tol and nerr(host(gpu.d_wpe), eg["wpe"]) <= tol, label
+    if eg["head"] is not None:
+        assert nerr(host(gpu.d_head), eg["head"]) <= tol, label
+    if eg["lnf"] is not None:
+        H = wl.hidden
+        assert nerr(host(gpu.d_lnf)[:H], eg["lnf"][0]) <= tol and nerr(host(gpu.d_lnf)[H:], eg["lnf"][1]) <= tol, label
+
+
+_REF = {}
+
+
+@pytest.mark.parametrize("tied", [True, False])
+@pytest.mark.parametrize("lanes", [1, 3])
+@pytest.mark.parametrize("name", list(RANK_CASES))
+def test_rank_list_with_ends_matches_oracle(name, lanes, tied):
+    wl = RANK_CASES[name]
+    gpu = GpuRank(wl, 0, lanes=lanes, ends=True, tied=tied)
+    peak = gpu.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0]
+    if (name, tied) not in _REF:
+        _REF[(name, tied)] = oracle_rank(wl, 0, gpu.tasks, oracle_ends(wl, tied))
+    check_rank_with_ends(gpu, _REF[(name, tied)], TOL[wl.dtype], "%s lanes %d tied %s" % (name, lanes, tied))
+
+
+def test_ends_with_input_only_stash():
+    wl = RANK_CASES["gpt_sched_small"]
+    gpu = GpuRank(wl, 0, lanes=2, stash_mode=hn.STASH_INPUT, ends=True)
+    gpu.run()
+    torch.cuda.synchronize()
+    if ("gpt_sched_small", True) not in _REF:
+        _REF[("gpt_sched_small", True)] = oracle_rank(wl, 0, gpu.tasks, oracle_ends(wl, True))
+    check_rank_with_ends(gpu, _REF[("gpt_sched_small", True)], TOL["bf16"], "input-only stash")
+
+
+def test_other_ranks_ignore_the_ends():
+    wl = RANK_CASES["tiny_gpt_fp32"]
+    plain = GpuRank(wl, 1)
+    plain.run()
+    with_ends = GpuRank(wl, 1, ends=True)       # the runner passes no ends for rank 1 ...
+    assert with_ends.ends is None
+    r0 = GpuRank(wl, 0, ends=True)
+    with_ends.ends = r0.ends                     # ... so hand rank 0's to the library, which must ignore them
+    with_ends.run()
+    torch.cuda.synchronize()
+    for a, b in zip(plain.act_out + plain.grad_out, with_ends.act_out + with_ends.grad_out):
+        assert torch.equal(a, b)
+    for a, b in zip(plain.grads, with_ends.grads):
+        assert nerr(host(b), host(a)) <= 1e-6    # fp32 atomics: the order of a few additions is not fixed
+    assert float(r0.loss.min()) == -1.0          # untouched
+
+
+def test_ends_arguments_are_checked():
+    wl = RANK_CASES["tiny_gpt_fp32"]
+    gpu = GpuRank(wl, 0, ends=True)
+    keep = gpu.ends.desc.vocab
+    gpu.ends.desc.vocab = 13
+    with pytest.raises(hn.HanayoError):
+        gpu.run()
+    gpu.ends.desc.vocab = keep
+    gpu.ends.loss = None
+    with pytest.raises(hn.HanayoError):
+        gpu.run()
+
+
+@pytest.mark.parametrize("name", ["tiny_gpt_fp32", "gpt_sched_small"])
+def test_two_training_iterations(name):
+    """Two iterations of rank 0: run the list, update every parameter with Adam at the flush (which also
+    clears the gradients), run again.  The second iteration's losses depend on every update of the first.
+    Adam's eps is set near the largest gradient magnitudes: with the usual 1e-8 the first update is
+    lr * sign(g), and the sign of an entry whose gradient is below its own rounding noise is not something
+    two correct implementations agree on."""
+    wl = RANK_CASES[name]
+    lr, b1, b2, eps, wd = 2.0 ** -9, 0.875, 0.9375, 1.0, 0.5
+    gpu = GpuRank(wl, 0, lanes=2, ends=True)
+    gpu.init_optimizer()
+    losses = []
+    for _ in range(2):
+        gpu.run()
+        losses.append(host(gpu.loss).copy())
+        gpu.adam_step(lr, b1, b2, eps, wd)
+    torch.cuda.synchronize()
+    # the oracle's two iterations
+    nchunk = 2 * wl.W
+    f = lambda a: np.asarray(a, dtype=np.float64)
+    params = [[{k: f(v) for k, v in blk.items()} for blk in synth.chunk_params(wl, c)] for c in range(nchunk)]
+    ends = oracle_ends(wl, True)
+    lst = [(int(t["kind"]), int(t["mb"]), int(t["chunk"]), int(t["stage"])) for t in gpu.tasks]
+    state = {}
+
+    def update(key, p, g, decay):
+        m, v = state.get(key, (np.zeros_like(p), np.zeros_like(p)))
+        q, m, v = _OE.adam_step(p, g, m, v, it + 1, lr, b1, b2, eps, wd if decay else 0.0)
+        state[key] = (m, v)
+        return q
+
+    from oracle import executor as OX
+    from helpers import oracle_cfg
+    vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
+    want_losses = []
+    for it in range(2):
+        out = OX.run_rank(lst, wl.P, wl.W, 0, oracle_cfg(wl), params, lambda m, c: synth.forward_input(wl, m, c),
+                          lambda m, c: synth.upstream_grad(wl, m, c), vl, ends=ends)
+        want_losses.append([out["loss"][m] for m in range(wl.M)])
+        for c in range(nchunk):
+            for bi, blk in enumerate(params[c]):
+                for k in blk:
+                    blk[k] = update((c, bi, k), blk[k], out["grads"][c][bi][k], k in ("wqkv", "wo", "w1", "w2"))
+        eg = out["ends_grads"]
+        ends["wte"] = update("wte", ends["wte"], eg["wte"], True)
+        ends["wpe"] = update("wpe", ends["wpe"], eg["wpe"], True)
+        if ends["lnf"] is not None:
+            ends["lnf"] = (update("lnf_g", ends["lnf"][0], eg["lnf"][0], False), update("lnf_b", ends["lnf"][1], eg["lnf"][1], False))
+    tol = TOL[wl.dtype]
+    for it in range(2):
+        for m in range(wl.M):
+            assert abs(losses[it][m] - want_losses[it][m]) <= tol * want_losses[it][m], (it, m)
+    if wl.dtype == "fp32":   # the update mattered
+        assert max(abs(a - b) for a, b in zip(want_losses[0], want_losses[1])) > 2 * tol * want_losses[0][0]
+    # the updated parameters themselves (fp32 masters for bf16)
+    masters = [o["master"] if o["master"] is not None else o["w"] for o in gpu.opt]
+    for c in range(nchunk):
+        got = hn.unpack_params(gpu.desc, host(masters[c]), params[c])
+        for bi, blk in enumerate(params[c]):
+            for k in blk:
+                assert nerr(got[bi][k], blk[k]) <= tol, (c, bi, k)
+    assert nerr(host(masters[nchunk]).reshape(ends["wte"].shape), ends["wte"]) <= tol
+    for g in gpu.grads + [gpu.d_wte, gpu.d_wpe]:
+        assert not bool(g.any())                 # cleared by the update

@@ -110,9 +110,12 @@ def test_arena_size_follows_the_plan():
 
 # ---------------------------------------------------------------- executor lane plan
 
-def _accesses(P, W, rank, tasks, slot, lane):
-    """Read and write sets of every task over the buffers the executor touches."""
+def _accesses(P, W, rank, tasks, slot, lane, ends=False):
+    """Read and write sets of every task over the buffers the executor touches.  With ends, rank 0's
+    forward of stage 0 / of the last stage and backward of stage 0 also touch the lane's ends workspace,
+    the loss-gradient buffer of the micro-batch and the (possibly shared) table gradients."""
     S_ = 2 * W * P
+    ends = ends and rank == 0
     out = []
     for i, t in enumerate(tasks):
         kind, m, c, stage = (int(t[k]) for k in ("kind", "mb", "chunk", "stage"))
@@ -122,6 +125,11 @@ def _accesses(P, W, rank, tasks, slot, lane):
                 reads.add(("act", m, c - 1))
             writes.add(("act", m, c))
             writes.add(("stash", c, int(slot[i])))
+            if ends and stage in (0, S_ - 1):
+                writes.add(("ends workspace", int(lane[i])))
+            if ends and stage == S_ - 1:
+                writes.add(("loss grad", m))
+                writes.add(("table grads",))
         else:
             reads.add(("stash", c, int(slot[i])))
             if stage < S_ - 1 and S.stage_rank(P, W, stage + 1) == rank:
@@ -129,22 +137,28 @@ def _accesses(P, W, rank, tasks, slot, lane):
             writes.add(("grad", m, c))
             writes.add(("weight grads", c))          # read-modify-write
             writes.add(("workspace", int(lane[i])))
+            if ends and stage == S_ - 1:
+                reads.add(("loss grad", m))
+            if ends and stage == 0:
+                writes.add(("table grads",))
         out.append((reads, writes))
     return out
 
 
+@pytest.mark.parametrize("ends", [False, True])
 @pytest.mark.parametrize("lanes", [1, 2, 3, 4])
 @pytest.mark.parametrize("P,W,M", [(2, 1, 4), (4, 2, 8), (4, 1, 16), (8, 4, 12), (3, 2, 5), (1, 2, 3), (5, 3, 2)])
-def test_lane_plan_orders_every_conflict(P, W, M, lanes):
+def test_lane_plan_orders_every_conflict(P, W, M, lanes, ends):
     """Any two tasks that touch one buffer, at least one of them writing, are ordered by the plan's
     event waits together with the in-order execution of each lane."""
     for rank in range(P):
         tasks = hn.hanayo_schedule(P, W, M, rank)
         n = len(tasks)
-        lane, deps = hn.hanayo_executor_plan(tasks, P, W, M, rank, lanes)
+        lane, deps = hn.hanayo_executor_plan(tasks, P, W, M, rank, lanes, ends)
         assert lane.min() >= 0 and lane.max() < lanes
+        assert ends and rank == 0 or (deps[:, 4] == -1).all()
         _, _, slot = S.stash_plan(S.schedule(P, W, M, rank), W)
-        acc = _accesses(P, W, rank, tasks, slot, lane)
+        acc = _accesses(P, W, rank, tasks, slot, lane, ends)
         before = [0] * n           # bit j set: task j is known to finish before task i starts
         last_on_lane = {}
         for i in range(n):
