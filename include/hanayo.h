@@ -333,9 +333,12 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
  * Results equal those of one lane (a chunk's gradient accumulations keep their
  * list order).  Calls with lanes > 1 on one device are serialised on the host.
  *
+ * The lanes are chosen by list scheduling with the schedule's own costs (forward 1, backward 2).
+ *
  * hanayo_executor_plan reports that plan without touching the GPU:
  *   lane  host [n]     lane of each task
- *   ends  1: plan as hanayo_executor_run does when args->ends is set
+ *   d, e  NULL, or the descriptors of a run with args->ends set: the plan then has the dependencies [4]
+ *         below and counts the head's work (from the shapes) into the forward task of the last stage
  *   deps  host [n][5]  indices of earlier tasks that task i waits for, -1 = none:
  *         [0] the local stage producing its input, [1] (B) its own forward,
  *         [2] (F) the backward that last read the stash entry it overwrites,
@@ -344,8 +347,8 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
  *             that added to the gradients of the embedding tables and the head.
  * Same list checks and error codes as hanayo_executor_run.
  */
-int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int ends,
-                         int32_t* lane, int32_t* deps);
+int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes,
+                         const hanayo_chunk_desc* d, const hanayo_ends_desc* e, int32_t* lane, int32_t* deps);
 
 
 /* ------------------------------------------------------------------------- *

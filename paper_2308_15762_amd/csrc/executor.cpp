@@ -75,8 +75,9 @@ struct LanePlan {
 //   DEP_GRADS    (backward) the previous backward of the same chunk: one accumulation at a time
 //   DEP_ENDS     (with the model's ends: forward of the last stage, backward of stage 0) the previous task that
 //                added to the gradients of the embedding tables and the head, which may be one table
-void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, bool ends, const Plan& pl,
-                LanePlan& lp) {
+// head_cost: with ends, what the head and loss add to the forward task of the last stage, in forward tasks.
+void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, bool ends, double head_cost,
+                const Plan& pl, LanePlan& lp) {
   const int nchunk = 2 * W, S = 2 * W * P;
   lp.lane.assign(n, 0);
   lp.dep.assign(n, {-1, -1, -1, -1, -1});
@@ -84,7 +85,9 @@ void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank
   std::vector<int32_t> f_at((size_t)M * nchunk, -1), b_at((size_t)M * nchunk, -1), last_b(nchunk, -1);
   std::vector<std::vector<int32_t>> slot_reader(nchunk);
   for (int c = 0; c < nchunk; ++c) slot_reader[c].assign(pl.per_chunk[c], -1);
-  std::vector<double> done(n, 0.0), lane_free(lanes, 0.0);
+  std::vector<double> done(n, 0.0), lane_free(lanes, 0.0), cost(n, 0.0);
+  for (size_t i = 0; i < n; ++i)
+    cost[i] = (list[i].kind == HANAYO_F ? 1.0 : 2.0) + (ends && list[i].kind == HANAYO_F && (int)list[i].stage == S - 1 ? head_cost : 0.0);
   for (size_t i = 0; i < n; ++i) {
     const hanayo_task& tk = list[i];
     const size_t at = (size_t)tk.mb * nchunk + tk.chunk;
@@ -113,16 +116,16 @@ void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank
       if (l == 0 || start < best_start) best = l, best_start = start;
     }
     lp.lane[i] = best;
-    done[i] = lane_free[best] = best_start + (tk.kind == HANAYO_F ? 1.0 : 2.0);
+    done[i] = lane_free[best] = best_start + cost[i];
   }
   // In the plan's own clock, how many lanes work during each task: the overlap of its interval
   // with every task's, over its length.
   lp.busy.assign(n, 1.0f);
   for (size_t i = 0; i < n; ++i) {
-    const double ci = list[i].kind == HANAYO_F ? 1.0 : 2.0, si = done[i] - ci;
+    const double ci = cost[i], si = done[i] - ci;
     double overlap = 0.0;
     for (size_t j = 0; j < n; ++j) {
-      const double sj = done[j] - (list[j].kind == HANAYO_F ? 1.0 : 2.0);
+      const double sj = done[j] - cost[j];
       const double lo = si > sj ? si : sj, hi = done[i] < done[j] ? done[i] : done[j];
       if (hi > lo) overlap += hi - lo;
     }
@@ -255,8 +258,15 @@ size_t hanayo_ends_workspace_bytes(const hanayo_chunk_desc* d, const hanayo_ends
   return align_up((size_t)sh.T * sh.H * sh.esz, 256) + head_workspace_bytes(sh, e->vocab);
 }
 
-int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, int ends,
-                         int32_t* lane, int32_t* deps) {
+namespace {
+// The head's GEMM work (logits, d_head, d_hidden: 6 T H V flops) over a forward task's (2 T (4 H^2 + 2 H F) per block).
+double head_cost_of(const Shape& sh, const hanayo_ends_desc& e) {
+  return 3.0 * e.vocab / ((double)sh.nb * (4.0 * sh.H + 2.0 * sh.F));
+}
+}  // namespace
+
+int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes,
+                         const hanayo_chunk_desc* d, const hanayo_ends_desc* e, int32_t* lane, int32_t* deps) {
   if (!list || !lane || !deps) return set_error(HANAYO_EINVAL, "executor_plan: NULL argument");
   if (P < 1 || W < 1 || M < 1 || rank < 0 || rank >= P || 2 * W > 255 || lanes < 1 || lanes > kMaxLanes)
     return set_error(HANAYO_EINVAL, "executor_plan: bad P=%d W=%d M=%d rank=%d lanes=%d", P, W, M, rank, lanes);
@@ -265,8 +275,17 @@ int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M,
   Plan pl;
   rc = make_plan(list, n, W, pl);
   if (rc) return rc;
+  double head_cost = 0.0;
+  if (e) {
+    Shape sh;
+    if (!d) return set_error(HANAYO_EINVAL, "executor_plan: the ends need the chunk descriptor");
+    rc = make_shape(d, sh);
+    if (!rc) rc = check_ends(sh, e);
+    if (rc) return rc;
+    head_cost = head_cost_of(sh, *e);
+  }
   LanePlan lp;
-  plan_lanes(list, n, P, W, M, rank, lanes, ends != 0 && rank == 0, pl, lp);
+  plan_lanes(list, n, P, W, M, rank, lanes, e != nullptr && rank == 0, head_cost, pl, lp);
   for (size_t i = 0; i < n; ++i) {
     lane[i] = lp.lane[i];
     for (int k = 0; k < N_DEPS; ++k) deps[i * N_DEPS + k] = lp.dep[i][k];
@@ -331,7 +350,7 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
   const int lanes = a->lanes < 1 ? 1 : a->lanes;
   if (lanes > kMaxLanes) return set_error(HANAYO_EINVAL, "executor: at most %d lanes", kMaxLanes);
   LanePlan lp;
-  plan_lanes(list, n, P, W, M, rank, lanes, en != nullptr, pl, lp);
+  plan_lanes(list, n, P, W, M, rank, lanes, en != nullptr, en ? head_cost_of(sh, en->desc) : 0.0, pl, lp);
   // a task records an event if a task on another lane waits for it
   std::vector<char> signals(n, 0);
   for (size_t i = 0; i < n; ++i)

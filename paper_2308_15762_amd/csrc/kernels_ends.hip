@@ -149,6 +149,74 @@ __global__ __launch_bounds__(256) void xent_kernel(T* __restrict__ logits, const
   }
 }
 
+// The same for bf16 rows of at most 1024 * 8 * NV columns: the workgroup's 1024 lanes hold the whole row
+// in registers, so the logits are read from memory once.
+template <int NV>
+__global__ __launch_bounds__(1024) void xent_row_kernel(bf16* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                        const float* __restrict__ count, float loss_scale,
+                                                        float* __restrict__ nll, int V) {
+  __shared__ float red_m[16], red_s[16];
+  const int row = blockIdx.x;
+  bf16* lr = logits + (size_t)row * V;
+  const int label = labels[row];
+  const int vecs = V / 8;
+  if (label < 0 || label >= V) {
+    const float zero[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int i = threadIdx.x; i < vecs; i += 1024) store8(lr + i * 8, zero);
+    if (threadIdx.x == 0) nll[row] = 0.f;
+    return;
+  }
+  bf16x8 v[NV];
+  float m = -INFINITY;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = k * 1024 + threadIdx.x;
+    if (i < vecs) {
+      v[k] = *reinterpret_cast<const bf16x8*>(lr + i * 8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) m = fmaxf(m, (float)v[k][j]);
+    }
+  }
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) red_m[threadIdx.x >> 6] = m;
+  __syncthreads();
+  float gm = red_m[0];
+#pragma unroll
+  for (int w = 1; w < 16; ++w) gm = fmaxf(gm, red_m[w]);
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    if (k * 1024 + (int)threadIdx.x < vecs) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) sum += __expf((float)v[k][j] - gm);
+    }
+  }
+  sum = wave_sum(sum);
+  if ((threadIdx.x & 63) == 0) red_s[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  float gs = 0.f;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) gs += red_s[w];
+  const float lse = gm + __logf(gs);
+  const float n = count[0];
+  const float scale = n > 0.f ? loss_scale / n : 0.f;
+#pragma unroll
+  for (int k = 0; k < NV; ++k) {
+    const int i = k * 1024 + threadIdx.x;
+    if (i < vecs) {
+      float g[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const float x = (float)v[k][j];
+        const bool hit = i * 8 + j == label;
+        if (hit) nll[row] = lse - x;
+        g[j] = (__expf(x - lse) - (hit ? 1.f : 0.f)) * scale;
+      }
+      store8(lr + i * 8, g);
+    }
+  }
+}
+
 // loss[0] = sum(nll) / count (0 if nothing was counted).  One workgroup, fixed summation order.
 __global__ __launch_bounds__(256) void loss_finish_kernel(const float* __restrict__ nll, const float* __restrict__ count,
                                                           int rows, float* __restrict__ loss) {
@@ -268,7 +336,11 @@ int count_labels(const int32_t* labels, int rows, int vocab, float* count, hipSt
 int softmax_xent(int dtype, void* logits, const int32_t* labels, const float* count, float loss_scale, float* nll,
                  int rows, int V, hipStream_t stream) {
   if (rows < 1 || V < 8 || V % 8) return set_error(HANAYO_EINVAL, "softmax_xent: bad shape");
-  if (dtype == HANAYO_BF16)
+  if (dtype == HANAYO_BF16 && V > 2048 && V <= 1024 * 8 * 8) {
+    const int nv = (V / 8 + 1023) / 1024;
+    auto kern = nv <= 2 ? xent_row_kernel<2> : nv <= 4 ? xent_row_kernel<4> : nv <= 6 ? xent_row_kernel<6> : xent_row_kernel<8>;
+    hipLaunchKernelGGL(kern, dim3(rows), dim3(1024), 0, stream, (bf16*)logits, labels, count, loss_scale, nll, V);
+  } else if (dtype == HANAYO_BF16)
     hipLaunchKernelGGL(xent_kernel<bf16>, dim3(rows), dim3(256), 0, stream, (bf16*)logits, labels, count, loss_scale, nll, V);
   else
     hipLaunchKernelGGL(xent_kernel<float>, dim3(rows), dim3(256), 0, stream, (float*)logits, labels, count, loss_scale, nll, V);

@@ -137,7 +137,7 @@ _lib.hanayo_stash_arena_bytes_input.argtypes = [_vp, _sz, _int, _descp]
 _lib.hanayo_recompute_scratch_bytes.restype = _sz
 _lib.hanayo_recompute_scratch_bytes.argtypes = [_descp]
 _lib.hanayo_executor_run.argtypes = [_vp, _sz, ctypes.POINTER(ExecArgs), ctypes.POINTER(_int)]
-_lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _int, _vp, _vp]
+_lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _vp, _vp, _vp, _vp]
 _lib.hanayo_pipeline_run.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), _vp, _vp]
 _lib.hanayo_replay.argtypes = [_vp, _vp, _int, _int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
 _lib.hanayo_actions.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
@@ -437,12 +437,15 @@ def _table(items):
     return arr
 
 
-def hanayo_executor_plan(tasks, P, W, M, rank, lanes, ends=False):
-    """(lane [n], deps [n][5]) of the executor's lane plan; host only."""
+def hanayo_executor_plan(tasks, P, W, M, rank, lanes, desc=None, ends=None):
+    """(lane [n], deps [n][5]) of the executor's lane plan; host only.  desc, ends: ChunkDesc and EndsDesc of a
+    run with the model's ends, or None."""
     tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
     lane = np.zeros(tasks.size, dtype=np.int32)
     deps = np.zeros((tasks.size, 5), dtype=np.int32)
-    _check(_lib.hanayo_executor_plan(tasks.ctypes.data, tasks.size, P, W, M, rank, lanes, int(ends), lane.ctypes.data,
+    _check(_lib.hanayo_executor_plan(tasks.ctypes.data, tasks.size, P, W, M, rank, lanes,
+                                     ctypes.addressof(desc) if desc is not None else None,
+                                     ctypes.addressof(ends) if ends is not None else None, lane.ctypes.data,
                                      deps.ctypes.data))
     return lane, deps
 

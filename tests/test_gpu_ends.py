@@ -24,7 +24,8 @@ def ends_desc(wl, final_ln=None):
     return hn.EndsDesc(wl.vocab, wl.seq, int(wl.norm == "pre") if final_ln is None else int(final_ln))
 
 
-CASES = [("fp32", 256, 37, 3, 512), ("fp32", 64, 5, 1, 8), ("bf16", 256, 100, 3, 1000), ("bf16", 1024, 128, 4, 2048)]
+CASES = [("fp32", 256, 37, 3, 512), ("fp32", 64, 5, 1, 8), ("bf16", 256, 100, 3, 1000), ("bf16", 1024, 128, 4, 2048),
+         ("bf16", 128, 64, 2, 8200)]   # the last one: rows of 1025 vectors, one more than the row kernel's 1024 lanes
 
 
 @pytest.mark.parametrize("dtype,hidden,seq,mb,vocab", CASES)

@@ -110,3 +110,50 @@ def test_benchmark_workload_sampled_micro_batch(benchmark_run):
     # property that holds at any size: every gradient buffer is finite and non-trivial
     for g in gpu.grads:
         assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
+
+
+def test_benchmark_workload_with_the_models_ends():
+    """Rank 0's list of the benchmark workload with the embedding in front of stage 0 and the tied head and
+    loss behind stage 15, four lanes: every micro-batch's loss, and the gradients of the token table (which
+    collects the head's and the embedding's contributions of all 8 micro-batches), the position table and
+    the final LayerNorm, against the oracle."""
+    from oracle import ends as OE
+    from helpers import oracle_ends
+    wl = W["gpt_1024_bf16"]
+    tol = TOL["bf16"]
+    gpu = GpuRank(wl, 0, lanes=4, ends=True)
+    gpu.run()
+    torch.cuda.synchronize()
+    cfg = oracle_cfg(wl)
+    last = 2 * wl.W - 1
+    ends = oracle_ends(wl)
+    p0, p3 = synth.chunk_params(wl, 0), synth.chunk_params(wl, last)
+    d_wte = np.zeros_like(ends["wte"])
+    d_wpe = np.zeros_like(ends["wpe"])
+    d_g, d_b = np.zeros(wl.hidden), np.zeros(wl.hidden)
+    loss = host(gpu.loss)
+    for m in range(wl.M):
+        y, _ = OB.chunk_forward(p3, synth.forward_input(wl, m, last), cfg)
+        w_loss, dy, d_head, d_lnf = OE.head_loss(y, ends["labels"](m), ends["wte"], ends["lnf"], cfg.eps, 1.0 / wl.M)
+        assert abs(loss[m] - w_loss) <= tol * w_loss, (m, loss[m], w_loss)
+        d_wte += d_head
+        d_g += d_lnf[0]
+        d_b += d_lnf[1]
+        if m == 5:
+            e = nerr(host(gpu.loss_grad[m]), dy)
+            assert e <= tol, "loss gradient of mb 5: %.3g" % e
+        x = OE.embed_forward(ends["wte"], ends["wpe"], ends["tokens"](m))
+        if m == 5:
+            y0, st = OB.chunk_forward(p0, x, cfg)
+            e = nerr(host(gpu.act_out[m * 2 * wl.W]), y0)
+            assert e <= tol, "stage 0 output of mb 5: %.3g" % e
+        else:
+            _, st = OB.chunk_forward(p0, x, cfg)
+        dx, _ = OB.chunk_backward(cfg, st, synth.upstream_grad(wl, m, 0))
+        del st
+        a, b = OE.embed_backward(ends["tokens"](m), dx, wl.vocab, wl.seq)
+        d_wte += a
+        d_wpe += b
+    assert nerr(host(gpu.d_wte), d_wte) <= tol, "d_wte %.3g" % nerr(host(gpu.d_wte), d_wte)
+    assert nerr(host(gpu.d_wpe), d_wpe) <= tol
+    assert nerr(host(gpu.d_lnf)[:wl.hidden], d_g) <= tol and nerr(host(gpu.d_lnf)[wl.hidden:], d_b) <= tol

@@ -154,7 +154,8 @@ def test_lane_plan_orders_every_conflict(P, W, M, lanes, ends):
     for rank in range(P):
         tasks = hn.hanayo_schedule(P, W, M, rank)
         n = len(tasks)
-        lane, deps = hn.hanayo_executor_plan(tasks, P, W, M, rank, lanes, ends)
+        desc = hn.make_desc(2, 256, 4, 1024, 128, 2, hn.PRE_LN, hn.MASK_CAUSAL, hn.BF16)
+        lane, deps = hn.hanayo_executor_plan(tasks, P, W, M, rank, lanes, desc, hn.EndsDesc(4096, 128, 1) if ends else None)
         assert lane.min() >= 0 and lane.max() < lanes
         assert ends and rank == 0 or (deps[:, 4] == -1).all()
         _, _, slot = S.stash_plan(S.schedule(P, W, M, rank), W)
