@@ -142,3 +142,60 @@ def test_bad_lists_deadlock_or_are_caught():
     bad[0][0], bad[1][0] = bad[1][0], bad[0][0]
     with pytest.raises(AssertionError):
         OP.run_pipeline(bad, P, W, M, cfg, params, xs, dys, vl)
+
+
+# ------------------------------------------------------------------ with the model's ends
+
+def tiny_ends(M, tied, final_ln, H=8, V=11, s=4, b=2, seed=3):
+    rng = np.random.default_rng(seed)
+    tokens = [rng.integers(0, V, size=(b, s)) for _ in range(M)]
+    labels = [rng.integers(-1, V, size=(b, s)) for _ in range(M)]
+    return {"wte": rng.normal(0, 0.5, (V, H)), "wpe": rng.normal(0, 0.5, (s, H)),
+            "head": None if tied else rng.normal(0, 0.5, (V, H)),
+            "lnf": (1.0 + 0.2 * rng.normal(size=H), 0.2 * rng.normal(size=H)) if final_ln else None,
+            "tokens": lambda m: tokens[m], "labels": lambda m: labels[m], "loss_scale": 1.0 / M}
+
+
+@pytest.mark.parametrize("tied,final_ln", [(True, True), (False, False)])
+def test_monolithic_with_ends_by_finite_differences(tied, final_ln):
+    """The mean of the micro-batch losses of the whole model (embedding, 4 stages, head) against central
+    differences, for table entries (a tied table collects two contributions), a chunk weight of the first
+    and of the last stage, and the final LayerNorm."""
+    M = 2
+    cfg, params, _, _, _ = tiny(2, 1, M)
+    ends = tiny_ends(M, tied, final_ln)
+    _, _, grads, losses, eg = OP.monolithic(cfg, params, None, None, ends=ends, M=M)
+    total = lambda: sum(OP.monolithic(cfg, params, None, None, ends=ends, M=M)[3].values()) / M
+    assert abs(total() - sum(losses.values()) / M) == 0.0
+    rng = np.random.default_rng(8)
+    checks = [(ends["wte"], eg["wte"]), (ends["wpe"], eg["wpe"]), (params[0][0]["w1"], grads[0][0]["w1"]),
+              (params[3][0]["wo"], grads[3][0]["wo"])]
+    if not tied:
+        checks.append((ends["head"], eg["head"]))
+    if final_ln:
+        checks += [(ends["lnf"][0], eg["lnf"][0]), (ends["lnf"][1], eg["lnf"][1])]
+    for tab, grad in checks:
+        for _ in range(5):
+            idx = tuple(int(rng.integers(0, n)) for n in tab.shape)
+            keep = tab[idx]
+            tab[idx] = keep + 1e-6
+            up = total()
+            tab[idx] = keep - 1e-6
+            dn = total()
+            tab[idx] = keep
+            assert abs((up - dn) / 2e-6 - grad[idx]) <= 2e-7 * max(1.0, abs(grad[idx])), (tab.shape, idx)
+
+
+@pytest.mark.parametrize("P,W,M", [(2, 1, 4), (3, 2, 5), (1, 1, 2)])
+def test_pipeline_with_ends_equals_monolithic(P, W, M):
+    cfg, params, _, _, _ = tiny(P, W, M, nb=1, s=4, b=2, seed=P * 100 + W * 10 + M)
+    ends = tiny_ends(M, True, True)
+    sim = OS.simulate(P, W, M)
+    ys, dxs, grads, losses, eg = OP.monolithic(cfg, params, None, None, ends=ends, M=M)
+    out = OP.run_pipeline(sim["lists"], P, W, M, cfg, params, None, None, ends=ends)
+    same(out, (ys, dxs, grads))
+    assert out["losses"] == losses
+    # the head's contributions to the tied table arrive in another order than the embedding's: equal up to rounding
+    assert np.allclose(out["ends_grads"]["wte"], eg["wte"], rtol=1e-12, atol=1e-15)
+    assert np.array_equal(out["ends_grads"]["wpe"], eg["wpe"])
+    assert np.array_equal(out["ends_grads"]["lnf"][0], eg["lnf"][0])
