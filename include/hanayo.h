@@ -432,6 +432,8 @@ typedef struct hanayo_pipeline_args {
   const size_t* stash_arena_bytes;
   void* workspace;
   void* hip_stream;
+  const struct hanayo_ends_args* ends; /* NULL, or the model's ends as in hanayo_exec_args (one lane); then x and
+                                          dy are not read and may be NULL.  hanayo_pipeline_run only. */
 } hanayo_pipeline_args;
 
 int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, const hanayo_pipeline_args* args,

@@ -34,11 +34,11 @@ def consistent_ratio(P, W):
     return (2.0 * P - 2.0) / (3.0 * P * W + 2.0 * P - 2.0)
 
 
-def measure(wl, repeat=3):
+def measure(wl, repeat=3, ends=False):
     """Task durations [rank][task] in ms: the median over `repeat` timed runs after one warm-up."""
     import torch
     from .runner import GpuPipeline
-    gpu = GpuPipeline(wl)
+    gpu = GpuPipeline(wl, ends=ends)
     gpu.run()
     torch.cuda.synchronize()
     runs = []
@@ -49,16 +49,19 @@ def measure(wl, repeat=3):
     return gpu.lists, [np.median(np.stack([r[k] for r in runs]), axis=0) for k in range(wl.P)]
 
 
-def report(wl, repeat=3):
+def report(wl, repeat=3, ends=False):
+    """ends: the model starts from token ids and ends in head + loss, which lengthens rank 0's forward task of
+    stage 0 (embedding), its forward task of the last stage (head forward and backward) and its backward task
+    of stage 0 (embedding backward)."""
     from . import hanayo as hn
     P, W, M = wl.P, wl.W, wl.M
-    lists, ms = measure(wl, repeat)
+    lists, ms = measure(wl, repeat, ends)
     makespan, idle = hn.hanayo_replay(lists, P, W, M, ms)
     unit_makespan, unit_idle = hn.hanayo_replay(lists, P, W, M)
     f = np.concatenate([m[t["kind"] == 0] for m, t in zip(ms, lists)])
     b = np.concatenate([m[t["kind"] == 1] for m, t in zip(ms, lists)])
     out = {
-        "workload": wl.name, "P": P, "W": W, "M": M, "stages": 2 * W * P,
+        "workload": wl.name, "P": P, "W": W, "M": M, "stages": 2 * W * P, "model_ends": bool(ends),
         "t_f_ms": float(f.mean()), "t_b_ms": float(b.mean()), "t_b_over_t_f": float(b.mean() / f.mean()),
         "makespan_ms": makespan, "idle_ms_per_rank": [float(v) for v in idle],
         "bubble_ratio_measured_times": float(np.mean(idle) / makespan),
@@ -67,6 +70,10 @@ def report(wl, repeat=3):
         "bubble_ratio_numerator_form_M_eq_P": consistent_ratio(P, W),
         "one_gpu_total_ms": float(sum(m.sum() for m in ms)),
     }
+    if ends:
+        last = [m[(t["kind"] == 0) & (t["stage"] == 2 * W * P - 1)] for m, t in zip(ms, lists)]
+        out["t_f_last_stage_with_head_ms"] = float(np.concatenate(last).mean())
+        out["busy_ms_per_rank"] = [float(m.sum()) for m in ms]
     return out
 
 
@@ -117,6 +124,7 @@ def main():
     ap.add_argument("--workload", default="gpt_1024_bf16")
     ap.add_argument("--M", type=int, default=None, help="micro-batches (default: the workload's)")
     ap.add_argument("--repeat", type=int, default=3)
+    ap.add_argument("--ends", action="store_true", help="embedding in front of stage 0, head + loss behind the last stage")
     ap.add_argument("--links", action="store_true", help="run from action lists with the transfers carried out")
     ap.add_argument("--link-workgroups", type=int, default=0, help="workgroups of a transfer's copy kernel (0 = unrestricted)")
     args = ap.parse_args()
@@ -127,7 +135,7 @@ def main():
     wl = synth.WORKLOADS[args.workload]
     if args.M is not None:
         wl = wl.scaled(M=args.M)
-    print(json.dumps(report_links(wl, args.link_workgroups, args.repeat) if args.links else report(wl, args.repeat)))
+    print(json.dumps(report_links(wl, args.link_workgroups, args.repeat) if args.links else report(wl, args.repeat, args.ends)))
 
 
 if __name__ == "__main__":

@@ -223,6 +223,18 @@ int validate(const hanayo_task* list, size_t n, int P, int W, int M, int rank) {
   return HANAYO_OK;
 }
 
+int check_ends_args(const Shape& sh, const hanayo_ends_args* en, int M) {
+  const int rc = check_ends(sh, &en->desc);
+  if (rc) return rc;
+  if (!en->wte || !en->d_wte || !en->wpe || !en->d_wpe || !en->head || !en->d_head || !en->tokens || !en->labels ||
+      !en->loss || !en->loss_grad || !en->workspace || (en->desc.final_ln && (!en->lnf || !en->d_lnf)))
+    return set_error(HANAYO_EINVAL, "ends: NULL argument");
+  for (int m = 0; m < M; ++m)
+    if (!en->tokens[m] || !en->labels[m] || !en->loss_grad[m])
+      return set_error(HANAYO_EINVAL, "ends: micro-batch %d has no tokens, labels or loss-gradient buffer", m);
+  return HANAYO_OK;
+}
+
 }  // namespace
 }  // namespace hanayo
 
@@ -322,14 +334,8 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
   // the model's ends sit on rank 0: stage 0 and stage S - 1
   const hanayo_ends_args* en = rank == 0 ? a->ends : nullptr;
   if (en) {
-    rc = check_ends(sh, &en->desc);
+    rc = check_ends_args(sh, en, M);
     if (rc) return rc;
-    if (!en->wte || !en->d_wte || !en->wpe || !en->d_wpe || !en->head || !en->d_head || !en->tokens || !en->labels ||
-        !en->loss || !en->loss_grad || !en->workspace || (en->desc.final_ln && (!en->lnf || !en->d_lnf)))
-      return set_error(HANAYO_EINVAL, "executor: ends: NULL argument");
-    for (int m = 0; m < M; ++m)
-      if (!en->tokens[m] || !en->labels[m] || !en->loss_grad[m])
-        return set_error(HANAYO_EINVAL, "executor: ends: micro-batch %d has no tokens, labels or loss-gradient buffer", m);
   }
   // every pointer the walk will dereference, checked before anything is enqueued
   for (size_t i = 0; i < n; ++i) {
@@ -442,8 +448,8 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
 // the lists (poll the ranks in turn, run a rank's head task once its producer has run).
 int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, const hanayo_pipeline_args* a,
                         int* peak_seen, float* const* task_ms) {
-  if (!lists || !counts || !a || !a->desc || !a->weights || !a->grads || !a->x || !a->dy || !a->act || !a->grad ||
-      !a->stash_arena || !a->stash_arena_bytes || !a->workspace)
+  if (!lists || !counts || !a || !a->desc || !a->weights || !a->grads || !a->act || !a->grad || !a->stash_arena ||
+      !a->stash_arena_bytes || !a->workspace || (!a->ends && (!a->x || !a->dy)))
     return set_error(HANAYO_EINVAL, "pipeline: NULL argument");
   const int P = a->P, W = a->W, M = a->M;
   if (P < 1 || W < 1 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "pipeline: bad P=%d W=%d M=%d", P, W, M);
@@ -451,6 +457,11 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
   int rc = prepare_call(a->desc, sh);
   if (rc) return rc;
   const int nchunk = 2 * W, S = nchunk * P;
+  const hanayo_ends_args* en = a->ends;
+  if (en) {
+    rc = check_ends_args(sh, en, M);
+    if (rc) return rc;
+  }
   std::vector<Plan> plans(P);
   const size_t entry_bytes = stash_layout(sh).block_bytes * sh.nb;
   for (int r = 0; r < P; ++r) {
@@ -466,7 +477,8 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
   for (int s = 0; s < S; ++s)
     if (!a->weights[s] || !a->grads[s]) return set_error(HANAYO_EINVAL, "pipeline: stage %d has no weights or grads", s);
   for (int m = 0; m < M; ++m) {
-    if (!a->x[m] || !a->dy[m]) return set_error(HANAYO_EINVAL, "pipeline: micro-batch %d has no input or loss gradient", m);
+    if (!en && (!a->x[m] || !a->dy[m]))
+      return set_error(HANAYO_EINVAL, "pipeline: micro-batch %d has no input or loss gradient", m);
     for (int s = 0; s < S; ++s)
       if (!a->act[(size_t)m * S + s] || !a->grad[(size_t)m * S + s])
         return set_error(HANAYO_EINVAL, "pipeline: missing boundary buffer for mb %d stage %d", m, s);
@@ -517,12 +529,19 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
                   (plans[r].chunk_base[tk.chunk] + (size_t)plans[r].slot[i]) * entry_bytes;
     const int32_t* vl = a->valid_len ? a->valid_len[tk.mb] : nullptr;
     if (task_ms) HIP_TRY(hipEventRecord(ev[2 * k], st));
+    char* ends_ws = en ? static_cast<char*>(en->workspace) : nullptr;  // embedding output, then the head's scratch
     if (tk.kind == HANAYO_F) {
-      const void* x = tk.stage == 0 ? a->x[tk.mb] : a->act[at - 1];
-      rc = chunk_forward(sh, a->weights[tk.stage], x, vl, a->act[at], entry, st);
+      const void* x = tk.stage > 0 ? a->act[at - 1] : en ? ends_ws : a->x[tk.mb];
+      if (en && tk.stage == 0) rc = embed_forward(sh, &en->desc, en->wte, en->wpe, en->tokens[tk.mb], ends_ws, st);
+      if (!rc) rc = chunk_forward(sh, a->weights[tk.stage], x, vl, a->act[at], entry, st);
+      if (!rc && en && (int)tk.stage == S - 1)
+        rc = head_loss(sh, &en->desc, en->lnf, en->head, a->act[at], en->labels[tk.mb], en->loss_scale, en->loss + tk.mb,
+                       en->loss_grad[tk.mb], en->d_lnf, en->d_head, ends_ws + align_up((size_t)sh.T * sh.H * sh.esz, 256), st);
     } else {
-      const void* dy = (int)tk.stage == S - 1 ? a->dy[tk.mb] : a->grad[at + 1];
+      const void* dy = (int)tk.stage < S - 1 ? a->grad[at + 1] : en ? en->loss_grad[tk.mb] : a->dy[tk.mb];
       rc = chunk_backward(sh, a->weights[tk.stage], a->grads[tk.stage], dy, vl, entry, a->grad[at], a->workspace, st);
+      if (!rc && en && tk.stage == 0)
+        rc = embed_backward(sh, &en->desc, en->tokens[tk.mb], a->grad[at], en->d_wte, en->d_wpe, st);
     }
     if (task_ms && !rc) HIP_TRY(hipEventRecord(ev[2 * k + 1], st));
   }
@@ -729,6 +748,7 @@ int hanayo_pipeline_run_actions(const hanayo_action* const* lists, const size_t*
   if (!lists || !counts || !a || !link || !a->desc || !a->weights || !a->grads || !a->x || !a->dy || !a->act || !a->grad ||
       !a->stash_arena || !a->stash_arena_bytes || !a->workspace || !link->act_recv || !link->grad_recv)
     return set_error(HANAYO_EINVAL, "pipeline_actions: NULL argument");
+  if (a->ends) return set_error(HANAYO_EUNSUPPORTED, "pipeline_actions: the model's ends are not part of this call");
   const int P = a->P, W = a->W, M = a->M;
   if (P < 1 || W < 1 || M < 1 || 2 * W > 255 || link->link_workgroups < 0)
     return set_error(HANAYO_EINVAL, "pipeline_actions: bad P=%d W=%d M=%d or link", P, W, M);

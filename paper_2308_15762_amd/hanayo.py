@@ -88,7 +88,7 @@ class PipelineArgs(ctypes.Structure):
                 ("act", ctypes.POINTER(ctypes.c_void_p)), ("grad", ctypes.POINTER(ctypes.c_void_p)),
                 ("valid_len", ctypes.POINTER(ctypes.c_void_p)),
                 ("stash_arena", ctypes.POINTER(ctypes.c_void_p)), ("stash_arena_bytes", ctypes.POINTER(ctypes.c_size_t)),
-                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p)]
+                ("workspace", ctypes.c_void_p), ("hip_stream", ctypes.c_void_p), ("ends", ctypes.POINTER(EndsArgs))]
 
 
 class LinkArgs(ctypes.Structure):
@@ -474,17 +474,17 @@ def _list_tables(lists):
 
 
 def hanayo_pipeline_run(lists, desc, P, W, M, weights, grads, x, dy, act, grad, valid_len, stash_arenas, workspace,
-                        stream=None, timing=False):
+                        stream=None, timing=False, ends=None):
     """All P ranks' lists on this device with true dataflow.  Tables are Python lists of tensors:
     weights, grads [S]; x, dy [M]; act, grad [M*S] indexed mb*S+stage; valid_len [M] or None;
     stash_arenas [P].  Returns (stash peaks [P], per-rank arrays of task durations in ms or None)."""
     lists, ptrs, counts = _list_tables(lists)
-    tabs = [_table(t) for t in (weights, grads, x, dy, act, grad)]
+    tabs = [_table(t) if t is not None else None for t in (weights, grads, x, dy, act, grad)]
     vl = _table(valid_len) if valid_len is not None else None
     arenas = _table(stash_arenas)
     arena_bytes = (ctypes.c_size_t * P)(*[t.numel() * t.element_size() for t in stash_arenas])
     args = PipelineArgs(ctypes.pointer(desc), P, W, M, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5], vl,
-                        arenas, arena_bytes, _ptr(workspace), stream)
+                        arenas, arena_bytes, _ptr(workspace), stream, ctypes.pointer(ends) if ends is not None else None)
     peaks = (ctypes.c_int * P)()
     ms = [np.zeros(t.size, dtype=np.float32) for t in lists] if timing else None
     ms_tab = (ctypes.c_void_p * P)(*[a.ctypes.data for a in ms]) if timing else None
@@ -528,7 +528,7 @@ def hanayo_replay_actions(lists, P, W, M, t_f=1.0, t_b=2.0, t_c=0.0, prefetch=Fa
 
 def hanayo_pipeline_run_actions(lists, desc, P, W, M, weights, grads, x, dy, act, grad, valid_len, stash_arenas,
                                 workspace, act_recv, grad_recv, async_copies=True, link_workgroups=0, stream=None,
-                                timing=False):
+                                timing=False, ends=None):
     """All P ranks' ACTION lists on this device, transfers carried out as device copies (see include/hanayo.h).
     act_recv, grad_recv: lists [M*S] of tensors or None.  Returns (stash peaks [P], per-rank arrays of action
     durations in ms or None)."""
@@ -540,7 +540,7 @@ def hanayo_pipeline_run_actions(lists, desc, P, W, M, weights, grads, x, dy, act
     arenas = _table(stash_arenas)
     arena_bytes = (ctypes.c_size_t * P)(*[t.numel() * t.element_size() for t in stash_arenas])
     args = PipelineArgs(ctypes.pointer(desc), P, W, M, tabs[0], tabs[1], tabs[2], tabs[3], tabs[4], tabs[5], vl,
-                        arenas, arena_bytes, _ptr(workspace), stream)
+                        arenas, arena_bytes, _ptr(workspace), stream, ctypes.pointer(ends) if ends is not None else None)
     link = LinkArgs(_table(act_recv), _table(grad_recv), int(bool(async_copies)), int(link_workgroups))
     peaks = (ctypes.c_int * P)()
     ms = [np.zeros(t.size, dtype=np.float32) for t in lists] if timing else None

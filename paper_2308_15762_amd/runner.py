@@ -60,6 +60,45 @@ class GpuChunk:
         return hn.unpack_params(self.desc, self.grads.cpu().numpy(), self.params)
 
 
+class _EndsState:
+    """Device state of the model's ends (tables, their gradients, tokens, labels, losses, workspace), set
+    as attributes on the GpuRank / GpuPipeline that owns it."""
+
+    @staticmethod
+    def init(o, wl, desc, lanes, like, tied):
+        M = wl.M
+        o.ends_params = p = synth.ends_params(wl)
+        o.ends_desc = e = hn.EndsDesc(wl.vocab, wl.seq, int(p["lnf"] is not None))
+        f32 = lambda shape: torch.zeros(shape, dtype=torch.float32, device="cuda")
+        o.wte, o.wpe = dev(p["wte"], wl.dtype), dev(p["wpe"], wl.dtype)
+        o.d_wte, o.d_wpe = f32(p["wte"].shape), f32(p["wpe"].shape)
+        o.tied = tied
+        if tied:
+            o.head, o.d_head = o.wte, o.d_wte
+        else:
+            o.head_host = synth.untied_head(wl)
+            o.head, o.d_head = dev(o.head_host, wl.dtype), f32(p["wte"].shape)
+        o.lnf = dev(np.concatenate(p["lnf"]), wl.dtype) if p["lnf"] is not None else None
+        o.d_lnf = f32(2 * wl.hidden) if p["lnf"] is not None else None
+        o.tokens = [torch.from_numpy(synth.token_ids(wl, m)).cuda() for m in range(M)]
+        o.labels = [torch.from_numpy(synth.labels(wl, m)).cuda() for m in range(M)]
+        o.loss = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
+        o.loss_grad = [torch.empty_like(like) for _ in range(M)]
+        o.ends_work = dev_bytes(max(lanes, 1) * hn.hanayo_ends_workspace_bytes(desc, e))
+        o.ends = hn.make_ends_args(e, o.wte, o.d_wte, o.wpe, o.d_wpe, o.head, o.d_head, o.lnf, o.d_lnf, o.tokens,
+                                   o.labels, o.loss, o.loss_grad, 1.0 / M, o.ends_work)
+
+    @staticmethod
+    def tensors(o):
+        """[(name, parameter tensor, fp32 gradient tensor)] of the embedding tables, head and final LayerNorm."""
+        out = [("wte", o.wte, o.d_wte), ("wpe", o.wpe, o.d_wpe)]
+        if not o.tied:
+            out.append(("head", o.head, o.d_head))
+        if o.lnf is not None:
+            out.append(("lnf", o.lnf, o.d_lnf))
+        return out
+
+
 class GpuRank:
     """Device state of one rank of a workload: per-chunk weights/grads, boundary
     tables, stash arena, workspace; runs a task list through hanayo_executor_run."""
@@ -109,41 +148,14 @@ class GpuRank:
         self.opt = None
 
     def _init_ends(self, tied):
-        wl, M = self.wl, self.wl.M
-        self.ends_params = p = synth.ends_params(wl)
-        self.ends_desc = e = hn.EndsDesc(wl.vocab, wl.seq, int(p["lnf"] is not None))
-        f32 = lambda shape: torch.zeros(shape, dtype=torch.float32, device="cuda")
-        self.wte, self.wpe = dev(p["wte"], wl.dtype), dev(p["wpe"], wl.dtype)
-        self.d_wte, self.d_wpe = f32(p["wte"].shape), f32(p["wpe"].shape)
-        self.tied = tied
-        if tied:
-            self.head, self.d_head = self.wte, self.d_wte
-        else:
-            self.head_host = synth.untied_head(wl)
-            self.head, self.d_head = dev(self.head_host, wl.dtype), f32(p["wte"].shape)
-        self.lnf = dev(np.concatenate(p["lnf"]), wl.dtype) if p["lnf"] is not None else None
-        self.d_lnf = f32(2 * wl.hidden) if p["lnf"] is not None else None
-        self.tokens = [torch.from_numpy(synth.token_ids(wl, m)).cuda() for m in range(M)]
-        self.labels = [torch.from_numpy(synth.labels(wl, m)).cuda() for m in range(M)]
-        self.loss = torch.full((M,), -1.0, dtype=torch.float32, device="cuda")
-        self.loss_grad = [torch.empty_like(self.act_out[0]) for _ in range(M)]
-        self.ends_work = dev_bytes(max(self.lanes, 1) * hn.hanayo_ends_workspace_bytes(self.desc, e))
+        _EndsState.init(self, self.wl, self.desc, self.lanes, self.act_out[0], tied)
         # with ends the executor must not read the synthetic stage-0 inputs and last-stage gradients
-        for m in range(M):
+        for m in range(self.wl.M):
             self.act_in[m * self.nchunk] = None
             self.grad_in[m * self.nchunk + self.nchunk - 1] = None
-        self.ends = hn.make_ends_args(e, self.wte, self.d_wte, self.wpe, self.d_wpe, self.head, self.d_head, self.lnf,
-                                      self.d_lnf, self.tokens, self.labels, self.loss, self.loss_grad, 1.0 / M,
-                                      self.ends_work)
 
     def ends_tensors(self):
-        """[(name, parameter tensor, fp32 gradient tensor)] of the embedding tables, head and final LayerNorm."""
-        out = [("wte", self.wte, self.d_wte), ("wpe", self.wpe, self.d_wpe)]
-        if not self.tied:
-            out.append(("head", self.head, self.d_head))
-        if self.lnf is not None:
-            out.append(("lnf", self.lnf, self.d_lnf))
-        return out
+        return _EndsState.tensors(self)
 
     def zero_grads(self):
         for g in self.grads:
@@ -193,7 +205,8 @@ class GpuPipeline:
     gradients per micro-batch, every stage-boundary buffer, one stash arena per rank; runs the P task
     lists with true dataflow through hanayo_pipeline_run."""
 
-    def __init__(self, wl):
+    def __init__(self, wl, ends=False):
+        """ends: the model starts from token ids and ends in the loss (tied head), see GpuRank."""
         self.wl = wl
         self.desc = hn.desc_for(wl)
         P, W, M = wl.P, wl.W, wl.M
@@ -214,16 +227,23 @@ class GpuPipeline:
         self.valid_len = None
         if wl.valid_len_range is not None:
             self.valid_len = [torch.from_numpy(synth.valid_lengths(wl, m)).cuda() for m in range(M)]
+        self.ends = None
+        if ends:
+            _EndsState.init(self, wl, self.desc, 1, self.act[0], True)
+            self.x = self.dy = None
 
     def zero_grads(self):
         for g in self.grads:
             g.zero_()
+        if self.ends is not None:
+            for _, _, g in _EndsState.tensors(self):
+                g.zero_()
 
     def run(self, lists=None, timing=False, stream=None):
         wl = self.wl
         return hn.hanayo_pipeline_run(self.lists if lists is None else lists, self.desc, wl.P, wl.W, wl.M,
                                       self.weights, self.grads, self.x, self.dy, self.act, self.grad, self.valid_len,
-                                      self.arenas, self.work, stream, timing)
+                                      self.arenas, self.work, stream, timing, self.ends)
 
     def grad_dicts(self, stage):
         return hn.unpack_params(self.desc, self.grads[stage].cpu().numpy(), self.params[stage])
@@ -248,4 +268,4 @@ class GpuPipeline:
         return hn.hanayo_pipeline_run_actions(self.actions if lists is None else lists, self.desc, wl.P, wl.W, wl.M,
                                               self.weights, self.grads, self.x, self.dy, self.act, self.grad,
                                               self.valid_len, self.arenas, self.work, self.act_recv, self.grad_recv,
-                                              async_copies, link_workgroups, stream, timing)
+                                              async_copies, link_workgroups, stream, timing, self.ends)

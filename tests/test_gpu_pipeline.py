@@ -203,3 +203,55 @@ def test_links_report_on_a_small_pipeline():
     for rep in (fast, slow):
         assert rep["makespan_ms_t_c_zero"] <= rep["makespan_ms_prefetch"] * (1 + 1e-9)
         assert rep["makespan_ms_prefetch"] <= rep["makespan_ms_no_prefetch"] * (1 + 1e-9)
+
+
+# ------------------------------------------------------------------ the whole model: tokens in, loss out
+
+ENDS_CASES = {
+    "tiny_gpt_fp32": W["tiny_gpt_fp32"],
+    "gpt_1024_small": W["gpt_1024_bf16"].scaled(hidden=128, heads=2, ffn=512, seq=128, mb=1, vocab=1000),
+    "bert_small": W["bert_1024_bf16"].scaled(hidden=128, heads=2, ffn=512, seq=96, mb=2, n_blocks=1, M=6,
+                                             valid_len_range=(48, 96), vocab=512),
+}
+
+
+@pytest.mark.parametrize("name", list(ENDS_CASES))
+def test_pipeline_with_the_models_ends_matches_the_model_without_a_pipeline(name):
+    """Token ids in, losses out: embedding, all 2WP stages under the wave schedule, tied head and loss, against
+    the oracle's non-pipelined model (losses, gradients of the tables, of the final LayerNorm, of every stage)."""
+    from helpers import oracle_ends
+    wl = ENDS_CASES[name]
+    tol = depth_tolerance(wl)
+    gpu = GpuPipeline(wl, ends=True)
+    gpu.run()
+    torch.cuda.synchronize()
+    S = gpu.S
+    params = [synth.stage_params(wl, s) for s in range(S)]
+    vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
+    ys, dxs, grads, losses, eg = OP.monolithic(oracle_cfg(wl), params, None, None, vl, ends=oracle_ends(wl), M=wl.M)
+    loss = host(gpu.loss)
+    for m in range(wl.M):
+        assert abs(loss[m] - losses[m]) <= tol * losses[m], (m, loss[m], losses[m])
+        assert nerr(host(gpu.act[m * S + S - 1]), ys[m]) <= tol
+        assert nerr(host(gpu.grad[m * S]), dxs[m]) <= tol
+    for s in range(S):
+        compare_grads(gpu.grad_dicts(s), grads[s], tol, "%s stage %d" % (name, s))
+    assert nerr(host(gpu.d_wte), eg["wte"]) <= tol and nerr(host(gpu.d_wpe), eg["wpe"]) <= tol
+    if eg["lnf"] is not None:
+        H = wl.hidden
+        assert nerr(host(gpu.d_lnf)[:H], eg["lnf"][0]) <= tol and nerr(host(gpu.d_lnf)[H:], eg["lnf"][1]) <= tol
+
+
+def test_pipeline_arguments_with_and_without_ends():
+    wl = ENDS_CASES["tiny_gpt_fp32"]
+    gpu = GpuPipeline(wl)
+    with pytest.raises(hn.HanayoError) as e:        # neither inputs nor ends
+        hn.hanayo_pipeline_run(gpu.lists, gpu.desc, wl.P, wl.W, wl.M, gpu.weights, gpu.grads, None, None, gpu.act, gpu.grad,
+                               None, gpu.arenas, gpu.work)
+    assert e.value.code == hn.EINVAL
+    # the action-list run takes the same argument block; there the ends are refused, not ignored
+    gpu.enable_links()
+    gpu.ends = GpuPipeline(wl, ends=True).ends
+    with pytest.raises(hn.HanayoError) as e:
+        gpu.run_actions()
+    assert e.value.code == hn.EUNSUPPORTED
