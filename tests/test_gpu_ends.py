@@ -1,15 +1,17 @@
 """GPU parity of the model's ends (embedding, head + loss) and the Adam step against the oracle,
 through the C ABI, on seeded inputs: tiny fp32 shapes, bf16 shapes that span several GEMM tiles with a
-ragged vocabulary, and the benchmark workload's head at its full size."""
+ragged vocabulary, and the benchmark workload's head at its full size; then the same inside the executor
+(rank 0's whole list with ends) and over two training iterations."""
 
 import numpy as np
 import pytest
 import torch
 
 from oracle import ends as OE
+from oracle import executor as OX
 from paper_2308_15762_amd import hanayo as hn
 from paper_2308_15762_amd import synth
-from helpers import TOL, dev, dev_bytes, host, nerr
+from helpers import TOL, GpuRank, compare_grads, dev, dev_bytes, host, nerr, oracle_cfg, oracle_ends, oracle_rank
 
 pytestmark = pytest.mark.gpu
 
@@ -210,9 +212,6 @@ def test_bad_arguments_are_rejected():
 
 # ------------------------------------------------------------------ the ends inside the executor
 
-from oracle import ends as _OE  # noqa: E402
-from helpers import GpuRank, compare_grads, oracle_ends, oracle_rank  # noqa: E402
-
 W = synth.WORKLOADS
 RANK_CASES = {
     # BASELINE configuration 1 in full (P=2, W=1, M=4; vocabulary 512)
@@ -334,12 +333,10 @@ def test_two_training_iterations(name):
 
     def update(key, p, g, decay):
         m, v = state.get(key, (np.zeros_like(p), np.zeros_like(p)))
-        q, m, v = _OE.adam_step(p, g, m, v, it + 1, lr, b1, b2, eps, wd if decay else 0.0)
+        q, m, v = OE.adam_step(p, g, m, v, it + 1, lr, b1, b2, eps, wd if decay else 0.0)
         state[key] = (m, v)
         return q
 
-    from oracle import executor as OX
-    from helpers import oracle_cfg
     vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
     want_losses = []
     for it in range(2):
