@@ -33,8 +33,10 @@ struct HeadLayout {
   size_t count;    // float
   size_t partial;  // [kMaxPartialRows][2H] float
   size_t logits;   // [T][V]
+  size_t split;    // [kHeadSplit][T][H] float: partial products of the d_hn GEMM when its K (= V) is split
   size_t bytes;
 };
+constexpr int kHeadSplit = 4;
 
 HeadLayout head_layout(const Shape& sh, int vocab) {
   HeadLayout L{};
@@ -52,6 +54,7 @@ HeadLayout head_layout(const Shape& sh, int vocab) {
   L.count = take(sizeof(float));
   L.partial = take((size_t)kMaxPartialRows * 2 * sh.H * sizeof(float));
   L.logits = take((size_t)sh.T * vocab * sh.esz);
+  L.split = take((size_t)kHeadSplit * sh.T * sh.H * sizeof(float));
   L.bytes = at;
   return L;
 }
@@ -95,12 +98,20 @@ int head_loss(const Shape& sh, const hanayo_ends_desc* e, const void* lnf, const
     hn = ws + L.hn;
   }
   TRY(k::count_labels(labels, T, V, count, st));
+  // The vocabulary is rarely a multiple of the largest GEMM tile (256): the rows of the table up to the last such
+  // multiple go out as one launch that may use it, the few rows left as a second, small one.
+  const int v_main = V >= 512 ? V / 256 * 256 : V, v_rest = V - v_main;
+  const char* head_rest = static_cast<const char*>(head) + (size_t)v_main * H * sh.esz;
   // logits[T][V] = hn[T][H] head[V][H]^T
   k::GemmArgs g{};
   g.A = hn; g.B = head; g.C = ws + L.logits;
-  g.M = T; g.N = V; g.K = H; g.lda = H; g.ldb = H; g.ldc = V;
+  g.M = T; g.N = v_main; g.K = H; g.lda = H; g.ldb = H; g.ldc = V;
   g.a_t = false; g.b_t = false; g.epi = k::EPI_NONE;
   TRY(k::gemm(sh.dtype, g, st));
+  if (v_rest) {
+    g.B = head_rest; g.C = ws + L.logits + (size_t)v_main * sh.esz; g.N = v_rest;
+    TRY(k::gemm(sh.dtype, g, st));
+  }
   // in place: logits -> gradient of loss_scale * loss w.r.t. the logits
   TRY(k::softmax_xent(sh.dtype, ws + L.logits, labels, count, loss_scale, nll, T, V, st));
   TRY(k::loss_finish(nll, count, T, loss, st));
@@ -109,13 +120,40 @@ int head_loss(const Shape& sh, const hanayo_ends_desc* e, const void* lnf, const
   gw.A = ws + L.logits; gw.B = hn; gw.C = d_head;
   gw.M = V; gw.N = H; gw.K = T; gw.lda = V; gw.ldb = H; gw.ldc = H;
   gw.a_t = true; gw.b_t = true; gw.epi = k::EPI_ACCUM_F32;
+  gw.M = v_main;
   TRY(k::gemm(sh.dtype, gw, st));
+  if (v_rest) {
+    gw.A = ws + L.logits + (size_t)v_main * sh.esz; gw.C = d_head + (size_t)v_main * H; gw.M = v_rest;
+    TRY(k::gemm(sh.dtype, gw, st));
+  }
   // d_hn[T][H] = dlogits[T][V] head[V][H]
   k::GemmArgs gx{};
   gx.A = ws + L.logits; gx.B = head; gx.C = e->final_ln ? static_cast<void*>(ws + L.d_hn) : dy;
   gx.M = T; gx.N = H; gx.K = V; gx.lda = V; gx.ldb = H; gx.ldc = H;
   gx.a_t = false; gx.b_t = true; gx.epi = k::EPI_NONE;
-  TRY(k::gemm(sh.dtype, gx, st));
+  // The output has T H / 256^2 tiles (64 for 4096 x 1024) and the contraction runs over the whole vocabulary:
+  // where the largest tile would leave most of the chip idle, K is cut into kHeadSplit slices that go out as one
+  // grouped launch into fp32 partial products, summed by a small kernel.
+  const int slice = (V / kHeadSplit) / 64 * 64;
+  const long tiles256 = (long)(T / 256) * (H / 256);
+  bool split = sh.dtype == HANAYO_BF16 && slice >= 1024 && T % 256 == 0 && H % 256 == 0 && tiles256 * kHeadSplit <= 256;
+  k::GemmArgs part[kHeadSplit];
+  for (int i = 0; i < kHeadSplit && split; ++i) {
+    const int k0 = i * slice, kn = i + 1 < kHeadSplit ? slice : V - k0;
+    part[i] = gx;
+    part[i].A = ws + L.logits + (size_t)k0 * sh.esz;
+    part[i].B = static_cast<const char*>(head) + (size_t)k0 * H * sh.esz;
+    part[i].C = ws + L.split + (size_t)i * T * H * sizeof(float);
+    part[i].K = kn;
+    part[i].epi = k::EPI_STORE_F32;
+    split = k::gemm_dma_supported(part[i], 6);
+  }
+  if (split) {
+    TRY(k::gemm_dma_group(part, kHeadSplit, 6, st));
+    TRY(k::sum_slices(sh.dtype, reinterpret_cast<const float*>(ws + L.split), kHeadSplit, (size_t)T * H, gx.C, st));
+  } else {
+    TRY(k::gemm(sh.dtype, gx, st));
+  }
   if (e->final_ln)
     TRY(k::ln_backward(sh.dtype, ws + L.d_hn, y, lnf, stats, nullptr, dy, d_lnf, d_lnf + H,
                        reinterpret_cast<float*>(ws + L.partial), T, H, st));

@@ -35,6 +35,8 @@ __device__ __forceinline__ void epilogue_one(const EpiParams<T>& p, int m, int n
     st(p.C + at, acc * gelu_grad_f(ld(p.aux + at)));
   } else if constexpr (EPI == EPI_ADD) {
     st(p.C + at, acc + ld(p.aux + at));
+  } else if constexpr (EPI == EPI_STORE_F32) {
+    p.Cf[at] = acc;
   } else {
     p.Cf[at] += acc;
   }

@@ -29,7 +29,8 @@ enum Epilogue {
   EPI_BIAS_RES,       // C = acc + bias[n] + aux[m][n]
   EPI_MUL_DGELU,      // C = acc * GELU'(aux[m][n])
   EPI_ADD,            // C = acc + aux[m][n]
-  EPI_ACCUM_F32       // C (fp32) += acc
+  EPI_ACCUM_F32,      // C (fp32) += acc
+  EPI_STORE_F32       // C (fp32) = acc   (partial products of a K split; !a_t && b_t only)
 };
 
 // C[M][N] = A[M][K] * B[K][N] with fp32 accumulation.
@@ -128,6 +129,9 @@ struct AdamArgs {
   size_t lo[4], hi[4];
 };
 int adam(int dtype, const AdamArgs& a, hipStream_t stream);
+
+// out[i] = sum over s < slices of parts[s * count + i]  (the partial products of a K split; count multiple of 8)
+int sum_slices(int dtype, const float* parts, int slices, size_t count, void* out, hipStream_t stream);
 
 // ---- misc ------------------------------------------------------------------------
 // max_workgroups > 0 caps the grid: a copy that uses only a few CUs and so runs at a chosen fraction of the

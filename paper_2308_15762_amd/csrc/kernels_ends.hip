@@ -232,6 +232,23 @@ __global__ __launch_bounds__(256) void loss_finish_kernel(const float* __restric
   if (threadIdx.x == 0) loss[0] = count[0] > 0.f ? part[0] / count[0] : 0.f;
 }
 
+// out[i] = sum over the slices of parts[s][i], 8 elements per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void sum_slices_kernel(const float* __restrict__ parts, int slices, size_t count,
+                                                         T* __restrict__ out) {
+  const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (i >= count) return;
+  float acc[8];
+  load8(parts + i, acc);
+  for (int s = 1; s < slices; ++s) {
+    float v[8];
+    load8(parts + (size_t)s * count + i, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] += v[j];
+  }
+  store8(out + i, acc);
+}
+
 // Adam with bias correction and decoupled weight decay on 4-element vectors.  The moments and, for
 // bf16 parameters, the fp32 master copy are updated in place; the stored parameter is the rounded
 // master.  Weight decay applies to the vectors for which decays() says so: everything, or only the
@@ -351,6 +368,17 @@ int loss_finish(const float* nll, const float* count, int rows, float* loss, hip
   if (rows < 1) return set_error(HANAYO_EINVAL, "loss_finish: bad shape");
   hipLaunchKernelGGL(loss_finish_kernel, dim3(1), dim3(256), 0, stream, nll, count, rows, loss);
   return check_launch("loss_finish");
+}
+
+int sum_slices(int dtype, const float* parts, int slices, size_t count, void* out, hipStream_t stream) {
+  if (slices < 1 || count == 0 || count % 8) return set_error(HANAYO_EINVAL, "sum_slices: bad shape");
+  const size_t blocks = (count / 8 + 255) / 256;
+  if (blocks > 0x7fffffffu) return set_error(HANAYO_EUNSUPPORTED, "sum_slices: too many elements");
+  if (dtype == HANAYO_BF16)
+    hipLaunchKernelGGL(sum_slices_kernel<bf16>, dim3((unsigned)blocks), dim3(256), 0, stream, parts, slices, count, (bf16*)out);
+  else
+    hipLaunchKernelGGL(sum_slices_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, parts, slices, count, (float*)out);
+  return check_launch("sum_slices");
 }
 
 int adam(int dtype, const AdamArgs& g, hipStream_t stream) {

@@ -558,6 +558,8 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
           cur[4 + e] = pre_c[i & 1][u][1][e] + v[4 + e];
         }
         store8(p.Cf + at, cur);
+      } else if constexpr (EPI == EPI_STORE_F32) {
+        store8(p.Cf + at, v);
       } else {
         if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
           float b[8];
@@ -617,6 +619,7 @@ int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
       case EPI_BIAS: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS>(grp, stream);
       case EPI_BIAS_GELU: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_GELU>(grp, stream);
       case EPI_BIAS_RES: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_BIAS_RES>(grp, stream);
+      case EPI_STORE_F32: return launch<BM, BN, WGM, WGN, NSTAGE, MODE, false, true, EPI_STORE_F32>(grp, stream);
       default: break;
     }
   } else if (!g.a_t && !g.b_t) {
@@ -644,7 +647,8 @@ void gemm_dma_tile(int config, int& bm, int& bn) {
 }
 
 bool gemm_dma_supported(const GemmArgs& g, int config) {
-  const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_NONE || g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES)) ||
+  const bool combo = (!g.a_t && g.b_t && (g.epi == EPI_NONE || g.epi == EPI_BIAS || g.epi == EPI_BIAS_GELU || g.epi == EPI_BIAS_RES ||
+                                             g.epi == EPI_STORE_F32)) ||
                      (!g.a_t && !g.b_t && (g.epi == EPI_NONE || g.epi == EPI_MUL_DGELU || g.epi == EPI_ADD)) ||
                      (g.a_t && g.b_t && g.epi == EPI_ACCUM_F32);
   int bm, bn;

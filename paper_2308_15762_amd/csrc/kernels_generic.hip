@@ -265,6 +265,7 @@ int gemm_alu_t(const GemmArgs& g, hipStream_t stream) {
     LAUNCH(EPI_MUL_DGELU);
     LAUNCH(EPI_ADD);
     LAUNCH(EPI_ACCUM_F32);
+    LAUNCH(EPI_STORE_F32);
   }
 #undef LAUNCH
   return check_launch("gemm_alu");
