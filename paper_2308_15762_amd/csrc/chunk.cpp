@@ -93,6 +93,7 @@ int g_gemm_config = -1;
 thread_local double g_gemm_sharing = 0.0;
 }
 void set_gemm_config(int config) { g_gemm_config = config; }
+double gemm_sharing() { return g_gemm_sharing; }
 void set_gemm_sharing(double share) { g_gemm_sharing = share < 0.0 ? 0.0 : (share > 1.0 ? 1.0 : share); }
 
 // Tile choice for the direct-to-LDS kernels by a cost model fitted to timings on MI355X: a launch

@@ -98,8 +98,8 @@ int head_loss(const Shape& sh, const hanayo_ends_desc* e, const void* lnf, const
     hn = ws + L.hn;
   }
   TRY(k::count_labels(labels, T, V, count, st));
-  // The vocabulary is rarely a multiple of the largest GEMM tile (256): the rows of the table up to the last such
-  // multiple go out as one launch that may use it, the few rows left as a second, small one.
+  // The vocabulary is rarely a multiple of the largest GEMM tile (256): for the logits the rows of the table up to
+  // the last such multiple go out as one launch that may use it, the few rows left as a second, small one.
   const int v_main = V >= 512 ? V / 256 * 256 : V, v_rest = V - v_main;
   const char* head_rest = static_cast<const char*>(head) + (size_t)v_main * H * sh.esz;
   // logits[T][V] = hn[T][H] head[V][H]^T
@@ -120,12 +120,15 @@ int head_loss(const Shape& sh, const hanayo_ends_desc* e, const void* lnf, const
   gw.A = ws + L.logits; gw.B = hn; gw.C = d_head;
   gw.M = V; gw.N = H; gw.K = T; gw.lda = V; gw.ldb = H; gw.ldc = H;
   gw.a_t = true; gw.b_t = true; gw.epi = k::EPI_ACCUM_F32;
-  gw.M = v_main;
-  TRY(k::gemm(sh.dtype, gw, st));
-  if (v_rest) {
-    gw.A = ws + L.logits + (size_t)v_main * sh.esz; gw.C = d_head + (size_t)v_main * H; gw.M = v_rest;
+  // Alone on the chip one launch of small tiles is fastest here (measured: V / 256 x H / 256 large tiles leave a
+  // quarter of the last round idle); next to other lanes' kernels idle CUs are not lost and the large tile's
+  // better use of a CU wins, so the rows split as for the logits.
+  if (v_rest && k::gemm_sharing() > 0.0) {
+    gw.M = v_main;
     TRY(k::gemm(sh.dtype, gw, st));
+    gw.A = ws + L.logits + (size_t)v_main * sh.esz; gw.C = d_head + (size_t)v_main * H; gw.M = v_rest;
   }
+  TRY(k::gemm(sh.dtype, gw, st));
   // d_hn[T][H] = dlogits[T][V] head[V][H]
   k::GemmArgs gx{};
   gx.A = ws + L.logits; gx.B = head; gx.C = e->final_ln ? static_cast<void*>(ws + L.d_hn) : dy;

@@ -94,6 +94,7 @@ void set_gemm_config(int config);
 // runs alone (choose the tile for the shortest launch), 1 = idle CUs are always taken by other work (choose
 // for the least CU time).  The executor sets it from its lane count while it enqueues a list.
 void set_gemm_sharing(double share);
+double gemm_sharing();
 bool attn_mfma_supported(const AttnArgs& a);
 int attn_forward_mfma(const AttnArgs& a, hipStream_t stream);
 int attn_backward_mfma(const AttnArgs& a, hipStream_t stream);
