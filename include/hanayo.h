@@ -190,7 +190,7 @@ typedef struct hanayo_ends_desc {
  * tokens  device int32 [b][s]; a token outside [0, V) contributes no table row
  *         (forward) and receives no gradient (backward)
  * x       device [b][s][H], fully overwritten
- * d_wte   device fp32 [V][H]: rows of equal tokens are added with fp32 atomics, in no fixed order
+ * d_wte   device fp32 [V][H]: rows of equal tokens are added in a fixed order, without atomics (H <= 4096)
  * d_wpe   device fp32 [max_pos][H]
  */
 int hanayo_embed_forward(const hanayo_chunk_desc* d, const hanayo_ends_desc* e, const void* wte, const void* wpe,

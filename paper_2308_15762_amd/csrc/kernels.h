@@ -103,7 +103,7 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream);
 // x[n][i][:] = wte[tokens[n][i]][:] + wpe[i][:]; tokens outside [0, vocab) contribute nothing.
 int embed_forward(int dtype, const void* wte, const void* wpe, const int32_t* tokens, void* x, int b, int s, int H,
                   int vocab, hipStream_t stream);
-// d_wte[tokens[n][i]][:] += dx[n][i][:] (fp32 atomics); d_wpe[i][:] += sum_n dx[n][i][:].
+// d_wte[tokens[n][i]][:] += dx[n][i][:] (fixed order, no atomics); d_wpe[i][:] += sum_n dx[n][i][:].
 int embed_backward(int dtype, const int32_t* tokens, const void* dx, float* d_wte, float* d_wpe, int b, int s, int H,
                    int vocab, hipStream_t stream);
 // count[0] = number of labels inside [0, vocab).

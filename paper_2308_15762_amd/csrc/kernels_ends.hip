@@ -39,21 +39,118 @@ __global__ __launch_bounds__(256) void embed_fwd_kernel(const T* __restrict__ wt
   }
 }
 
-// d_wte[token[t]][:] += dx[t][:]  (rows of equal tokens meet in fp32 atomics: their order is not fixed)
-template <typename T>
+// d_wte[token[t]][:] += dx[t][:] without atomics and in a fixed order.  One workgroup per row t; the workgroup of
+// the FIRST row that holds a token owns that token's table row for the launch: it lists, in ascending order, the
+// rows that hold the same token (ballot + prefix counts, 256 rows at a time), its four wavefronts sum every fourth
+// listed row each, and the four partial sums are added to the table row in
+// wavefront order.  Workgroups of later occurrences leave at once.  NV = 8-element vectors per lane (H <= 512 NV).
+// (the listed rows' loads: 8 in flight per wavefront, fewer for wide rows)
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void embed_bwd_token_kernel(const int32_t* __restrict__ tokens, const T* __restrict__ dx,
                                                               float* __restrict__ d_wte, int rows, int H, int vocab) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * kRowsPerBlock + (threadIdx.x >> 6);
-  if (row >= rows) return;
+  __shared__ int list[256];
+  __shared__ int cnt[4];
+  extern __shared__ float part[];  // [3][H]: partial sums of wavefronts 1..3
+  const int row = blockIdx.x;
   const int tok = tokens[row];
   if (tok < 0 || tok >= vocab) return;
-  float* out = d_wte + (size_t)tok * H;
-  for (int c = lane * 8; c < H; c += 64 * 8) {
-    float v[8];
-    load8(dx + (size_t)row * H + c, v);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int seen = 0;
+  for (int t = threadIdx.x; t < row; t += 256) seen |= tokens[t] == tok;
+  if (__syncthreads_or(seen)) return;  // an earlier row owns this token
+  float acc[NV][8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) atomicAdd(out + c + j, v[j]);
+  for (int i = 0; i < NV; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+  for (int base = row; base < rows; base += 256) {
+    const int t = base + (int)threadIdx.x;
+    const bool hit = t < rows && tokens[t] == tok;
+    const unsigned long long mask = __ballot(hit);
+    if (lane == 0) cnt[wave] = __popcll(mask);
+    __syncthreads();
+    int before = 0, n = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      if (w < wave) before += cnt[w];
+      n += cnt[w];
+    }
+    if (hit) list[before + __popcll(mask & ((1ull << lane) - 1ull))] = t;
+    __syncthreads();
+    // wavefront w takes list entries w, w + 4, w + 8, ...; U of them in flight (fewer for wide rows: registers)
+    constexpr int U = NV <= 2 ? 8 : NV <= 4 ? 4 : 2;
+    for (int i0 = wave; i0 < n; i0 += 4 * U) {
+      bf16x8 raw16[U][NV];
+      f32x4 raw32[U][NV][2];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = i0 + 4 * u;
+        if (i < n) {
+          const T* src = dx + (size_t)list[i] * H;
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            const int c = (v * 64 + lane) * 8;
+            if (c < H) {
+              if constexpr (sizeof(T) == 2) {
+                raw16[u][v] = *reinterpret_cast<const bf16x8*>(src + c);
+              } else {
+                raw32[u][v][0] = *reinterpret_cast<const f32x4*>(src + c);
+                raw32[u][v][1] = *reinterpret_cast<const f32x4*>(src + c + 4);
+              }
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (i0 + 4 * u < n) {
+#pragma unroll
+          for (int v = 0; v < NV; ++v) {
+            if ((v * 64 + lane) * 8 < H) {
+#pragma unroll
+              for (int j = 0; j < 8; ++j) {
+                if constexpr (sizeof(T) == 2) acc[v][j] += (float)raw16[u][v][j];
+                else acc[v][j] += raw32[u][v][j >> 2][j & 3];
+              }
+            }
+          }
+        }
+      }
+    }
+    __syncthreads();  // the list is rebuilt in the next round
+  }
+  // wavefronts 1..3 hand their sums to wavefront 0, which adds them in order and updates the table row
+  if (wave > 0) {
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (v * 64 + lane) * 8;
+      if (c < H) store8(part + (size_t)(wave - 1) * H + c, acc[v]);
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    float* out = d_wte + (size_t)tok * H;
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+      const int c = (v * 64 + lane) * 8;
+      if (c < H) {
+        float cur[8];
+        load8(out + c, cur);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          float add[8];
+          if (w == 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) add[j] = acc[v][j];
+          } else {
+            load8(part + (size_t)(w - 1) * H + c, add);
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j) cur[j] += add[j];
+        }
+        store8(out + c, cur);
+      }
+    }
   }
 }
 
@@ -328,20 +425,34 @@ int embed_forward(int dtype, const void* wte, const void* wpe, const int32_t* to
   return check_launch("embed_forward");
 }
 
+namespace {
+template <typename T>
+int embed_backward_t(const int32_t* tokens, const void* dx, float* d_wte, float* d_wpe, int b, int s, int H, int vocab,
+                     hipStream_t stream) {
+  const int rows = b * s;
+  const size_t lds = (size_t)3 * H * sizeof(float);
+  const int nv = (H + 511) / 512;
+#define LAUNCH(NV)                                                                                              \
+  hipLaunchKernelGGL((embed_bwd_token_kernel<T, NV>), dim3(rows), dim3(256), lds, stream, tokens, (const T*)dx, d_wte, \
+                     rows, H, vocab)
+  if (nv <= 1) LAUNCH(1);
+  else if (nv <= 2) LAUNCH(2);
+  else if (nv <= 4) LAUNCH(4);
+  else LAUNCH(8);
+#undef LAUNCH
+  int rc = check_launch("embed_backward (tokens)");
+  if (rc) return rc;
+  const dim3 pgrid((unsigned)(((long)s * (H / 8) + 255) / 256));
+  hipLaunchKernelGGL(embed_bwd_pos_kernel<T>, pgrid, dim3(256), 0, stream, (const T*)dx, d_wpe, b, s, H);
+  return check_launch("embed_backward (positions)");
+}
+}  // namespace
+
 int embed_backward(int dtype, const int32_t* tokens, const void* dx, float* d_wte, float* d_wpe, int b, int s, int H,
                    int vocab, hipStream_t stream) {
-  if (b < 1 || s < 1 || H < 8 || H % 8 || vocab < 1) return set_error(HANAYO_EINVAL, "embed_backward: bad shape");
-  const int rows = b * s;
-  const dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock);
-  const dim3 pgrid((unsigned)(((long)s * (H / 8) + 255) / 256));
-  if (dtype == HANAYO_BF16) {
-    hipLaunchKernelGGL(embed_bwd_token_kernel<bf16>, grid, dim3(256), 0, stream, tokens, (const bf16*)dx, d_wte, rows, H, vocab);
-    hipLaunchKernelGGL(embed_bwd_pos_kernel<bf16>, pgrid, dim3(256), 0, stream, (const bf16*)dx, d_wpe, b, s, H);
-  } else {
-    hipLaunchKernelGGL(embed_bwd_token_kernel<float>, grid, dim3(256), 0, stream, tokens, (const float*)dx, d_wte, rows, H, vocab);
-    hipLaunchKernelGGL(embed_bwd_pos_kernel<float>, pgrid, dim3(256), 0, stream, (const float*)dx, d_wpe, b, s, H);
-  }
-  return check_launch("embed_backward");
+  if (b < 1 || s < 1 || H < 8 || H % 8 || H > 4096 || vocab < 1) return set_error(HANAYO_EINVAL, "embed_backward: bad shape");
+  return dtype == HANAYO_BF16 ? embed_backward_t<bf16>(tokens, dx, d_wte, d_wpe, b, s, H, vocab, stream)
+                              : embed_backward_t<float>(tokens, dx, d_wte, d_wpe, b, s, H, vocab, stream);
 }
 
 int count_labels(const int32_t* labels, int rows, int vocab, float* count, hipStream_t stream) {

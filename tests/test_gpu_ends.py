@@ -51,6 +51,28 @@ def test_embedding(dtype, hidden, seq, mb, vocab):
     assert nerr(host(d_wte), 2 * w_wte) <= 1e-6 and nerr(host(d_wpe), 2 * w_wpe) <= 1e-6
 
 
+@pytest.mark.parametrize("dtype,hidden", [("bf16", 1024), ("fp32", 256), ("bf16", 2560)])
+def test_embedding_backward_with_heavy_repeats_is_exact_in_order(dtype, hidden):
+    """One token on 700 of 1200 rows (its owner lists them over several rounds of 256), the rest Zipf: against the
+    oracle, and bit-identical from run to run (no atomics: the summation order is fixed)."""
+    wl = small(dtype, hidden, 300, 4, 512)
+    d, e = hn.desc_for(wl), ends_desc(wl)
+    tok = synth.token_ids(wl, 0)
+    flat = tok.reshape(-1)
+    flat[synth.rng_for(5, 1).permutation(flat.size)[:700]] = 41
+    dx = synth.upstream_grad(wl, 0, 0)
+    tokd, dxd = torch.from_numpy(tok).cuda(), dev(dx, dtype)
+    outs = []
+    for _ in range(2):
+        d_wte = torch.zeros((512, hidden), dtype=torch.float32, device="cuda")
+        d_wpe = torch.zeros((300, hidden), dtype=torch.float32, device="cuda")
+        hn.hanayo_embed_backward(d, e, tokd, dxd, d_wte, d_wpe)
+        outs.append((d_wte, d_wpe))
+    w_wte, w_wpe = OE.embed_backward(tok, dx.astype(np.float64), 512, 300)
+    assert nerr(host(outs[0][0]), w_wte) <= 1e-6 and nerr(host(outs[0][1]), w_wpe) <= 1e-6
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
 def test_embedding_ignores_tokens_outside_the_vocabulary():
     wl = small("fp32", 64, 6, 2, 16)
     d, e = hn.desc_for(wl), ends_desc(wl)
