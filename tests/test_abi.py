@@ -88,3 +88,28 @@ def test_compute_calls_fail_loudly_without_a_gpu():
     with pytest.raises(hn.HanayoError) as ei:
         hn.hanayo_chunk_forward(d, dummy, dummy, None, dummy, dummy, dummy)
     assert ei.value.code in (hn.EHIP, hn.EUNSUPPORTED, hn.EINVAL)
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    """include/hanayo.h compiled by a C compiler (-std=c99, warnings as errors), the program linked against
+    libhanayo.so and run: rank 0's list of (4, 2, 8) and its stash plan, against the oracle."""
+    import shutil
+    import subprocess
+    from oracle import schedule as OS
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        pytest.skip("no C compiler")
+    exe = str(tmp_path / "schedule_from_c")
+    libdir = os.path.dirname(hn.LIB_PATH)
+    subprocess.check_call([cc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "tests", "abi_c", "schedule_from_c.c"), "-o", exe,
+                           "-L", libdir, "-lhanayo", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib",
+                           "-Wl,--allow-shlib-undefined"])
+    out = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr
+    lines = out.stdout.strip().splitlines()
+    tasks = OS.schedule(4, 2, 8, 0)
+    peak, _, slot = OS.stash_plan(tasks, 2)
+    assert lines[0] == "peak %d" % peak
+    want = ["%s %d %d %d %d" % ("FB"[t.kind], t.mb, t.chunk, t.stage, s) for t, s in zip(tasks, slot)]
+    assert lines[1:] == want
