@@ -113,3 +113,18 @@ def test_header_is_plain_c_and_links_from_c(tmp_path):
     assert lines[0] == "peak %d" % peak
     want = ["%s %d %d %d %d" % ("FB"[t.kind], t.mb, t.chunk, t.stage, s) for t, s in zip(tasks, slot)]
     assert lines[1:] == want
+
+
+def test_ends_workspace_sizes():
+    d = hn.make_desc(2, 1024, 16, 4096, 1024, 4, hn.PRE_LN, hn.MASK_CAUSAL, hn.BF16)
+    e = hn.EndsDesc(50304, 1024, 1)
+    T, H, V = 4096, 1024, 50304
+    head = hn.hanayo_head_workspace_bytes(d, e)
+    # the logits, two activation-sized tensors, and the fp32 partial products of the split d_hidden GEMM
+    assert head >= T * V * 2 + 2 * T * H * 2 + 4 * T * H * 4 and head % 256 == 0
+    assert hn.hanayo_ends_workspace_bytes(d, e) == head + T * H * 2
+    for bad in (hn.EndsDesc(50300, 1024, 1), hn.EndsDesc(50304, 1000, 1), hn.EndsDesc(0, 1024, 0), hn.EndsDesc(50304, 1024, 3)):
+        with pytest.raises(hn.HanayoError):
+            hn.hanayo_head_workspace_bytes(d, bad)
+        with pytest.raises(hn.HanayoError):
+            hn.hanayo_ends_workspace_bytes(d, bad)
