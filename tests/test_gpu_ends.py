@@ -401,7 +401,7 @@ def test_two_training_iterations(name):
 def test_training_lowers_the_loss():
     """The whole stack as a user would drive it: one rank that holds every stage (P = 1), token ids in, Adam at
     every flush.  Thirty iterations on the same three micro-batches must pull the loss well below its starting
-    value (log V for an untrained model; measured 4.15 -> 2.8); nothing is compared with the oracle here, the point is that the
+    value (log V for an untrained model; measured 4.15 -> 1.5 with a learning rate of 3e-3; 1e-2 is past the edge of stability for this model); nothing is compared with the oracle here, the point is that the
     pieces work together over many iterations (gradients cleared by the update, step counts, tied table)."""
     wl = RANK_CASES["single_rank"]
     gpu = GpuRank(wl, 0, lanes=2, ends=True)
@@ -410,7 +410,7 @@ def test_training_lowers_the_loss():
     for _ in range(30):
         gpu.run()
         history.append(float(gpu.loss.mean().item()))
-        gpu.adam_step(1e-2, weight_decay=0.0)
+        gpu.adam_step(3e-3, weight_decay=0.0)
     assert abs(history[0] - np.log(wl.vocab)) < 0.2
-    assert history[-1] < history[10] < history[0] and history[-1] < 0.75 * history[0], history
+    assert history[-1] < history[10] < history[0] and history[-1] < 0.5 * history[0], history
     assert all(np.isfinite(history))
