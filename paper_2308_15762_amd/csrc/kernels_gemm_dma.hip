@@ -2,15 +2,16 @@
 // global memory straight into LDS (global_load_lds_dwordx4, no VGPR staging and no
 // LDS write instructions), through a ring of NSTAGE LDS buffers, so that loads
 // for tile t+NSTAGE-1 are in flight while tile t is multiplied.  One workgroup
-// barrier per K tile (32 elements).
+// barrier per K tile (32 elements; 64 in the two-stage form).
 //
 // LDS layouts are unpadded and XOR-swizzled in units of 16 bytes ("slots"); a
 // direct load writes 64 consecutive slots per wavefront instruction, so the
 // swizzle is applied by choosing which global vector each lane fetches:
 //   * contraction-contiguous operand, tile [rows][32]: 4 slots per row,
 //       slot' = slot ^ ((row >> 2) & 3)          (16-byte fragment reads of 16
-//       consecutive rows then cover all 64 banks)
-//   * contraction-strided operand, tile [32][cols]: cols/8 slots per row,
+//       consecutive rows then cover all 64 banks);
+//     tile [rows][64] (two-stage form): 8 slots per row, slot' = slot ^ ((row >> 1) & 7)
+//   * contraction-strided operand, tile [32 or 64][cols]: cols/8 slots per row,
 //       slot' = slot ^ ((row & 3) << 2)          (the 4 rows x 4 slots one half
 //       wavefront touches in a transpose read cover all 64 banks)
 // MFMA and fragment orientation are those of the staged kernel (kernels_gemm_mfma.hip).
@@ -90,11 +91,11 @@ __device__ __forceinline__ void wait_tiles(int tiles_in_flight) {
   }
 }
 
-// Operand tile description.  T = contraction strided in memory (tile is [32][EXT]).
-template <int EXT, bool T, int NW>
+// Operand tile description.  T = contraction strided in memory (tile is [BK][EXT]); BK = 32 or 64.
+template <int EXT, bool T, int NW, int BK>
 struct Operand {
-  static constexpr int kSlotsPerRow = T ? EXT / 8 : 4;
-  static constexpr int kRows = T ? kBK : EXT;
+  static constexpr int kSlotsPerRow = T ? EXT / 8 : BK / 8;
+  static constexpr int kRows = T ? BK : EXT;
   static constexpr int kBytes = kRows * kSlotsPerRow * 16;
   static constexpr int kInstr = kBytes / 1024;      // wavefront-wide loads per tile
   static constexpr int kPerWave = kInstr / NW;      // issued by each wavefront
@@ -104,28 +105,31 @@ struct Operand {
   // instruction starts at a multiple of 4 rows
   static_assert(!T || ((kPerWave * 64) / kSlotsPerRow) % 4 == 0, "wavefront's share must start on a 4-row boundary");
 
-  __device__ static int swizzle(int row, int slot) { return T ? slot ^ ((row & 3) << 2) : slot ^ ((row >> 2) & 3); }
+  // contraction-contiguous rows are 64 bytes (BK = 32: four rows per 256 bytes of banks, slot ^ (row / 4 mod 4)) or
+  // 128 bytes (BK = 64: two rows, slot ^ (row / 2 mod 8)): 16 consecutive rows at one logical slot cover all banks
+  __device__ static int swizzle(int row, int slot) {
+    return T ? slot ^ ((row & 3) << 2) : (BK == 32 ? slot ^ ((row >> 2) & 3) : slot ^ ((row >> 1) & 7));
+  }
 
   // Byte offset, from the first element an instruction covers, of the vector that lane `lane`
-  // fetches.  `row_base` = (first tile row of the instruction) mod 4: the swizzle of a transposed
-  // tile depends on the absolute row, and an instruction may start at a row that is not a
-  // multiple of 4 (it covers 64 / slots-per-row rows).
+  // fetches.  `row_base` = the bits of the instruction's first tile row that the swizzle looks at: the
+  // swizzle depends on the absolute row, and an instruction may start at a row that is not a multiple of
+  // the swizzle's period (it covers 64 / slots-per-row rows).
   __device__ static unsigned lane_offset(int lane, int ld, int row_base) {
-    if (T) {
-      const int row = lane / kSlotsPerRow, sp = lane % kSlotsPerRow;
-      return (unsigned)((row * ld + swizzle(row_base + row, sp) * 8) * 2);
-    }
-    const int row = lane >> 2, sp = lane & 3;
-    return (unsigned)((row * ld + swizzle(row, sp) * 8) * 2);
+    const int row = lane / kSlotsPerRow, sp = lane % kSlotsPerRow;
+    return (unsigned)((row * ld + swizzle(row_base + row, sp) * 8) * 2);
   }
-  // row_base of instruction q
-  __device__ static constexpr int row_base(int q) { return T ? ((q * 64) / kSlotsPerRow) & 3 : 0; }
+  // row_base of instruction q: the bits of its first tile row that the swizzle looks at (a contraction-contiguous
+  // tile's swizzle has period 16 rows; an instruction covers 16 rows of 64 bytes or 8 rows of 128 bytes)
+  __device__ static constexpr int row_base(int q) { return T ? ((q * 64) / kSlotsPerRow) & 3 : ((q * 64) / kSlotsPerRow) & 15; }
+  static_assert(T || ((kPerWave * 64) / kSlotsPerRow) % 16 == 0, "wavefront's share must start on a 16-row boundary");
 };
 
 template <int PITCH_SLOTS>
 __device__ __forceinline__ bf16x8 frag_k(const char* lds, int r0, int kk, int lane) {
   const int row = r0 + (lane & 31), slot = 2 * kk + (lane >> 5);
-  return *reinterpret_cast<const bf16x8*>(lds + (row * 4 + (slot ^ ((row >> 2) & 3))) * 16);
+  const int swz = PITCH_SLOTS == 4 ? (row >> 2) & 3 : (row >> 1) & 7;
+  return *reinterpret_cast<const bf16x8*>(lds + (row * PITCH_SLOTS + (slot ^ swz)) * 16);
 }
 
 template <int SPR>
@@ -163,12 +167,16 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   constexpr int NSP = WGM * WGN;                 // wavefronts that tile the output
   constexpr int NW = NSP * (MODE == 2 ? 2 : 1);  // wavefronts in the workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
-  using OpA = Operand<BM, A_T, NW>;
-  using OpB = Operand<BN, B_T, NW>;
+  // A ring of two stages holds 64-wide K tiles (the same bytes in flight as four stages of 32, half as many
+  // barriers and waits per unit of work, whole 128-byte lines per row of a contraction-contiguous operand).
+  constexpr int BK = NSTAGE == 2 ? 64 : 32;
+  constexpr int KS = BK / 16;  // MFMA steps per K tile
+  using OpA = Operand<BM, A_T, NW, BK>;
+  using OpB = Operand<BN, B_T, NW, BK>;
   constexpr int STAGE_BYTES = OpA::kBytes + OpB::kBytes;
   constexpr int LOADS = OpA::kPerWave + OpB::kPerWave;  // per thread per tile
   static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt range");
-  static_assert(NSTAGE >= 3 && kBK == 32, "pipeline below is written for two MFMA steps per tile");
+  static_assert(NSTAGE >= 3 || (NSTAGE == 2 && MODE == 0), "two stages: the 64-wide pipeline of MODE 0 only");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // LDS byte address of the ring (address-space-3 offset, what M0 takes)
@@ -183,7 +191,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   tile_m = __builtin_amdgcn_readfirstlane(tile_m);
   tile_n = __builtin_amdgcn_readfirstlane(tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
-  const int nk = p.K / kBK;
+  const int nk = p.K / BK;
 
   // Direct loads of one K tile.  The wavefront's i-th instruction for an operand covers the 64
   // slots q = wave * kPerWave + i of the tile; which rows that is goes into the lane's byte
@@ -194,21 +202,21 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   for (int i = 0; i < OpA::kPerWave; ++i) {
     const int q = wave * OpA::kPerWave + i;
     const unsigned first = A_T ? (unsigned)((((q * 64) / OpA::kSlotsPerRow) * p.lda + ((q * 64) % OpA::kSlotsPerRow) * 8) * 2)
-                               : (unsigned)((q * 16 * p.lda) * 2);
+                               : (unsigned)((q * (64 / OpA::kSlotsPerRow) * p.lda) * 2);
     voff_a[i] = first + OpA::lane_offset(lane, p.lda, OpA::row_base(i));
   }
 #pragma unroll
   for (int i = 0; i < OpB::kPerWave; ++i) {
     const int q = wave * OpB::kPerWave + i;
     const unsigned first = B_T ? (unsigned)((((q * 64) / OpB::kSlotsPerRow) * p.ldb + ((q * 64) % OpB::kSlotsPerRow) * 8) * 2)
-                               : (unsigned)((q * 16 * p.ldb) * 2);
+                               : (unsigned)((q * (64 / OpB::kSlotsPerRow) * p.ldb) * 2);
     voff_b[i] = first + OpB::lane_offset(lane, p.ldb, OpB::row_base(i));
   }
   // uniform running state of the loader: next tile's base pointers and LDS buffer
   const bf16* a_next = A_T ? p.A + m0 : p.A + (size_t)m0 * p.lda;
   const bf16* b_next = B_T ? p.B + n0 : p.B + (size_t)n0 * p.ldb;
-  const size_t a_step = A_T ? (size_t)kBK * p.lda : (size_t)kBK;
-  const size_t b_step = B_T ? (size_t)kBK * p.ldb : (size_t)kBK;
+  const size_t a_step = A_T ? (size_t)BK * p.lda : (size_t)BK;
+  const size_t b_step = B_T ? (size_t)BK * p.ldb : (size_t)BK;
   unsigned stage_next = 0;  // buffer index the next issued tile goes to
   const unsigned wave_lds_a = lds0 + wave * OpA::kPerWave * 1024;
   const unsigned wave_lds_b = lds0 + OpA::kBytes + wave * OpB::kPerWave * 1024;
@@ -249,13 +257,15 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     const char* a_lds = smem + (kt % NSTAGE) * STAGE_BYTES;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
-      f[i] = A_T ? frag_t<OpA::kSlotsPerRow>(a_lds, wm * WM + i * 32, kk, lane) : frag_k<4>(a_lds, wm * WM + i * 32, kk, lane);
+      f[i] = A_T ? frag_t<OpA::kSlotsPerRow>(a_lds, wm * WM + i * 32, kk, lane)
+                 : frag_k<OpA::kSlotsPerRow>(a_lds, wm * WM + i * 32, kk, lane);
   };
   auto read_b = [&](int kt, int kk, bf16x8 (&f)[TN]) {
     const char* b_lds = smem + (kt % NSTAGE) * STAGE_BYTES + OpA::kBytes;
 #pragma unroll
     for (int j = 0; j < TN; ++j)
-      f[j] = B_T ? frag_t<OpB::kSlotsPerRow>(b_lds, wn * WN + j * 32, kk, lane) : frag_k<4>(b_lds, wn * WN + j * 32, kk, lane);
+      f[j] = B_T ? frag_t<OpB::kSlotsPerRow>(b_lds, wn * WN + j * 32, kk, lane)
+                 : frag_k<OpB::kSlotsPerRow>(b_lds, wn * WN + j * 32, kk, lane);
   };
   auto mfma_step = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN]) {
 #pragma unroll
@@ -266,7 +276,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
 
   // Column sums of B (bias gradient): the K tiles are dealt round-robin to the workgroups of a
   // column of the grid, each thread adds 4 columns x (32 / kColRowGroups) rows of a tile it owns.
-  constexpr int kColGroups = BN / 4, kColRowGroups = NW * 64 / kColGroups, kColRows = kBK / kColRowGroups;
+  constexpr int kColGroups = BN / 4, kColRowGroups = NW * 64 / kColGroups, kColRows = BK / kColRowGroups;
   float csum[4] = {0.f, 0.f, 0.f, 0.f};
   int colsum_next = p.colsum ? tile_m : 0x7fffffff;  // next K tile this workgroup sums
   auto colsum_tile = [&](int kt) {
@@ -287,7 +297,52 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     }
   };
 
-  if constexpr (!FDEEP) {
+  if constexpr (NSTAGE == 2) {
+    // Two 64-wide stages.  Per K tile (KS = 4 MFMA steps):
+    //   steps 0 .. KS-2 of tile kt    | LDS reads: the following step of tile kt
+    //   every fragment of tile kt is in registers; wait until tile kt+1 has landed; barrier (everyone is there)
+    //   start the loads of tile kt+2 into the buffer tile kt occupied
+    //   step KS-1 of tile kt          | LDS reads: step 0 of tile kt+1
+    issue();
+    if (nk > 1) issue();
+    bf16x8 fa[2][TM], fb[2][TN];
+    wait_tiles<LOADS>(min(1, nk - 1));
+    __syncthreads();
+    colsum_tile(0);
+    read_a(0, 0, fa[0]);
+    read_b(0, 0, fb[0]);
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+#pragma unroll
+      for (int st = 0; st + 1 < KS; ++st) {
+        read_a(kt, st + 1, fa[(st + 1) & 1]);
+        read_b(kt, st + 1, fb[(st + 1) & 1]);
+        mfma_step(fa[st & 1], fb[st & 1]);
+        interleave();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // the buffer of tile kt is overwritten right after the barrier: its last fragments must have arrived
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      wait_vmcnt<0>();
+      __syncthreads();
+      if (kt + 2 < nk) issue();
+      colsum_tile(kt + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_a(kt + 1, 0, fa[0]);
+      read_b(kt + 1, 0, fb[0]);
+      mfma_step(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int st = 0; st + 1 < KS; ++st) {
+      read_a(nk - 1, st + 1, fa[(st + 1) & 1]);
+      read_b(nk - 1, st + 1, fb[(st + 1) & 1]);
+      mfma_step(fa[st & 1], fb[st & 1]);
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    mfma_step(fa[(KS - 1) & 1], fb[(KS - 1) & 1]);
+  } else if constexpr (!FDEEP) {
 #pragma unroll
     for (int t = 0; t < NSTAGE - 1; ++t)
       if (t < nk) issue();
@@ -589,8 +644,9 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE, bool A_T, bool B_T, int EPI>
 int launch(DmaGemmGroup& grp, hipStream_t stream) {
   constexpr int NW = WGM * WGN * (MODE == 2 ? 2 : 1);
-  using OpA = Operand<BM, A_T, NW>;
-  using OpB = Operand<BN, B_T, NW>;
+  constexpr int BK = NSTAGE == 2 ? 64 : 32;  // as in the kernel
+  using OpA = Operand<BM, A_T, NW, BK>;
+  using OpB = Operand<BN, B_T, NW, BK>;
   constexpr size_t lds = (size_t)NSTAGE * (OpA::kBytes + OpB::kBytes);
   auto kern = gemm_dma_kernel<BM, BN, WGM, WGN, NSTAGE, MODE, A_T, B_T, EPI>;
   static thread_local bool raised = false;
@@ -640,10 +696,11 @@ int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
 // Tile configurations: 0 = 256 x 256, 1 = 128 x 128 with an 8-deep buffer ring, 2 = 256 x 128,
 // 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU), 5 = as 4 with 8 wavefronts that split
 // the MFMA steps of a K tile, 6 = 256 x 256 with 8 wavefronts (2 x 4, 128 x 64 each: two per SIMD
-// that cover each other's stalls).  The others use 4 wavefronts.
+// that cover each other's stalls), 7 and 8 = 6 and 2 with a ring of two 64-wide K tiles instead of four
+// 32-wide ones (same bytes in flight, one barrier per 64 of K).  The others use 4 wavefronts.
 void gemm_dma_tile(int config, int& bm, int& bn) {
   bm = (config == 1 || config == 4 || config == 5) ? 128 : 256;
-  bn = (config == 0 || config == 6) ? 256 : 128;
+  bn = (config == 0 || config == 6 || config == 7) ? 256 : 128;  // 2 and 8: 256 x 128
 }
 
 bool gemm_dma_supported(const GemmArgs& g, int config) {
@@ -654,8 +711,9 @@ bool gemm_dma_supported(const GemmArgs& g, int config) {
   int bm, bn;
   gemm_dma_tile(config, bm, bn);
   // lane offsets are 32-bit byte offsets from the tile origin
-  const long span_a = (long)(g.a_t ? kBK : bm) * g.lda * 2, span_b = (long)(g.b_t ? kBK : bn) * g.ldb * 2;
-  return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % kBK == 0 && g.K >= kBK && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
+  const int bk = config == 7 || config == 8 ? 64 : kBK;
+  const long span_a = (long)(g.a_t ? bk : bm) * g.lda * 2, span_b = (long)(g.b_t ? bk : bn) * g.ldb * 2;
+  return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % bk == 0 && g.K >= bk && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
          g.ldc % 4 == 0 && span_a < (1L << 31) && span_b < (1L << 31);
 }
 
@@ -681,6 +739,8 @@ int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream
     case 4: return launch_layout<128, 128, 2, 2, 4, 1>(g, grp, stream);  // 64 KiB LDS: two per CU
     case 5: return launch_layout<128, 128, 2, 2, 4, 2>(g, grp, stream);
     case 6: return launch_layout<256, 256, 2, 4, 4, 0>(g, grp, stream);  // 8 wavefronts, 128 x 64 each
+    case 7: return launch_layout<256, 256, 2, 4, 2, 0>(g, grp, stream);  // as 6 with two stages of 64-wide K tiles
+    case 8: return launch_layout<256, 128, 2, 2, 2, 0>(g, grp, stream);  // as 2 with two stages of 64-wide K tiles
     default: return launch_layout<256, 128, 2, 2, 4, 0>(g, grp, stream);
   }
 }
