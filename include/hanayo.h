@@ -547,8 +547,9 @@ int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
    -1 (default) = chosen from the shape by a fitted cost model; 0 / 1 / 2 / 4 / 5 / 6 = direct-to-LDS
    kernel with 256x256 / 128x128 (8-deep load ring) / 256x128 / 128x128 (4-deep ring, two workgroups per
    CU) / 128x128 (8 wavefronts that split a K tile's MFMA steps) / 256x256 (8 wavefronts) tiles wherever
-   the shape is a whole number of tiles; 7 / 8 = as 6 / 2 with two stages of 64-wide K tiles instead of four
-   of 32 (K a multiple of 64); 3 = register-staged kernel only.  HANAYO_EINVAL outside -1..8.
+   the shape is a whole number of tiles; 7 / 8 / 9 = 256x256 (8 wavefronts) / 256x128 / 128x128 with two stages
+   of 64-wide K tiles instead of four of 32 (K a multiple of 64); 3 = register-staged kernel only.
+   HANAYO_EINVAL outside -1..9.
    Process-wide, not thread-safe. */
 int hanayo_op_gemm_config(int config);
 

@@ -133,7 +133,10 @@ int choose_dma_config(const GemmArgs* gs, int count) {
     const double cost = t.start + rounds * ((ktiles / tiles) * t.per_ktile + t.epilogue);
     if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
   }
-  if (best == 6 || best == 2) {  // the same tile with 64-wide K tiles (half the barriers per unit of work) where K allows it
+  // The same tile with 64-wide K tiles (half the barriers per unit of work) where K allows it.  Not for the
+  // 128 x 128 tile: its 64-wide form (config 9) wins on launches of several rounds (4096^3: 778 -> 1065 TFLOP/s)
+  // but not on the one-round launches this path uses that tile for.
+  if (best == 6 || best == 2) {
     const int wide_config = best == 6 ? 7 : 8;
     bool wide = true;
     for (int i = 0; i < count; ++i) wide = wide && gemm_dma_supported(gs[i], wide_config);

@@ -696,10 +696,10 @@ int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
 // Tile configurations: 0 = 256 x 256, 1 = 128 x 128 with an 8-deep buffer ring, 2 = 256 x 128,
 // 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU), 5 = as 4 with 8 wavefronts that split
 // the MFMA steps of a K tile, 6 = 256 x 256 with 8 wavefronts (2 x 4, 128 x 64 each: two per SIMD
-// that cover each other's stalls), 7 and 8 = 6 and 2 with a ring of two 64-wide K tiles instead of four
-// 32-wide ones (same bytes in flight, one barrier per 64 of K).  The others use 4 wavefronts.
+// that cover each other's stalls), 7, 8 and 9 = the tiles of 6, 2 and 4 with a ring of two 64-wide K tiles
+// instead of four 32-wide ones (same bytes in flight, one barrier per 64 of K).  The others use 4 wavefronts.
 void gemm_dma_tile(int config, int& bm, int& bn) {
-  bm = (config == 1 || config == 4 || config == 5) ? 128 : 256;
+  bm = (config == 1 || config == 4 || config == 5 || config == 9) ? 128 : 256;
   bn = (config == 0 || config == 6 || config == 7) ? 256 : 128;  // 2 and 8: 256 x 128
 }
 
@@ -711,7 +711,7 @@ bool gemm_dma_supported(const GemmArgs& g, int config) {
   int bm, bn;
   gemm_dma_tile(config, bm, bn);
   // lane offsets are 32-bit byte offsets from the tile origin
-  const int bk = config == 7 || config == 8 ? 64 : kBK;
+  const int bk = config >= 7 ? 64 : kBK;
   const long span_a = (long)(g.a_t ? bk : bm) * g.lda * 2, span_b = (long)(g.b_t ? bk : bn) * g.ldb * 2;
   return combo && g.M % bm == 0 && g.N % bn == 0 && g.K % bk == 0 && g.K >= bk && g.lda % 8 == 0 && g.ldb % 8 == 0 &&
          g.ldc % 4 == 0 && span_a < (1L << 31) && span_b < (1L << 31);
@@ -741,6 +741,7 @@ int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream
     case 6: return launch_layout<256, 256, 2, 4, 4, 0>(g, grp, stream);  // 8 wavefronts, 128 x 64 each
     case 7: return launch_layout<256, 256, 2, 4, 2, 0>(g, grp, stream);  // as 6 with two stages of 64-wide K tiles
     case 8: return launch_layout<256, 128, 2, 2, 2, 0>(g, grp, stream);  // as 2 with two stages of 64-wide K tiles
+    case 9: return launch_layout<128, 128, 2, 2, 2, 0>(g, grp, stream);  // 128 x 128 likewise (two workgroups per CU)
     default: return launch_layout<256, 128, 2, 2, 4, 0>(g, grp, stream);
   }
 }
