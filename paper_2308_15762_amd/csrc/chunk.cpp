@@ -111,7 +111,7 @@ int choose_dma_config(const GemmArgs* gs, int count) {
   }
   if (g_gemm_config != -1) return -1;
   static const struct { int config; double per_ktile, epilogue, start; } kTiles[] = {
-      {6, 0.84, 3.0, 7.0}, {2, 0.52, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
+      {6, 0.79, 3.0, 7.0}, {2, 0.49, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
   int best = -1;
   double best_cost = 0.0;
   for (const auto& t : kTiles) {
@@ -133,13 +133,19 @@ int choose_dma_config(const GemmArgs* gs, int count) {
     const double cost = t.start + rounds * ((ktiles / tiles) * t.per_ktile + t.epilogue);
     if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
   }
-  // The same tile with 64-wide K tiles (half the barriers per unit of work) where K allows it.  Not for the
-  // 128 x 128 tile: its 64-wide form (config 9) wins on launches of several rounds (4096^3: 778 -> 1065 TFLOP/s)
-  // but not on the one-round launches this path uses that tile for.
-  if (best == 6 || best == 2) {
-    const int wide_config = best == 6 ? 7 : 8;
+  // The same tile with 64-wide K tiles (half the barriers per unit of work) where K allows it.  For the 128 x 128
+  // tile only where a CU holds two workgroups at a time (more than 256 tiles, or a chip shared with other lanes):
+  // measured alone on the chip, 2048 x 2560 x 2560 takes 35 us instead of 44, but 4096 x 1024 x 4096, one
+  // workgroup per CU, 42 instead of 38.
+  if (best == 6 || best == 2 || best == 4) {
+    const int wide_config = best == 6 ? 7 : best == 2 ? 8 : 9;
     bool wide = true;
-    for (int i = 0; i < count; ++i) wide = wide && gemm_dma_supported(gs[i], wide_config);
+    long tiles = 0;
+    for (int i = 0; i < count; ++i) {
+      wide = wide && gemm_dma_supported(gs[i], wide_config);
+      tiles += (long)(gs[i].M / 128) * (gs[i].N / 128);
+    }
+    if (best == 4 && tiles <= 256 && g_gemm_sharing <= 0.0) wide = false;
     if (wide) best = wide_config;
   }
   return best;
