@@ -137,7 +137,7 @@ int head_loss(const Shape& sh, const hanayo_ends_desc* e, const void* lnf, const
   // The output has T H / 256^2 tiles (64 for 4096 x 1024) and the contraction runs over the whole vocabulary:
   // where the largest tile would leave most of the chip idle, K is cut into kHeadSplit slices that go out as one
   // grouped launch into fp32 partial products, summed by a small kernel.
-  const int slice = (V / kHeadSplit) / 64 * 64;
+  const int slice = (V / kHeadSplit) / 64 * 64;  // the last slice takes the rest
   const long tiles256 = (long)(T / 256) * (H / 256);
   bool split = sh.dtype == HANAYO_BF16 && slice >= 1024 && T % 256 == 0 && H % 256 == 0 && tiles256 * kHeadSplit <= 256;
   k::GemmArgs part[kHeadSplit];
@@ -149,10 +149,10 @@ int head_loss(const Shape& sh, const hanayo_ends_desc* e, const void* lnf, const
     part[i].C = ws + L.split + (size_t)i * T * H * sizeof(float);
     part[i].K = kn;
     part[i].epi = k::EPI_STORE_F32;
-    split = k::gemm_dma_supported(part[i], 6);
+    split = k::gemm_dma_supported(part[i], 7);  // 256 x 256 tiles, 64-wide K tiles
   }
   if (split) {
-    TRY(k::gemm_dma_group(part, kHeadSplit, 6, st));
+    TRY(k::gemm_dma_group(part, kHeadSplit, 7, st));
     TRY(k::sum_slices(sh.dtype, reinterpret_cast<const float*>(ws + L.split), kHeadSplit, (size_t)T * H, gx.C, st));
   } else {
     TRY(k::gemm(sh.dtype, gx, st));
