@@ -157,3 +157,56 @@ def test_benchmark_workload_with_the_models_ends():
     assert nerr(host(gpu.d_wte), d_wte) <= tol, "d_wte %.3g" % nerr(host(gpu.d_wte), d_wte)
     assert nerr(host(gpu.d_wpe), d_wpe) <= tol
     assert nerr(host(gpu.d_lnf)[:wl.hidden], d_g) <= tol and nerr(host(gpu.d_lnf)[wl.hidden:], d_b) <= tol
+
+
+def test_bert_workload_sampled_micro_batch_four_lanes():
+    """Configuration 3 (post-LN, key padding, 3 blocks per chunk, M = 16) at full size through the executor in the
+    launch configuration bench.py times (four lanes): micro-batch 9's boundary tensors of both of rank 0's chunks
+    against the oracle, and the stash peak against the plan."""
+    wl = W["bert_1024_bf16"]
+    tol = TOL["bf16"]
+    gpu = GpuRank(wl, 0, lanes=4)
+    peak = gpu.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0]
+    m = 9
+    cfg = oracle_cfg(wl)
+    vl = synth.valid_lengths(wl, m)
+    nchunk = 2 * wl.W
+    for c in range(nchunk):
+        params = synth.chunk_params(wl, c)
+        y, st = OB.chunk_forward(params, synth.forward_input(wl, m, c), cfg, vl)
+        dx, _ = OB.chunk_backward(cfg, st, synth.upstream_grad(wl, m, c))
+        del st
+        e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+        assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
+        e = nerr(host(gpu.grad_out[m * nchunk + c]), dx)
+        assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
+    for g in gpu.grads:
+        assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
+
+
+def test_wave4_workload_sampled_micro_batch_four_lanes():
+    """Configuration 5 (P = 8, W = 4, M = 64: rank 0's full list of 1024 tasks over 8 chunks) at full size, four
+    lanes: the stash peak against the plan (64 entries), and micro-batch 37 through the local turn-around
+    chunks 1 -> 2 against the oracle."""
+    wl = W["gpt_2560_wave4_bf16"]
+    tol = TOL["bf16"]
+    gpu = GpuRank(wl, 0, lanes=4)
+    peak = gpu.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0] == 64
+    m = 37
+    cfg = oracle_cfg(wl)
+    nchunk = 2 * wl.W
+    p1, p2 = (synth.chunk_params(wl, c) for c in (1, 2))
+    y1, st1 = OB.chunk_forward(p1, synth.forward_input(wl, m, 1), cfg)
+    y2, st2 = OB.chunk_forward(p2, y1, cfg)                                    # local hand-off
+    d2, _ = OB.chunk_backward(cfg, st2, synth.upstream_grad(wl, m, 2))
+    d1, _ = OB.chunk_backward(cfg, st1, d2)                                    # local hand-off
+    del st1, st2
+    for c, y, d in ((1, y1, d1), (2, y2, d2)):
+        e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+        assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
+        e = nerr(host(gpu.grad_out[m * nchunk + c]), d)
+        assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
