@@ -27,6 +27,15 @@ def printed_ratio(P, W):
     return (2.0 * P - 2.0) / (3.0 * P * W + P - 1.0)
 
 
+def paper_ratio(P, W, t_f, t_b, t_c):
+    """The paper's bubble-ratio equation (theoretical analysis section) with communication time: t_f and t_b are
+    the forward and backward times of ONE micro-batch through all 2W chunks of a device (the paper's T_F and T_B),
+    t_c one transfer.  With t_b = 2 t_f and t_c = 0 it reduces to printed_ratio."""
+    num = t_b / W + (1.0 + 2.0 * W + 2.0 / P + (P - 2.0) / 3.0) * t_c
+    den = P / (P - 1.0) * t_f + (1.0 / (2.0 * W) + P / (P - 1.0)) * t_b + ((P - 2.0) / 2.0 + 4.0 * W) * t_c
+    return num / den
+
+
 def consistent_ratio(P, W):
     """Idle (P - 1) T_B / W per rank (the numerator of the paper's bubble equation) over idle plus the
     rank's own compute P (T_F + T_B), with T_B = 2 T_F: the ratio that equation gives once numerator and
@@ -67,6 +76,8 @@ def report(wl, repeat=3, ends=False):
         "bubble_ratio_measured_times": float(np.mean(idle) / makespan),
         "bubble_ratio_assumed_costs": float(np.mean(unit_idle) / unit_makespan),
         "bubble_ratio_paper_closed_form_M_eq_P": printed_ratio(P, W),
+        "bubble_ratio_paper_equation_measured_times_M_eq_P": paper_ratio(P, W, 2 * W * float(f.mean()), 2 * W * float(b.mean()), 0.0)
+        if P > 1 else None,
         "bubble_ratio_numerator_form_M_eq_P": consistent_ratio(P, W),
         "one_gpu_total_ms": float(sum(m.sum() for m in ms)),
     }
@@ -116,6 +127,11 @@ def report_links(wl, link_workgroups=0, repeat=3):
         out["waited_ms_per_rank_" + name] = [float(v) for v in waited]
     makespan0, idle0, _ = hn.hanayo_replay_actions(gpu.actions, P, W, M, 0.0, 0.0, 0.0, False, ms_block)
     out["makespan_ms_t_c_zero"] = makespan0
+    comp = [(a["kind"] == hn.F, a["kind"] == hn.B) for a in gpu.actions]
+    t_f = float(np.concatenate([m[c[0]] for m, c in zip(ms_block, comp)]).mean())
+    t_b = float(np.concatenate([m[c[1]] for m, c in zip(ms_block, comp)]).mean())
+    if P > 1:  # the paper's own equation for M = P micro-batches, with the measured times
+        out["bubble_ratio_paper_equation_M_eq_P"] = paper_ratio(P, W, 2 * W * t_f, 2 * W * t_b, t_c_alone)
     return out
 
 

@@ -84,3 +84,21 @@ def test_replay_rejects_deadlock_and_bad_lists():
     with pytest.raises(hn.HanayoError) as e:
         hn.hanayo_replay(good, 0, W, M)
     assert e.value.code == hn.EINVAL
+
+
+def test_paper_bubble_equation_reduces_to_its_simplified_form():
+    """The bubble-ratio equation of the theoretical analysis section, as typed into the bubble report: with
+    T_B = 2 T_F and T_C = 0 it is (2P - 2) / (3PW + P - 1) exactly; it falls with W; communication time raises it."""
+    from fractions import Fraction
+    from paper_2308_15762_amd import bubble
+    for P in (2, 3, 4, 8, 16):
+        for W in (1, 2, 4):
+            got = bubble.paper_ratio(P, W, 1.0, 2.0, 0.0)
+            assert abs(got - float(Fraction(2 * P - 2, 3 * P * W + P - 1))) < 1e-12
+            assert abs(got - bubble.printed_ratio(P, W)) < 1e-12
+            assert bubble.paper_ratio(P, W, 1.0, 2.0, 0.05) > got
+        assert bubble.paper_ratio(P, 1, 1.0, 2.0, 0.0) > bubble.paper_ratio(P, 2, 1.0, 2.0, 0.0) > bubble.paper_ratio(P, 4, 1.0, 2.0, 0.0)
+    # a value worked by hand from the equation: P = 4, W = 2, T_F = 1, T_B = 2, T_C = 0.1
+    num = 2.0 / 2 + (1 + 4 + 0.5 + 2.0 / 3.0) * 0.1
+    den = 4.0 / 3.0 * 1.0 + (0.25 + 4.0 / 3.0) * 2.0 + (1.0 + 8.0) * 0.1
+    assert abs(bubble.paper_ratio(4, 2, 1.0, 2.0, 0.1) - num / den) < 1e-12
