@@ -1,9 +1,9 @@
 """GPU parity at the benchmark's full chunk shapes, in the launch configuration bench.py
 times (same kernels, same dispatch).  The oracle cannot replay a whole rank list at these
 sizes in seconds, so: one full micro-batch forward+backward of one chunk is compared
-element by element (configurations 2, 3 and 5; configuration 4 with one sequence chunk on
-sampled tensors), and for the benchmark workload the executor's outputs for one sampled
-micro-batch are compared with the oracle walking that micro-batch's tasks."""
+element by element (configurations 2, 3 and 5; configuration 4 with one block), and for
+every workload the executor's outputs for one sampled micro-batch are compared with the
+oracle walking that micro-batch's tasks."""
 
 import numpy as np
 import pytest
@@ -210,3 +210,27 @@ def test_wave4_workload_sampled_micro_batch_four_lanes():
         assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
         e = nerr(host(gpu.grad_out[m * nchunk + c]), d)
         assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
+
+
+def test_largest_workload_sampled_micro_batch_four_lanes():
+    """Configuration 4 (P = 16, W = 2, M = 32, H = 4096, 2048-token sequences: rank 0's list of 256 tasks) at
+    full size, four lanes: the stash peak against the plan, and micro-batch 21 through the last stage's chunk
+    (input and upstream gradient both from outside) against the oracle in float32."""
+    wl = W["gpt_4096_bf16"]
+    tol = TOL["bf16"]
+    gpu = GpuRank(wl, 0, lanes=4)
+    peak = gpu.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0]
+    m, c = 21, 2 * wl.W - 1
+    cfg = oracle_cfg(wl)
+    y, st = OB.chunk_forward(synth.chunk_params(wl, c), synth.forward_input(wl, m, c), cfg, dtype=np.float32)
+    dx, _ = OB.chunk_backward(cfg, st, synth.upstream_grad(wl, m, c))
+    del st
+    nchunk = 2 * wl.W
+    e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+    assert e <= tol, "act_out: %.3g" % e
+    e = nerr(host(gpu.grad_out[m * nchunk + c]), dx)
+    assert e <= tol, "grad_out: %.3g" % e
+    for g in gpu.grads:
+        assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
