@@ -562,6 +562,16 @@ int hanayo_op_layernorm_forward(int dtype, const void* x, const void* gamma, con
 int hanayo_op_layernorm_backward(int dtype, const void* dout, const void* x, const void* gamma, const float* stats,
                                  const void* addend, void* dz, float* dgamma, float* dbeta, float* scratch, int rows,
                                  int hidden, void* hip_stream);
+/* For callers that cannot allocate device memory or have no workspace to hand over (code under HIP graph
+   capture, tight serving loops, harnesses that forbid hipMalloc): hanayo_op_layernorm_backward without the
+   scratch argument.  The partial gamma/beta sums go to a fixed 8 MiB device array inside the library (one
+   copy per GPU, held until the process ends); the call allocates nothing and uses the same kernels, so the
+   results are those of hanayo_op_layernorm_backward.  hidden: multiple of 8, at most 4096, HANAYO_EINVAL
+   beyond that.  All calls on one GPU share the array: calls that may overlap on one GPU (different streams
+   or threads) race on it and must be ordered by the caller. */
+int hanayo_op_layernorm_backward_static(int dtype, const void* dout, const void* x, const void* gamma,
+                                        const float* stats, const void* addend, void* dz, float* dgamma, float* dbeta,
+                                        int rows, int hidden, void* hip_stream);
 /* out[n] (fp32) += sum over rows of in[row][n].  scratch: at least 64 * n floats. */
 int hanayo_op_colsum_add(int dtype, const void* in, int rows, int n, float* out, float* scratch, void* hip_stream);
 

@@ -4,6 +4,8 @@
 // that a wavefront touches 1 KiB (bf16) of contiguous memory per load, row
 // statistics are wavefront butterfly reductions, and per-column sums live in
 // registers across the rows a wavefront visits.
+#include <atomic>
+
 #include "device_util.h"
 #include "kernels.h"
 
@@ -13,6 +15,7 @@ namespace k {
 namespace {
 
 constexpr int kRowsPerBlock = 4;  // wavefronts per 256-thread block
+constexpr int kLnBwdMaxBlocks = 256;  // workgroups of the LN backward = partial rows of gamma/beta sums it writes
 
 // ------------------------------------------------------------------ LN forward
 // NV = vectors of 8 per lane kept in registers (H <= 64 * 8 * NV).
@@ -266,7 +269,7 @@ int ln_backward_t(const void* dout, const void* x, const void* gamma, const floa
   const int nv = (H + 511) / 512;
   const int waves = nv <= 4 ? 8 : 4;
   int blocks = (T_ + waves - 1) / waves;
-  if (blocks > 256) blocks = 256;  // a wavefront then walks several rows; 256 partial rows at most
+  if (blocks > kLnBwdMaxBlocks) blocks = kLnBwdMaxBlocks;  // a wavefront then walks several rows
   const size_t lds = (size_t)4 * H * sizeof(float);
 #define LAUNCH(NV, U, WAVES)                                                                                   \
   hipLaunchKernelGGL((ln_bwd_kernel<T, NV, U, WAVES>), dim3(blocks), dim3(WAVES * 64), lds, stream, (const T*)dout, \
@@ -348,3 +351,52 @@ int copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t stream, int
 
 }  // namespace k
 }  // namespace hanayo
+
+// ---------------------------------------------------------------------------------------------
+// LayerNorm backward for callers that cannot allocate and have no workspace to pass: the partial
+// rows of the gamma/beta sums live in a fixed array of the library's own, one copy per GPU.
+namespace {
+constexpr int kStaticMaxHidden = 4096;
+constexpr size_t kStaticScratchFloats = (size_t)hanayo::k::kLnBwdMaxBlocks * 2 * kStaticMaxHidden;  // 8 MiB
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
+
+// Device address of `scratch` on each GPU: the array's name is only a host-side handle, so the
+// address is looked up once per device (with that device current) and kept.
+constexpr int kMaxDevices = 64;
+std::atomic<float*> scratch_ptr[kMaxDevices];
+
+int static_scratch(float** out) {
+  int device = -1;
+  hipError_t e = hipGetDevice(&device);
+  if (e != hipSuccess) return hanayo::set_error(HANAYO_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+  if (device < 0 || device >= kMaxDevices) return hanayo::set_error(HANAYO_EUNSUPPORTED, "device index %d", device);
+  float* p = scratch_ptr[device].load(std::memory_order_acquire);
+  if (!p) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !sym)
+      return hanayo::set_error(HANAYO_EHIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    p = static_cast<float*>(sym);
+    scratch_ptr[device].store(p, std::memory_order_release);  // two racing threads store the same address
+  }
+  *out = p;
+  return HANAYO_OK;
+}
+}  // namespace
+
+extern "C" int hanayo_op_layernorm_backward_static(int dtype, const void* dout, const void* x, const void* gamma,
+                                                   const float* stats, const void* addend, void* dz, float* dgamma,
+                                                   float* dbeta, int rows, int hidden, void* hip_stream) {
+  if (dtype != HANAYO_FP32 && dtype != HANAYO_BF16)
+    return hanayo::set_error(HANAYO_EINVAL, "dtype must be HANAYO_FP32 or HANAYO_BF16");
+  if (!dout || !x || !gamma || !stats || !dz || !dgamma || !dbeta || rows < 1)
+    return hanayo::set_error(HANAYO_EINVAL, "op_layernorm_backward_static: bad argument");
+  if (hidden < 8 || hidden % 8 || hidden > kStaticMaxHidden)
+    return hanayo::set_error(HANAYO_EINVAL, "op_layernorm_backward_static: hidden = %d, the fixed scratch array covers "
+                             "multiples of 8 up to %d", hidden, kStaticMaxHidden);
+  float* partial = nullptr;
+  if (int rc = static_scratch(&partial)) return rc;
+  // every partial row the finaliser reads is written by the backward kernel first: nothing to clear
+  return hanayo::k::ln_backward(dtype, dout, x, gamma, reinterpret_cast<const float2*>(stats), addend, dz, dgamma, dbeta,
+                                partial, rows, hidden, static_cast<hipStream_t>(hip_stream));
+}

@@ -108,7 +108,7 @@ EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
            "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_stash_arena_bytes_input",
            "hanayo_recompute_scratch_bytes", "hanayo_executor_run", "hanayo_executor_plan", "hanayo_pipeline_run", "hanayo_replay", "hanayo_actions", "hanayo_replay_actions", "hanayo_pipeline_run_actions", "hanayo_device_info",
-           "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_colsum_add",
+           "hanayo_op_gemm", "hanayo_op_gemm_group", "hanayo_op_gemm_config", "hanayo_op_copy", "hanayo_op_layernorm_forward", "hanayo_op_layernorm_backward", "hanayo_op_layernorm_backward_static", "hanayo_op_colsum_add",
            "hanayo_op_attention_forward", "hanayo_op_attention_backward",
            "hanayo_embed_forward", "hanayo_embed_backward", "hanayo_head_workspace_bytes", "hanayo_head_loss",
            "hanayo_adam_step", "hanayo_chunk_adam_step", "hanayo_ends_workspace_bytes")
@@ -151,6 +151,7 @@ _lib.hanayo_op_gemm_config.argtypes = [_int]
 _lib.hanayo_op_copy.argtypes = [_vp, _vp, _sz, _vp]
 _lib.hanayo_op_layernorm_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _vp, _vp, _int, _int, ctypes.c_float, _vp]
 _lib.hanayo_op_layernorm_backward.argtypes = [_int] + [_vp] * 9 + [_int, _int, _vp]
+_lib.hanayo_op_layernorm_backward_static.argtypes = [_int] + [_vp] * 8 + [_int, _int, _vp]
 _lib.hanayo_op_colsum_add.argtypes = [_int, _vp, _int, _int, _vp, _vp, _vp]
 _lib.hanayo_op_attention_forward.argtypes = [_int, _vp, _vp, _vp, _vp, _int, _int, _int, _int, _int, _vp]
 _lib.hanayo_op_attention_backward.argtypes = [_int] + [_vp] * 7 + [_int] * 5 + [_vp]
@@ -413,6 +414,13 @@ def hanayo_op_layernorm_backward(dtype, dout, x, gamma, stats, addend, dz, dgamm
                                  stream=None):
     _check(_lib.hanayo_op_layernorm_backward(dtype, _ptr(dout), _ptr(x), _ptr(gamma), _ptr(stats), _ptr(addend),
                                              _ptr(dz), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), rows, hidden, stream))
+
+
+def hanayo_op_layernorm_backward_static(dtype, dout, x, gamma, stats, addend, dz, dgamma, dbeta, rows, hidden,
+                                        stream=None):
+    _check(_lib.hanayo_op_layernorm_backward_static(dtype, _ptr(dout), _ptr(x), _ptr(gamma), _ptr(stats),
+                                                    _ptr(addend), _ptr(dz), _ptr(dgamma), _ptr(dbeta), rows, hidden,
+                                                    stream))
 
 
 def hanayo_op_colsum_add(dtype, inp, rows, n, out, scratch, stream=None):
