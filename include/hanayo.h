@@ -81,6 +81,47 @@ int hanayo_rank_stage(int P, int W, int rank, int chunk, int* stage /* host out 
 int hanayo_schedule(int P, int W, int M, int rank, hanayo_task* out, size_t cap, size_t* n);
 
 /*
+ * The other schedulers (runtime section: "scheduling algorithms for existing mainstream pipeline schemes" next
+ * to Hanayo's, all emitting the same kind of per-worker list; background section for what each scheme does).
+ *   HANAYO_SCHEME_HANAYO        hanayo_schedule(P, W, M, rank)
+ *   HANAYO_SCHEME_CHIMERA_WAVE  Chimera after the swap of the section on transforming it into wave-like
+ *                               pipelines (mirrored blocks exchanged, replicas become data parallelism, order
+ *                               of computation unchanged): the one-wave list; W must be 1
+ *   HANAYO_SCHEME_GPIPE         one stage per device; every forward pass of the iteration, then every backward
+ *   HANAYO_SCHEME_1F1B          DAPPLE's one-forward-one-backward: P-1-rank forward passes, then forward and
+ *                               backward alternate, then the remaining backward passes (at most P - rank
+ *                               activations alive on device `rank`)
+ * Placements.  The two wave schemes use the placement above (2W chunks per device).  GPipe and 1F1B use the
+ * straight placement: S = P stages, stage s on device s, one chunk per device; in Table 1's notation that is
+ * W = S / 2P = 1/2, and it is written W = 0 in this interface: pass W = 0 to hanayo_schedule_scheme and to
+ * hanayo_stage_rank, hanayo_rank_stage, hanayo_stash_plan, hanayo_stash_arena_bytes*, hanayo_executor_plan,
+ * hanayo_executor_run, hanayo_pipeline_run and hanayo_replay when they handle such a list (2*M records per
+ * rank, chunk 0, stage = rank).  Same calling convention and error codes as hanayo_schedule; HANAYO_EINVAL
+ * for a W that does not fit the scheme.
+ */
+enum { HANAYO_SCHEME_HANAYO = 0, HANAYO_SCHEME_CHIMERA_WAVE = 1, HANAYO_SCHEME_GPIPE = 2, HANAYO_SCHEME_1F1B = 3 };
+int hanayo_schedule_scheme(int scheme, int P, int W, int M, int rank, hanayo_task* out, size_t cap, size_t* n);
+
+/*
+ * Bubble model (theoretical-analysis section; host only).  t_f / t_b: a device's whole forward / backward
+ * time for one micro-batch (the paper's T_F and T_B: all its stages added), t_c: one transfer (T_C).
+ *   wave schemes (M must equal P, the case the paper's equation covers):
+ *     *ratio         = ( T_B/W + (1 + 2W + 2/P + (P-2)/3) T_C )
+ *                      / ( P/(P-1) T_F + (1/(2W) + P/(P-1)) T_B + ((P-2)/2 + 4W) T_C )       as printed;
+ *                      (2P-2)/(3PW+P-1) at T_B = 2 T_F, T_C = 0
+ *     *idle          = (P-1) times the numerator: the idle time per device that the summed bubble zones give
+ *     *ratio_of_idle = idle / (idle + M (T_F + T_B)): the same bubble over the iteration time that follows
+ *                      from it (the printed denominator counts only half of the idle term)
+ *   GPipe, 1F1B (any M): idle = (P-1)(T_F + T_B + 2 T_C): the fill before the last device starts and the
+ *     drain after its last backward; ratio = ratio_of_idle = idle / (idle + M (T_F + T_B)).  Exact for GPipe
+ *     while the other transfers hide behind compute (receives posted one task ahead, T_C <= T_F); for 1F1B
+ *     exact at T_C = 0; a lower bound otherwise (hanayo_replay_actions simulates those cases).
+ * Outputs may be NULL.  HANAYO_EINVAL: bad scheme / W combination, M != P for a wave scheme, negative times.
+ */
+int hanayo_bubble_model(int scheme, int P, int W, int M, double t_f, double t_b, double t_c, double* ratio,
+                        double* idle, double* ratio_of_idle);
+
+/*
  * Activation-stash accounting of a list (M_a of Table 1 counted per chunk):
  * an entry lives from the F task of (mb, chunk) to its B task.
  *   peak_total  host out, may be NULL: peak number of live entries
@@ -255,7 +296,7 @@ int hanayo_chunk_adam_step(const hanayo_adam* o, const hanayo_chunk_desc* d, voi
  * ------------------------------------------------------------------------- */
 typedef struct hanayo_exec_args {
   const hanayo_chunk_desc* desc;
-  int P, W, M, rank;
+  int P, W, M, rank;                /* W = 0: straight placement (GPipe / 1F1B lists), one chunk: read "1" for "2W" below */
   const void* const* weights;      /* host [2W] -> device */
   float* const* grads;             /* host [2W] -> device fp32 */
   const void* const* act_in;       /* host [M*2W] -> device */
@@ -376,6 +417,11 @@ typedef struct hanayo_action {
 } hanayo_action;  /* 12 bytes, no padding */
 
 int hanayo_actions(int P, int W, int M, int rank, hanayo_action* out, size_t cap, size_t* n);
+/* The same for any task list of rank `rank` (a list of hanayo_schedule_scheme; W = 0 for the straight
+   placement): the list with its receive and send actions put around the tasks.  HANAYO_ESTATE if a record is
+   not a task of that rank. */
+int hanayo_actions_of(const hanayo_task* tasks /* host */, size_t count, int P, int W, int rank, hanayo_action* out,
+                      size_t cap, size_t* n);
 
 /*
  * Host only: the P interpreters simulated.  Sends are asynchronous (no time on the sender); a transfer starts

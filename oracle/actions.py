@@ -33,9 +33,14 @@ RECVS = (RECV_ACT, RECV_GRAD)
 def actions(P, W, M, rank):
     """[(kind, mb, chunk, stage, peer)] for one rank; peer = own rank for compute actions.
     `stage` of a communication action is the stage of the local compute it serves."""
-    S = 2 * W * P
+    return actions_from_tasks(OS.schedule(P, W, M, rank), P, W, rank)
+
+
+def actions_from_tasks(tasks, P, W, rank):
+    """The action list of any scheme's task list (W = 0: straight placement), same reading."""
+    S = OS.n_stages(P, W)
     out = []
-    for t in OS.schedule(P, W, M, rank):
+    for t in tasks:
         kind, mb, chunk, stage = t
         if kind == OS.F:
             src = OS.stage_rank(P, W, stage - 1) if stage > 0 else rank
@@ -98,7 +103,7 @@ def check_matching(lists, P, W, M):
 def replay(lists, P, W, M, t_f=1.0, t_b=2.0, t_c=0.0, prefetch=False):
     """Event simulation of the P interpreters.  Returns dict(makespan, idle, waited): `waited[r]` = time
     rank r spent blocked in receives.  Raises AssertionError on deadlock."""
-    S = 2 * W * P
+    S = OS.n_stages(P, W)
     done = {}       # (kind, mb, stage) of compute actions -> finish time
     sent = {}       # message -> time the send was executed
     posted = {}     # message -> time the receive was posted

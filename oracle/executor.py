@@ -30,10 +30,10 @@ def run_rank(tasks, P, W, rank, cfg, chunk_params, act_in, grad_in, valid_len=No
     labels(mb), loss_scale); then act_in / grad_in are not asked for stage 0 / the last stage.
     Returns dict(act_out, grad_out, grads, peak) and with ends also loss {mb: value} and
     ends_grads dict(wte, wpe, head (None if tied: its gradient is inside wte), lnf)."""
-    S = 2 * W * P
+    S = OS.n_stages(P, W)          # W = 0: the straight placement of a GPipe / 1F1B list (one chunk per rank)
     kw = {} if dtype is None else {"dtype": dtype}
     act_out, grad_out, stash = {}, {}, {}
-    grads = [None] * (2 * W)
+    grads = [None] * OS.chunks_per_rank(W)
     peak = 0
     loss, loss_grad, eg = {}, {}, None
     if ends is not None:

@@ -97,7 +97,7 @@ def run_pipeline(lists, P, W, M, cfg, stage_params, xs, dys, valid_len=None, dty
     forward task of the last stage, the embedding's backward the backward task of stage 0).
     Raises AssertionError on a list that deadlocks or runs a task twice."""
     kw = {} if dtype is None else {"dtype": dtype}
-    S = 2 * W * P
+    S = OS.n_stages(P, W)          # W = 0: straight placement (GPipe / 1F1B lists)
     en = _Ends(ends) if ends is not None else None
     loss_grad = {}
     assert len(lists) == P and len(stage_params) == S and (en is not None or (len(xs) == M and len(dys) == M))

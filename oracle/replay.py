@@ -22,6 +22,12 @@ def _placement(P, W, stage):
     return pos if lap % 2 == 0 else P - 1 - pos
 
 
+def _n_stages(P, W):
+    """W waves: 2*W*P stages.  W = 0 stands for the straight placement of GPipe and 1F1B (one stage per
+    device, half a wave in Table 1's W = S / 2P), where stage s sits on device s."""
+    return 2 * W * P if W else P
+
+
 def replay(lists, P, W, M, cost_f=1, cost_b=2, cost=None):
     """Execute the lists; return dict(makespan, idle, start, finish, peak).
 
@@ -31,11 +37,11 @@ def replay(lists, P, W, M, cost_f=1, cost_b=2, cost=None):
     Raises AssertionError on: wrong rank for a stage, a task missing or
     repeated, chunk field inconsistent with the stage, deadlock.
     """
-    S = 2 * W * P
+    S = _n_stages(P, W)
     assert len(lists) == P
     seen = set()
     for r, lst in enumerate(lists):
-        assert len(lst) == 4 * W * M, "rank %d: list length" % r
+        assert len(lst) == 2 * (S // P) * M, "rank %d: list length" % r
         for (kind, mb, chunk, stage) in lst:
             assert kind in (F, B) and 0 <= mb < M and 0 <= stage < S
             assert _placement(P, W, stage) == r, "task on the wrong rank"

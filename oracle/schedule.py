@@ -41,7 +41,14 @@ Task = namedtuple("Task", "kind mb chunk stage")
 
 
 def n_stages(P, W):
-    return 2 * W * P
+    """W waves: 2*W*P stages.  W = 0 denotes the straight placement of the comparison schemes (GPipe, 1F1B):
+    one stage per device, S = P, half a wave in Table 1's W = S / 2P; stage_rank / rank_stage then reduce to
+    stage s on device s."""
+    return 2 * W * P if W else P
+
+
+def chunks_per_rank(W):
+    return 2 * W if W else 1
 
 
 def stage_rank(P, W, stage):
@@ -54,7 +61,7 @@ def stage_rank(P, W, stage):
 
 def rank_stage(P, W, rank, chunk):
     """Global stage of a rank's local chunk (chunk = stage // P)."""
-    if not (0 <= rank < P and 0 <= chunk < 2 * W):
+    if not (0 <= rank < P and 0 <= chunk < chunks_per_rank(W)):
         raise ValueError("rank/chunk out of range")
     return chunk * P + (rank if chunk % 2 == 0 else P - 1 - rank)
 
@@ -154,7 +161,7 @@ def stash_plan(tasks, W):
     a B task the id its F took.  Raises on a B without a live F or a second F
     of a live (mb, chunk).
     """
-    nchunk = 2 * W
+    nchunk = chunks_per_rank(W)
     live = {}
     used = [set() for _ in range(nchunk)]
     per_chunk = [0] * nchunk

@@ -11,6 +11,7 @@ closed form the paper gives for one unit of P micro-batches.
 
     python -m paper_2308_15762_amd.bubble --workload gpt_1024_bf16 [--M 4] [--repeat 3]
     python -m paper_2308_15762_amd.bubble --links [--link-workgroups 2]      (see report_links)
+    python -m paper_2308_15762_amd.bubble --figure [--t-c 0.1]               (host only, see figure_table)
 
 Prints one JSON line.
 """
@@ -23,24 +24,57 @@ import numpy as np
 
 
 def printed_ratio(P, W):
-    """The paper's simplified bubble ratio for M = P micro-batches, T_B = 2 T_F, T_C = 0."""
-    return (2.0 * P - 2.0) / (3.0 * P * W + P - 1.0)
+    """The paper's simplified bubble ratio for M = P micro-batches, T_B = 2 T_F, T_C = 0 (hanayo_bubble_model)."""
+    from . import hanayo as hn
+    return hn.hanayo_bubble_model(hn.SCHEME_HANAYO, P, W, P, 1.0, 2.0, 0.0)[0] if P > 1 else 0.0
 
 
 def paper_ratio(P, W, t_f, t_b, t_c):
-    """The paper's bubble-ratio equation (theoretical analysis section) with communication time: t_f and t_b are
-    the forward and backward times of ONE micro-batch through all 2W chunks of a device (the paper's T_F and T_B),
-    t_c one transfer.  With t_b = 2 t_f and t_c = 0 it reduces to printed_ratio."""
-    num = t_b / W + (1.0 + 2.0 * W + 2.0 / P + (P - 2.0) / 3.0) * t_c
-    den = P / (P - 1.0) * t_f + (1.0 / (2.0 * W) + P / (P - 1.0)) * t_b + ((P - 2.0) / 2.0 + 4.0 * W) * t_c
-    return num / den
+    """The paper's bubble-ratio equation (theoretical analysis section) with communication time, from
+    hanayo_bubble_model: t_f and t_b are the forward and backward times of ONE micro-batch through all 2W
+    chunks of a device (the paper's T_F and T_B), t_c one transfer."""
+    from . import hanayo as hn
+    return hn.hanayo_bubble_model(hn.SCHEME_HANAYO, P, W, P, t_f, t_b, t_c)[0]
 
 
 def consistent_ratio(P, W):
-    """Idle (P - 1) T_B / W per rank (the numerator of the paper's bubble equation) over idle plus the
-    rank's own compute P (T_F + T_B), with T_B = 2 T_F: the ratio that equation gives once numerator and
-    denominator use the same idle time."""
-    return (2.0 * P - 2.0) / (3.0 * P * W + 2.0 * P - 2.0)
+    """The same equation's idle time (its numerator) over idle plus the rank's own compute, T_B = 2 T_F."""
+    from . import hanayo as hn
+    return hn.hanayo_bubble_model(hn.SCHEME_HANAYO, P, W, P, 1.0, 2.0, 0.0)[2]
+
+
+def figure_table(t_c=0.0, prefetch=True):
+    """The curves of the paper's bubble-ratio figure, host only: for each device count P (B = P micro-batches,
+    T_B = 2 T_F, transfers t_c in units of T_F) the ratio of GPipe, 1F1B, Chimera-wave and Hanayo with 2, 4
+    and 8 waves, from the model (hanayo_bubble_model) and, in brackets, from the library's schedules replayed
+    by the interpreter simulation (hanayo_replay_actions).  Returns the table as a list of rows."""
+    from . import hanayo as hn
+    cols = [("GPipe", hn.SCHEME_GPIPE, 0), ("1F1B", hn.SCHEME_1F1B, 0), ("Chimera-wave", hn.SCHEME_CHIMERA_WAVE, 1),
+            ("Hanayo W=2", hn.SCHEME_HANAYO, 2), ("Hanayo W=4", hn.SCHEME_HANAYO, 4), ("Hanayo W=8", hn.SCHEME_HANAYO, 8)]
+    rows = []
+    for P in (2, 4, 8, 16, 32):
+        row = {"P": P}
+        for name, scheme, W in cols:
+            model = hn.hanayo_bubble_model(scheme, P, W, P, 1.0, 2.0, t_c)
+            tasks = [hn.hanayo_schedule_scheme(scheme, P, W, P, r) for r in range(P)]
+            acts = [hn.hanayo_actions_of(tasks[r], P, W, r) for r in range(P)]
+            # a task of a wave scheme is 1/2W of the device's forward or backward time
+            n = hn.chunks_per_rank(W)
+            makespan, idle, _ = hn.hanayo_replay_actions(acts, P, W, P, 1.0 / n, 2.0 / n, t_c, prefetch)
+            row[name] = (model[0], model[2], float(np.mean(idle) / makespan))
+        rows.append(row)
+    return rows
+
+
+def print_figure(t_c, prefetch):
+    rows = figure_table(t_c, prefetch)
+    names = [k for k in rows[0] if k != "P"]
+    print("bubble ratio at B = P, T_B = 2 T_F, T_C = %g T_F: equation as printed / idle form / schedule simulated%s"
+          % (t_c, " with prefetch" if prefetch else ""))
+    print("| P | " + " | ".join(names) + " |")
+    print("|---|" + "---|" * len(names))
+    for row in rows:
+        print("| %d | " % row["P"] + " | ".join("%.3f / %.3f / %.3f" % row[k] for k in names) + " |")
 
 
 def measure(wl, repeat=3, ends=False):
@@ -143,7 +177,13 @@ def main():
     ap.add_argument("--ends", action="store_true", help="embedding in front of stage 0, head + loss behind the last stage")
     ap.add_argument("--links", action="store_true", help="run from action lists with the transfers carried out")
     ap.add_argument("--link-workgroups", type=int, default=0, help="workgroups of a transfer's copy kernel (0 = unrestricted)")
+    ap.add_argument("--figure", action="store_true",
+                    help="host only: the bubble-ratio curves of every scheme (model and simulated schedules)")
+    ap.add_argument("--t-c", type=float, default=0.0, help="--figure: transfer time in units of T_F")
     args = ap.parse_args()
+    if args.figure:
+        print_figure(args.t_c, True)
+        return
     import torch
     from . import synth
     if not torch.cuda.is_available():

@@ -45,12 +45,12 @@ struct Plan {
 
 int make_plan(const hanayo_task* list, size_t n, int W, Plan& pl) {
   pl.slot.assign(n, 0);
-  pl.per_chunk.assign(2 * W, 0);
+  pl.per_chunk.assign(chunks_per_rank(W), 0);
   const int rc = plan_stash(list, n, W, &pl.peak, pl.per_chunk.data(), pl.slot.data());
   if (rc) return rc;
-  pl.chunk_base.assign(2 * W, 0);
+  pl.chunk_base.assign(chunks_per_rank(W), 0);
   size_t at = 0;
-  for (int c = 0; c < 2 * W; ++c) {
+  for (int c = 0; c < chunks_per_rank(W); ++c) {
     pl.chunk_base[c] = at;
     at += (size_t)pl.per_chunk[c];
   }
@@ -78,7 +78,7 @@ struct LanePlan {
 // head_cost: with ends, what the head and loss add to the forward task of the last stage, in forward tasks.
 void plan_lanes(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes, bool ends, double head_cost,
                 const Plan& pl, LanePlan& lp) {
-  const int nchunk = 2 * W, S = 2 * W * P;
+  const int nchunk = chunks_per_rank(W), S = nchunk * P;
   lp.lane.assign(n, 0);
   lp.dep.assign(n, {-1, -1, -1, -1, -1});
   int32_t last_ends = -1;
@@ -193,12 +193,20 @@ struct TimingEvents {
     const hipError_t e_ = (call);                                                                      \
     if (e_ != hipSuccess) return set_error(HANAYO_EHIP, "executor: %s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
+// Inside the executor's task loop a failure must not return: the loop ends, and the run still resets the
+// GEMM tile-choice state of the thread and joins the side lanes into the caller's stream.
+#define HIP_NOTE(rc, call)                                                                             \
+  do {                                                                                                 \
+    const hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess && !(rc)) (rc) = set_error(HANAYO_EHIP, "executor: %s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
 
 // The list must hold exactly this rank's tasks, once each, in an order in which
 // every task's local predecessor has already run.
 int validate(const hanayo_task* list, size_t n, int P, int W, int M, int rank) {
-  const int nchunk = 2 * W, S = 2 * W * P;
-  if (n != (size_t)4 * W * M) return set_error(HANAYO_ESTATE, "executor: list has %zu tasks, rank needs %d", n, 4 * W * M);
+  const int nchunk = chunks_per_rank(W), S = nchunk * P;
+  if (n != (size_t)2 * nchunk * M)
+    return set_error(HANAYO_ESTATE, "executor: list has %zu tasks, rank needs %d", n, 2 * nchunk * M);
   std::vector<char> fdone((size_t)M * nchunk, 0), bdone((size_t)M * nchunk, 0);
   for (size_t i = 0; i < n; ++i) {
     const hanayo_task& tk = list[i];
@@ -244,7 +252,7 @@ extern "C" {
 
 size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const hanayo_chunk_desc* d) {
   Shape sh;
-  if (make_shape(d, sh) || W < 1 || 2 * W > 255 || (!list && n)) return 0;
+  if (make_shape(d, sh) || W < 0 || 2 * W > 255 || (!list && n)) return 0;
   Plan pl;
   if (make_plan(list, n, W, pl)) return 0;
   return pl.entries * (stash_layout(sh).block_bytes * sh.nb);
@@ -252,7 +260,7 @@ size_t hanayo_stash_arena_bytes(const hanayo_task* list, size_t n, int W, const 
 
 size_t hanayo_stash_arena_bytes_input(const hanayo_task* list, size_t n, int W, const hanayo_chunk_desc* d) {
   Shape sh;
-  if (make_shape(d, sh) || W < 1 || 2 * W > 255 || (!list && n)) return 0;
+  if (make_shape(d, sh) || W < 0 || 2 * W > 255 || (!list && n)) return 0;
   Plan pl;
   if (make_plan(list, n, W, pl)) return 0;
   return pl.entries * align_up((size_t)sh.T * sh.H * sh.esz, 256);
@@ -280,8 +288,10 @@ double head_cost_of(const Shape& sh, const hanayo_ends_desc& e) {
 int hanayo_executor_plan(const hanayo_task* list, size_t n, int P, int W, int M, int rank, int lanes,
                          const hanayo_chunk_desc* d, const hanayo_ends_desc* e, int32_t* lane, int32_t* deps) {
   if (!list || !lane || !deps) return set_error(HANAYO_EINVAL, "executor_plan: NULL argument");
-  if (P < 1 || W < 1 || M < 1 || rank < 0 || rank >= P || 2 * W > 255 || lanes < 1 || lanes > kMaxLanes)
+  if (P < 1 || W < 0 || M < 1 || rank < 0 || rank >= P || 2 * W > 255 || lanes < 1 || lanes > kMaxLanes)
     return set_error(HANAYO_EINVAL, "executor_plan: bad P=%d W=%d M=%d rank=%d lanes=%d", P, W, M, rank, lanes);
+  if (e && W == 0 && P > 1)
+    return set_error(HANAYO_EUNSUPPORTED, "executor_plan: the model's ends need the first and the last stage on one rank");
   int rc = validate(list, n, P, W, M, rank);
   if (rc) return rc;
   Plan pl;
@@ -310,7 +320,7 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
       !a->stash_arena || !a->workspace)
     return set_error(HANAYO_EINVAL, "executor: NULL argument");
   const int P = a->P, W = a->W, M = a->M, rank = a->rank;
-  if (P < 1 || W < 1 || M < 1 || rank < 0 || rank >= P || 2 * W > 255)
+  if (P < 1 || W < 0 || M < 1 || rank < 0 || rank >= P || 2 * W > 255)
     return set_error(HANAYO_EINVAL, "executor: bad P=%d W=%d M=%d rank=%d", P, W, M, rank);
   Shape sh;
   int rc = prepare_call(a->desc, sh);
@@ -330,9 +340,12 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
   if (pl.entries * entry_bytes > a->stash_arena_bytes)
     return set_error(HANAYO_ESTATE, "executor: stash arena holds %zu bytes, plan needs %zu", a->stash_arena_bytes,
                      pl.entries * entry_bytes);
-  const int nchunk = 2 * W, S = 2 * W * P;
+  const int nchunk = chunks_per_rank(W), S = nchunk * P;
   // the model's ends sit on rank 0: stage 0 and stage S - 1
   const hanayo_ends_args* en = rank == 0 ? a->ends : nullptr;
+  if (a->ends && W == 0 && P > 1)
+    return set_error(HANAYO_EUNSUPPORTED, "executor: the model's ends need the first and the last stage on one rank "
+                     "(any wave placement); a straight placement splits them over ranks 0 and P-1");
   if (en) {
     rc = check_ends_args(sh, en, M);
     if (rc) return rc;
@@ -388,7 +401,8 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
     const int lane = lp.lane[i];
     hipStream_t st = stream[lane];
     for (int32_t j : lp.dep[i])
-      if (j >= 0 && lp.lane[j] != lane) HIP_TRY(hipStreamWaitEvent(st, res->events[j], 0));
+      if (j >= 0 && lp.lane[j] != lane) HIP_NOTE(rc, hipStreamWaitEvent(st, res->events[j], 0));
+    if (rc) break;
     // Measured: next to one other busy lane the shortest GEMM launch still wins, next to three the
     // one with the least CU time does; the plan says how busy the other lanes are during this task.
     k::set_gemm_sharing((lp.busy[i] - 2.0f) * 0.5f);
@@ -428,13 +442,16 @@ int hanayo_executor_run(const hanayo_task* list, size_t n, const hanayo_exec_arg
       --live;
     }
     if (rc) break;
-    if (signals[i]) HIP_TRY(hipEventRecord(res->events[i], st));
+    if (signals[i]) HIP_NOTE(rc, hipEventRecord(res->events[i], st));
+    if (rc) break;
   }
   k::set_gemm_sharing(0.0);
-  // join, also after a failed enqueue: the caller's stream ends after every side lane
+  // join, also after a failed enqueue or a failed event call: the caller's stream ends after every side lane
   for (int l = 1; l < lanes; ++l) {
-    HIP_TRY(hipEventRecord(res->events[n + l], stream[l]));
-    HIP_TRY(hipStreamWaitEvent(stream[0], res->events[n + l], 0));
+    int jrc = 0;
+    HIP_NOTE(jrc, hipEventRecord(res->events[n + l], stream[l]));
+    if (!jrc) HIP_NOTE(jrc, hipStreamWaitEvent(stream[0], res->events[n + l], 0));
+    if (jrc && !rc) rc = jrc;
   }
   if (rc) return rc;
   if (peak_seen) *peak_seen = peak;
@@ -452,11 +469,11 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
       !a->stash_arena_bytes || !a->workspace || (!a->ends && (!a->x || !a->dy)))
     return set_error(HANAYO_EINVAL, "pipeline: NULL argument");
   const int P = a->P, W = a->W, M = a->M;
-  if (P < 1 || W < 1 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "pipeline: bad P=%d W=%d M=%d", P, W, M);
+  if (P < 1 || W < 0 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "pipeline: bad P=%d W=%d M=%d", P, W, M);
   Shape sh;
   int rc = prepare_call(a->desc, sh);
   if (rc) return rc;
-  const int nchunk = 2 * W, S = nchunk * P;
+  const int nchunk = chunks_per_rank(W), S = nchunk * P;
   const hanayo_ends_args* en = a->ends;
   if (en) {
     rc = check_ends_args(sh, en, M);
@@ -563,8 +580,8 @@ int hanayo_pipeline_run(const hanayo_task* const* lists, const size_t* counts, c
 int hanayo_replay(const hanayo_task* const* lists, const size_t* counts, int P, int W, int M, const float* const* cost,
                   double* makespan, double* idle) {
   if (!lists || !counts || !makespan) return set_error(HANAYO_EINVAL, "replay: NULL argument");
-  if (P < 1 || W < 1 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "replay: bad P=%d W=%d M=%d", P, W, M);
-  const int S = 2 * W * P;
+  if (P < 1 || W < 0 || M < 1 || 2 * W > 255) return set_error(HANAYO_EINVAL, "replay: bad P=%d W=%d M=%d", P, W, M);
+  const int S = chunks_per_rank(W) * P;
   for (int r = 0; r < P; ++r) {
     if (!lists[r] || (cost && !cost[r])) return set_error(HANAYO_EINVAL, "replay: rank %d has no list or costs", r);
     const int rc = validate(lists[r], counts[r], P, W, M, r);
@@ -618,9 +635,9 @@ int hanayo_replay_actions(const hanayo_action* const* lists, const size_t* count
                           double t_b, double t_c, int prefetch, const float* const* cost, double* makespan,
                           double* idle, double* waited) {
   if (!lists || !counts || !makespan) return set_error(HANAYO_EINVAL, "replay_actions: NULL argument");
-  if (P < 1 || W < 1 || M < 1 || 2 * W > 255 || !(t_f >= 0.0) || !(t_b >= 0.0) || !(t_c >= 0.0))
+  if (P < 1 || W < 0 || M < 1 || 2 * W > 255 || !(t_f >= 0.0) || !(t_b >= 0.0) || !(t_c >= 0.0))
     return set_error(HANAYO_EINVAL, "replay_actions: bad P=%d W=%d M=%d or negative time", P, W, M);
-  const int S = 2 * W * P;
+  const int S = chunks_per_rank(W) * P;
   // structure: the compute actions are the rank's tasks; each communication action belongs to its neighbour
   for (int r = 0; r < P; ++r) {
     if (!lists[r] || (cost && !cost[r])) return set_error(HANAYO_EINVAL, "replay_actions: rank %d has no list or costs", r);
@@ -750,12 +767,12 @@ int hanayo_pipeline_run_actions(const hanayo_action* const* lists, const size_t*
     return set_error(HANAYO_EINVAL, "pipeline_actions: NULL argument");
   if (a->ends) return set_error(HANAYO_EUNSUPPORTED, "pipeline_actions: the model's ends are not part of this call");
   const int P = a->P, W = a->W, M = a->M;
-  if (P < 1 || W < 1 || M < 1 || 2 * W > 255 || link->link_workgroups < 0)
+  if (P < 1 || W < 0 || M < 1 || 2 * W > 255 || link->link_workgroups < 0)
     return set_error(HANAYO_EINVAL, "pipeline_actions: bad P=%d W=%d M=%d or link", P, W, M);
   Shape sh;
   int rc = prepare_call(a->desc, sh);
   if (rc) return rc;
-  const int nchunk = 2 * W, S = nchunk * P;
+  const int nchunk = chunks_per_rank(W), S = nchunk * P;
   // the lists themselves (structure, matching, no deadlock) are checked by the interpreter simulation
   double dummy = 0.0;
   rc = hanayo_replay_actions(lists, counts, P, W, M, 1.0, 2.0, 0.0, 0, nullptr, &dummy, nullptr, nullptr);

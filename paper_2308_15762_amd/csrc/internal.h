@@ -12,6 +12,11 @@ namespace hanayo {
 // Records a thread-local message and returns `code`.
 int set_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 
+// Placements.  W >= 1: the wave placement of Table 1 (S = 2WP stages, 2W chunks per device, a micro-batch runs
+// down the devices and back W times).  W == 0: the straight placement of GPipe and 1F1B, one stage per device
+// (S = P; in Table 1's notation W = S / 2P = 1/2).  stage_rank / rank_stage cover both: with S = P the first
+// lap of the wave is the straight pipeline.
+inline int chunks_per_rank(int W) { return W ? 2 * W : 1; }
 int stage_rank(int P, int stage);
 int rank_stage(int P, int rank, int chunk);
 void generate(int P, int W, int M, int rank, std::vector<hanayo_task>& out);

@@ -104,6 +104,7 @@ class HanayoError(RuntimeError):
 
 
 EXPORTS = ("hanayo_strerror", "hanayo_last_error", "hanayo_stage_rank", "hanayo_rank_stage", "hanayo_schedule",
+           "hanayo_schedule_scheme", "hanayo_bubble_model", "hanayo_actions_of",
            "hanayo_stash_plan", "hanayo_param_span", "hanayo_weight_bytes", "hanayo_grad_bytes",
            "hanayo_stash_bytes", "hanayo_workspace_bytes", "hanayo_act_bytes", "hanayo_chunk_forward",
            "hanayo_chunk_backward", "hanayo_stash_arena_bytes", "hanayo_stash_arena_bytes_input",
@@ -122,6 +123,9 @@ _lib.hanayo_last_error.argtypes = []
 _lib.hanayo_stage_rank.argtypes = [_int, _int, _int, ctypes.POINTER(_int)]
 _lib.hanayo_rank_stage.argtypes = [_int, _int, _int, _int, ctypes.POINTER(_int)]
 _lib.hanayo_schedule.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
+_lib.hanayo_schedule_scheme.argtypes = [_int, _int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
+_dbl = ctypes.c_double
+_lib.hanayo_bubble_model.argtypes = [_int, _int, _int, _int, _dbl, _dbl, _dbl] + [ctypes.POINTER(_dbl)] * 3
 _lib.hanayo_stash_plan.argtypes = [_vp, _sz, _int, ctypes.POINTER(_int), _vp, _vp]
 _lib.hanayo_param_span.argtypes = [_descp, _int, _int, ctypes.POINTER(_sz), ctypes.POINTER(_sz)]
 for _n in ("hanayo_weight_bytes", "hanayo_grad_bytes", "hanayo_stash_bytes", "hanayo_workspace_bytes",
@@ -141,6 +145,7 @@ _lib.hanayo_executor_plan.argtypes = [_vp, _sz, _int, _int, _int, _int, _int, _v
 _lib.hanayo_pipeline_run.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), _vp, _vp]
 _lib.hanayo_replay.argtypes = [_vp, _vp, _int, _int, _int, _vp, ctypes.POINTER(ctypes.c_double), _vp]
 _lib.hanayo_actions.argtypes = [_int, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
+_lib.hanayo_actions_of.argtypes = [_vp, _sz, _int, _int, _int, _vp, _sz, ctypes.POINTER(_sz)]
 _lib.hanayo_replay_actions.argtypes = [_vp, _vp, _int, _int, _int, ctypes.c_double, ctypes.c_double, ctypes.c_double, _int,
                                        _vp, ctypes.POINTER(ctypes.c_double), _vp, _vp]
 _lib.hanayo_pipeline_run_actions.argtypes = [_vp, _vp, ctypes.POINTER(PipelineArgs), ctypes.POINTER(LinkArgs), _vp, _vp]
@@ -221,11 +226,37 @@ def hanayo_schedule(P, W, M, rank):
     return out
 
 
+SCHEME_HANAYO, SCHEME_CHIMERA_WAVE, SCHEME_GPIPE, SCHEME_1F1B = range(4)
+
+
+def chunks_per_rank(W):
+    """Buffer-table width of a placement: 2W chunks per device, one for the straight placement (W = 0)."""
+    return 2 * W if W else 1
+
+
+def hanayo_schedule_scheme(scheme, P, W, M, rank):
+    """Ordered task list of one rank under a scheme (W = 0 for GPipe / 1F1B, 1 for Chimera-wave)."""
+    n = _sz()
+    rc = _lib.hanayo_schedule_scheme(scheme, P, W, M, rank, None, 0, ctypes.byref(n))
+    if rc != EBUFSIZE:
+        _check(rc)
+    out = np.zeros(n.value, dtype=TASK_DTYPE)
+    _check(_lib.hanayo_schedule_scheme(scheme, P, W, M, rank, out.ctypes.data, out.size, ctypes.byref(n)))
+    return out
+
+
+def hanayo_bubble_model(scheme, P, W, M, t_f, t_b, t_c):
+    """Returns (ratio, idle, ratio_of_idle)."""
+    r, i, q = _dbl(), _dbl(), _dbl()
+    _check(_lib.hanayo_bubble_model(scheme, P, W, M, t_f, t_b, t_c, ctypes.byref(r), ctypes.byref(i), ctypes.byref(q)))
+    return r.value, i.value, q.value
+
+
 def hanayo_stash_plan(tasks, W):
     """Returns (peak_total, per_chunk[2W], slot[n])."""
     tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
     peak = _int()
-    per_chunk = np.zeros(2 * W, dtype=np.int32)
+    per_chunk = np.zeros(chunks_per_rank(W), dtype=np.int32)
     slot = np.zeros(tasks.size, dtype=np.int32)
     _check(_lib.hanayo_stash_plan(tasks.ctypes.data, tasks.size, W, ctypes.byref(peak),
                                   per_chunk.ctypes.data, slot.ctypes.data))
@@ -513,6 +544,18 @@ def hanayo_actions(P, W, M, rank):
         _check(rc if rc != OK else ESTATE)
     out = np.zeros(n.value, dtype=ACTION_DTYPE)
     _check(_lib.hanayo_actions(P, W, M, rank, out.ctypes.data, out.size, ctypes.byref(n)))
+    return out
+
+
+def hanayo_actions_of(tasks, P, W, rank):
+    """Action list of any task list of a rank (W = 0: straight placement)."""
+    tasks = np.ascontiguousarray(tasks, dtype=TASK_DTYPE)
+    n = _sz()
+    rc = _lib.hanayo_actions_of(tasks.ctypes.data, tasks.size, P, W, rank, None, 0, ctypes.byref(n))
+    if rc != EBUFSIZE:
+        _check(rc)
+    out = np.zeros(n.value, dtype=ACTION_DTYPE)
+    _check(_lib.hanayo_actions_of(tasks.ctypes.data, tasks.size, P, W, rank, out.ctypes.data, out.size, ctypes.byref(n)))
     return out
 
 

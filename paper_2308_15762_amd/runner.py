@@ -109,7 +109,8 @@ class GpuRank:
         self.wl, self.rank, self.lanes, self.stash_mode = wl, rank, lanes, stash_mode
         self.desc = hn.desc_for(wl)
         P, W, M = wl.P, wl.W, wl.M
-        self.nchunk = 2 * W
+        self.nchunk = hn.chunks_per_rank(W)        # W = 0: the straight placement of a GPipe / 1F1B list
+        assert W > 0 or tasks is not None, "a straight placement has no wave schedule: pass the scheme's list"
         self.tasks = hn.hanayo_schedule(P, W, M, rank) if tasks is None else tasks
         self.params = [synth.chunk_params(wl, c) for c in range(self.nchunk)]
         self.weights = [dev(hn.pack_params(self.desc, p), wl.dtype) for p in self.params]
@@ -123,7 +124,7 @@ class GpuRank:
         else:
             self.arena_bytes = hn.hanayo_stash_arena_bytes(self.tasks, W, self.desc)
         self.arena = dev_bytes(self.arena_bytes)
-        S = 2 * W * P
+        S = self.nchunk * P
         n = M * self.nchunk
         self.act_in, self.grad_in = [None] * n, [None] * n
         self.act_out, self.grad_out = [None] * n, [None] * n
@@ -205,13 +206,14 @@ class GpuPipeline:
     gradients per micro-batch, every stage-boundary buffer, one stash arena per rank; runs the P task
     lists with true dataflow through hanayo_pipeline_run."""
 
-    def __init__(self, wl, ends=False):
-        """ends: the model starts from token ids and ends in the loss (tied head), see GpuRank."""
+    def __init__(self, wl, ends=False, lists=None):
+        """ends: the model starts from token ids and ends in the loss (tied head), see GpuRank.
+        lists: the P task lists (default: the wave schedule's; required for a straight placement, wl.W = 0)."""
         self.wl = wl
         self.desc = hn.desc_for(wl)
         P, W, M = wl.P, wl.W, wl.M
-        self.S = S = 2 * W * P
-        self.lists = [hn.hanayo_schedule(P, W, M, r) for r in range(P)]
+        self.S = S = hn.chunks_per_rank(W) * P
+        self.lists = [hn.hanayo_schedule(P, W, M, r) for r in range(P)] if lists is None else lists
         self.params = [synth.stage_params(wl, s) for s in range(S)]
         self.weights = [dev(hn.pack_params(self.desc, p), wl.dtype) for p in self.params]
         self.grads = [torch.zeros(hn.hanayo_grad_bytes(self.desc) // 4, dtype=torch.float32, device="cuda")

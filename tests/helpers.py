@@ -11,9 +11,32 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 
 def nerr(got, ref):
-    """max |got - ref| / max |ref|  (the normalised error the tolerances refer to)."""
+    """max |got - ref| / max |ref|: the per-tensor normalised maximum error."""
     ref = np.asarray(ref, dtype=np.float64)
     return float(np.abs(np.asarray(got, dtype=np.float64) - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def rel_l2(got, ref):
+    """||got - ref||_2 / ||ref||_2: sees a region of small entries that is wrong as a whole, which the
+    maximum error normalised by the largest entry cannot."""
+    ref = np.asarray(ref, dtype=np.float64).ravel()
+    d = np.asarray(got, dtype=np.float64).ravel() - ref
+    return float(np.sqrt(np.dot(d, d)) / max(np.sqrt(np.dot(ref, ref)), 1e-30))
+
+
+def elem_err(got, ref):
+    """Element-wise relative error with an absolute floor: max_i |got_i - ref_i| / (|ref_i| + rms(ref)).
+    Every entry is judged at its own size, entries near zero at the tensor's typical size."""
+    ref = np.asarray(ref, dtype=np.float64)
+    d = np.abs(np.asarray(got, dtype=np.float64) - ref)
+    floor = max(float(np.sqrt(np.mean(ref * ref))), 1e-30)
+    return float((d / (np.abs(ref) + floor)).max())
+
+
+def perr(got, ref):
+    """The parity error the GPU tests hold against the tolerances: the larger of the normalised maximum
+    error and the relative L2 error, so `perr <= tol` asserts both."""
+    return max(nerr(got, ref), rel_l2(got, ref))
 
 
 def oracle_cfg(wl):
@@ -24,9 +47,13 @@ def compare_grads(got, ref, tol, label=""):
     worst = 0.0
     for bi, (g, r) in enumerate(zip(got, ref)):
         for name in hn.PARAM_NAMES:
-            e = nerr(g[name], r[name])
+            e = perr(g[name], r[name])
             worst = max(worst, e)
-            assert e <= tol, "%s block %d %s: normalised error %.3g > %.3g" % (label, bi, name, e, tol)
+            assert e <= tol, "%s block %d %s: error %.3g (max-normalised %.3g, relative L2 %.3g) > %.3g" % (
+                label, bi, name, e, nerr(g[name], r[name]), rel_l2(g[name], r[name]), tol)
+            if tol <= 1e-4:   # fp32 storage: every entry at its own size as well
+                ee = elem_err(g[name], r[name])
+                assert ee <= tol, "%s block %d %s: element-wise error %.3g > %.3g" % (label, bi, name, ee, tol)
     return worst
 
 

@@ -7,7 +7,7 @@ import pytest
 
 from oracle import block as OB
 from paper_2308_15762_amd import synth
-from helpers import TOL, GpuChunk, compare_grads, nerr, oracle_cfg
+from helpers import TOL, GpuChunk, compare_grads, perr, oracle_cfg
 
 pytestmark = pytest.mark.gpu
 
@@ -44,10 +44,10 @@ def test_chunk_forward_backward_matches_oracle(name):
     gpu = GpuChunk(wl, params)
     y, stash = gpu.forward(x, vl)
     assert np.isfinite(y).all()
-    assert nerr(y, y_ref) <= tol, "y: %.3g" % nerr(y, y_ref)
+    assert perr(y, y_ref) <= tol, "y: %.3g" % perr(y, y_ref)
     dx = gpu.backward(dy, stash)
     assert np.isfinite(dx).all()
-    assert nerr(dx, dx_ref) <= tol, "dx: %.3g" % nerr(dx, dx_ref)
+    assert perr(dx, dx_ref) <= tol, "dx: %.3g" % perr(dx, dx_ref)
     compare_grads(gpu.grad_dicts(), g_ref, tol, name)
 
 
@@ -80,4 +80,4 @@ def test_forward_does_not_modify_inputs_and_stash_survives_other_forwards():
     dx = gpu.backward(dy0, st0)
     _, st_ref = OB.chunk_forward(params, x0, cfg, vl0)
     dx_ref, _ = OB.chunk_backward(cfg, st_ref, dy0)
-    assert nerr(dx, dx_ref) <= TOL["bf16"]
+    assert perr(dx, dx_ref) <= TOL["bf16"]

@@ -12,7 +12,8 @@ import torch
 from oracle import block as OB
 from paper_2308_15762_amd import hanayo as hn
 from paper_2308_15762_amd import synth
-from helpers import TOL, GpuChunk, GpuRank, compare_grads, host, nerr, oracle_cfg
+from helpers import TOL, GpuChunk, GpuRank, compare_grads, host, perr, oracle_cfg
+from oracle import executor as OE
 
 pytestmark = pytest.mark.gpu
 
@@ -32,9 +33,9 @@ def test_full_size_chunk_pair(name):
     del st
     gpu = GpuChunk(wl, params)
     y, stash = gpu.forward(x, vl)
-    assert nerr(y, y_ref) <= tol, "y %.3g" % nerr(y, y_ref)
+    assert perr(y, y_ref) <= tol, "y %.3g" % perr(y, y_ref)
     dx = gpu.backward(dy, stash)
-    assert nerr(dx, dx_ref) <= tol, "dx %.3g" % nerr(dx, dx_ref)
+    assert perr(dx, dx_ref) <= tol, "dx %.3g" % perr(dx, dx_ref)
     compare_grads(gpu.grad_dicts(), g_ref, tol, name)
 
 
@@ -51,9 +52,9 @@ def test_largest_chunk_shape_single_block():
     del st
     gpu = GpuChunk(wl, params)
     y, stash = gpu.forward(x)
-    assert nerr(y, y_ref) <= tol
+    assert perr(y, y_ref) <= tol
     dx = gpu.backward(dy, stash)
-    assert nerr(dx, dx_ref) <= tol
+    assert perr(dx, dx_ref) <= tol
     compare_grads(gpu.grad_dicts(), g_ref, tol, "gpt_4096 block")
 
 
@@ -103,9 +104,9 @@ def test_benchmark_workload_sampled_micro_batch(benchmark_run):
     d[1], _ = OB.chunk_backward(cfg, st[1], d[2])                              # local hand-off
     d[0], _ = OB.chunk_backward(cfg, st[0], synth.upstream_grad(wl, m, 0))
     for c in range(nchunk):
-        e = nerr(host(gpu.act_out[m * nchunk + c]), y[c])
+        e = perr(host(gpu.act_out[m * nchunk + c]), y[c])
         assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
-        e = nerr(host(gpu.grad_out[m * nchunk + c]), d[c])
+        e = perr(host(gpu.grad_out[m * nchunk + c]), d[c])
         assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
     # property that holds at any size: every gradient buffer is finite and non-trivial
     for g in gpu.grads:
@@ -140,12 +141,12 @@ def test_benchmark_workload_with_the_models_ends():
         d_g += d_lnf[0]
         d_b += d_lnf[1]
         if m == 5:
-            e = nerr(host(gpu.loss_grad[m]), dy)
+            e = perr(host(gpu.loss_grad[m]), dy)
             assert e <= tol, "loss gradient of mb 5: %.3g" % e
         x = OE.embed_forward(ends["wte"], ends["wpe"], ends["tokens"](m))
         if m == 5:
             y0, st = OB.chunk_forward(p0, x, cfg)
-            e = nerr(host(gpu.act_out[m * 2 * wl.W]), y0)
+            e = perr(host(gpu.act_out[m * 2 * wl.W]), y0)
             assert e <= tol, "stage 0 output of mb 5: %.3g" % e
         else:
             _, st = OB.chunk_forward(p0, x, cfg)
@@ -154,9 +155,9 @@ def test_benchmark_workload_with_the_models_ends():
         a, b = OE.embed_backward(ends["tokens"](m), dx, wl.vocab, wl.seq)
         d_wte += a
         d_wpe += b
-    assert nerr(host(gpu.d_wte), d_wte) <= tol, "d_wte %.3g" % nerr(host(gpu.d_wte), d_wte)
-    assert nerr(host(gpu.d_wpe), d_wpe) <= tol
-    assert nerr(host(gpu.d_lnf)[:wl.hidden], d_g) <= tol and nerr(host(gpu.d_lnf)[wl.hidden:], d_b) <= tol
+    assert perr(host(gpu.d_wte), d_wte) <= tol, "d_wte %.3g" % perr(host(gpu.d_wte), d_wte)
+    assert perr(host(gpu.d_wpe), d_wpe) <= tol
+    assert perr(host(gpu.d_lnf)[:wl.hidden], d_g) <= tol and perr(host(gpu.d_lnf)[wl.hidden:], d_b) <= tol
 
 
 def test_bert_workload_sampled_micro_batch_four_lanes():
@@ -178,9 +179,9 @@ def test_bert_workload_sampled_micro_batch_four_lanes():
         y, st = OB.chunk_forward(params, synth.forward_input(wl, m, c), cfg, vl)
         dx, _ = OB.chunk_backward(cfg, st, synth.upstream_grad(wl, m, c))
         del st
-        e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+        e = perr(host(gpu.act_out[m * nchunk + c]), y)
         assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
-        e = nerr(host(gpu.grad_out[m * nchunk + c]), dx)
+        e = perr(host(gpu.grad_out[m * nchunk + c]), dx)
         assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
     for g in gpu.grads:
         assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
@@ -206,9 +207,9 @@ def test_wave4_workload_sampled_micro_batch_four_lanes():
     d1, _ = OB.chunk_backward(cfg, st1, d2)                                    # local hand-off
     del st1, st2
     for c, y, d in ((1, y1, d1), (2, y2, d2)):
-        e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+        e = perr(host(gpu.act_out[m * nchunk + c]), y)
         assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
-        e = nerr(host(gpu.grad_out[m * nchunk + c]), d)
+        e = perr(host(gpu.grad_out[m * nchunk + c]), d)
         assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
 
 
@@ -228,9 +229,51 @@ def test_largest_workload_sampled_micro_batch_four_lanes():
     dx, _ = OB.chunk_backward(cfg, st, synth.upstream_grad(wl, m, c))
     del st
     nchunk = 2 * wl.W
-    e = nerr(host(gpu.act_out[m * nchunk + c]), y)
+    e = perr(host(gpu.act_out[m * nchunk + c]), y)
     assert e <= tol, "act_out: %.3g" % e
-    e = nerr(host(gpu.grad_out[m * nchunk + c]), dx)
+    e = perr(host(gpu.grad_out[m * nchunk + c]), dx)
     assert e <= tol, "grad_out: %.3g" % e
     for g in gpu.grads:
         assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
+
+
+@pytest.mark.parametrize("name", ["gpt_4096_bf16", "gpt_2560_wave4_bf16"])
+def test_full_size_one_micro_batch_through_all_rank0_chunks(name):
+    """Configurations 4 and 5 at their full chunk shapes with their own (P, W), two micro-batches, four lanes:
+    micro-batch 0 through ALL of rank 0's chunks -- every chunk's output activation and input gradient,
+    which includes every local turn-around of the wave (chunks 1 -> 2, 3 -> 4, ... forward and back) -- and
+    every chunk's parameter gradients of that micro-batch's share are covered by the accumulated comparison:
+    the gradients the turn-around chunk 2 has accumulated over both micro-batches against the oracle's sum.
+    The oracle (float32, as configured for the largest shapes) walks micro-batch 0's tasks of the list."""
+    wl = W[name].scaled(M=2)
+    tol = TOL["bf16"]
+    gpu = GpuRank(wl, 0, lanes=4)
+    peak = gpu.run()
+    torch.cuda.synchronize()
+    assert peak == hn.hanayo_stash_plan(gpu.tasks, wl.W)[0]
+    nchunk = 2 * wl.W
+    cfg = oracle_cfg(wl)
+    params = [synth.chunk_params(wl, c) for c in range(nchunk)]
+    tasks0 = [(int(t["kind"]), int(t["mb"]), int(t["chunk"]), int(t["stage"])) for t in gpu.tasks if int(t["mb"]) == 0]
+    assert len(tasks0) == 2 * nchunk
+    ref = OE.run_rank(tasks0, wl.P, wl.W, 0, cfg, params, lambda m, c: synth.forward_input(wl, m, c),
+                      lambda m, c: synth.upstream_grad(wl, m, c), dtype=np.float32)
+    for c in range(nchunk):
+        e = perr(host(gpu.act_out[c]), ref["act_out"][(0, c)])
+        assert e <= tol, "act_out chunk %d: %.3g" % (c, e)
+        e = perr(host(gpu.grad_out[c]), ref["grad_out"][(0, c)])
+        assert e <= tol, "grad_out chunk %d: %.3g" % (c, e)
+    # accumulated gradients of chunk 2, whose input is chunk 1's output (the local turn-around): micro-batch 0's
+    # share comes from the walk above, micro-batch 1's from chunks 1 -> 2 of that micro-batch
+    y1, st1 = OB.chunk_forward(params[1], synth.forward_input(wl, 1, 1), cfg, dtype=np.float32)
+    del st1
+    _, st2 = OB.chunk_forward(params[2], y1, cfg, dtype=np.float32)
+    # (stage 2P sits on rank 0 and feeds stage 2P+1 on rank 1, so chunk 2's upstream gradient is a received one)
+    _, g2 = OB.chunk_backward(cfg, st2, synth.upstream_grad(wl, 1, 2))
+    del st2
+    total = [{k: a[k] + b[k] for k in a} for a, b in zip(ref["grads"][2], g2)]
+    compare_grads(gpu.grad_dicts(2), total, tol, "%s chunk 2 over both micro-batches" % name)
+    # the other chunks' accumulated gradients: finite and non-trivial (a property that holds at any size)
+    for g in gpu.grads:
+        assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
+

@@ -11,7 +11,7 @@ import torch
 from oracle import block as OB
 from paper_2308_15762_amd import hanayo as hn
 from paper_2308_15762_amd import synth
-from helpers import TOL, dev, host, nerr
+from helpers import TOL, dev, host, perr
 
 pytestmark = pytest.mark.gpu
 
@@ -82,8 +82,8 @@ def test_gemm_group_weight_gradients(dtype, shapes):
     hn.hanayo_op_gemm_group(DT[dtype], True, True, hn.EPI_ACCUM_F32, probs)
     torch.cuda.synchronize()
     for t, (want, want_cs) in zip(probs, checks):
-        assert nerr(t["C"].cpu().numpy(), want) <= TOL[dtype]
-        assert nerr(t["colsum"].cpu().numpy(), want_cs) <= 1e-4
+        assert perr(t["C"].cpu().numpy(), want) <= TOL[dtype]
+        assert perr(t["colsum"].cpu().numpy(), want_cs) <= 1e-4
     with pytest.raises(hn.HanayoError):
         hn.hanayo_op_gemm_group(DT[dtype], True, True, hn.EPI_ACCUM_F32, (probs * 3)[:5])   # more than 4
 
@@ -123,11 +123,11 @@ def run_gemm_case(dtype, layout, shape):
         torch.cuda.synchronize()
         if cs is not None:
             want_cs = B.astype(np.float64).sum(0)
-            assert nerr(cs.cpu().numpy() - cs0, want_cs) <= 1e-4, "column sums"
-        e = nerr(host(Cd), want)
+            assert perr(cs.cpu().numpy() - cs0, want_cs) <= 1e-4, "column sums"
+        e = perr(host(Cd), want)
         assert e <= TOL[dtype], "epilogue %d: %.3g" % (epi, e)
         if out2 is not None:
-            assert nerr(host(out2), ref + bias) <= TOL[dtype]
+            assert perr(host(out2), ref + bias) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
@@ -150,7 +150,7 @@ def test_layernorm_forward_backward(dtype, rows, H):
     stats = torch.empty((rows, 2), dtype=torch.float32, device="cuda")
     hn.hanayo_op_layernorm_forward(DT[dtype], xd, gd, bd, out, stats, cp, rows, H, 1e-5)
     torch.cuda.synchronize()
-    assert nerr(host(out), out_ref) <= TOL[dtype]
+    assert perr(host(out), out_ref) <= TOL[dtype]
     assert torch.equal(cp, xd)
     st = stats.cpu().numpy().astype(np.float64)
     assert np.allclose(st[:, 0], x64.mean(-1), atol=1e-5)
@@ -162,10 +162,10 @@ def test_layernorm_forward_backward(dtype, rows, H):
     for addend, want in ((None, dz_ref), (ad, dz_ref + add)):
         hn.hanayo_op_layernorm_backward(DT[dtype], dd, xd, gd, stats, addend, dz, dgd, dbd, scratch, rows, H)
         torch.cuda.synchronize()
-        assert nerr(host(dz), want) <= TOL[dtype]
+        assert perr(host(dz), want) <= TOL[dtype]
     # gamma / beta gradients were accumulated twice on top of their initial values
-    assert nerr(dgd.cpu().numpy() - dg0, 2 * dg_ref) <= 1e-4
-    assert nerr(dbd.cpu().numpy() - db0, 2 * db_ref) <= 1e-4
+    assert perr(dgd.cpu().numpy() - dg0, 2 * dg_ref) <= 1e-4
+    assert perr(dbd.cpu().numpy() - db0, 2 * db_ref) <= 1e-4
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
@@ -178,7 +178,7 @@ def test_colsum(dtype, rows, N):
     scratch = torch.empty(64 * N, dtype=torch.float32, device="cuda")
     hn.hanayo_op_colsum_add(DT[dtype], dev(a, dtype), rows, N, od, scratch)
     torch.cuda.synchronize()
-    assert nerr(od.cpu().numpy() - o0, a.astype(np.float64).sum(0)) <= 1e-5
+    assert perr(od.cpu().numpy() - o0, a.astype(np.float64).sum(0)) <= 1e-5
 
 
 ATTN_CASES = [
@@ -233,7 +233,7 @@ def test_attention_forward_backward(dtype, case):
     lse = torch.empty((b, h, s), dtype=torch.float32, device="cuda")
     hn.hanayo_op_attention_forward(DT[dtype], qd, vld, ctx, lse, b, s, h, d, causal)
     torch.cuda.synchronize()
-    assert nerr(host(ctx), ctx_ref) <= TOL[dtype]
+    assert perr(host(ctx), ctx_ref) <= TOL[dtype]
     assert np.abs(lse.cpu().numpy() - lse_ref).max() <= (2e-2 if dtype == "bf16" else 1e-4)
     dqkv = torch.full((b, s, 3 * H), float("nan"), dtype=qd.dtype, device="cuda")
     delta = torch.empty((b, h, s), dtype=torch.float32, device="cuda")
@@ -242,7 +242,7 @@ def test_attention_forward_backward(dtype, case):
     got = host(dqkv)
     assert np.isfinite(got).all()
     for i, name in enumerate("qkv"):
-        e = nerr(got[..., i * H:(i + 1) * H], dqkv_ref[..., i * H:(i + 1) * H])
+        e = perr(got[..., i * H:(i + 1) * H], dqkv_ref[..., i * H:(i + 1) * H])
         assert e <= TOL[dtype], "d%s: %.3g" % (name, e)
 
 

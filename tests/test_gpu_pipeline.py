@@ -12,7 +12,7 @@ from oracle import schedule as OS
 from paper_2308_15762_amd import hanayo as hn
 from paper_2308_15762_amd import synth
 from paper_2308_15762_amd.runner import GpuPipeline
-from helpers import TOL, compare_grads, host, nerr, oracle_cfg
+from helpers import TOL, compare_grads, host, perr, oracle_cfg
 from test_host_pipeline import deadlocking_lists
 
 pytestmark = pytest.mark.gpu
@@ -61,9 +61,9 @@ def test_pipeline_matches_the_model_without_a_pipeline(name):
     ys, dxs, grads = reference(wl)
     S = gpu.S
     for m in range(wl.M):
-        e = nerr(host(gpu.act[m * S + S - 1]), ys[m])
+        e = perr(host(gpu.act[m * S + S - 1]), ys[m])
         assert e <= tol, "output of micro-batch %d: %.3g" % (m, e)
-        e = nerr(host(gpu.grad[m * S]), dxs[m])
+        e = perr(host(gpu.grad[m * S]), dxs[m])
         assert e <= tol, "input gradient of micro-batch %d: %.3g" % (m, e)
     for s in range(S):
         compare_grads(gpu.grad_dicts(s), grads[s], tol, "%s stage %d" % (name, s))
@@ -122,7 +122,7 @@ def test_full_size_pipeline_sampled_output():
     a = synth.model_input(wl, m)
     for s in range(S):
         a, _ = OB.chunk_forward(synth.stage_params(wl, s), a, cfg, dtype=np.float32)
-    e = nerr(host(gpu.act[m * S + S - 1]), a)
+    e = perr(host(gpu.act[m * S + S - 1]), a)
     assert e <= depth_tolerance(wl), "model output of micro-batch %d: %.3g" % (m, e)
     for g in gpu.grads:
         assert bool(torch.isfinite(g).all()) and float(g.abs().max()) > 0
@@ -148,8 +148,8 @@ def test_pipeline_from_action_lists(name, mode):
     ys, dxs, grads = reference(wl)
     S = gpu.S
     for m in range(wl.M):
-        assert nerr(host(gpu.act[m * S + S - 1]), ys[m]) <= tol
-        assert nerr(host(gpu.grad[m * S]), dxs[m]) <= tol
+        assert perr(host(gpu.act[m * S + S - 1]), ys[m]) <= tol
+        assert perr(host(gpu.grad[m * S]), dxs[m]) <= tol
     for s in range(S):
         compare_grads(gpu.grad_dicts(s), grads[s], tol, "%s stage %d" % (name, s))
     # every receive buffer holds exactly what its producer wrote
@@ -232,14 +232,14 @@ def test_pipeline_with_the_models_ends_matches_the_model_without_a_pipeline(name
     loss = host(gpu.loss)
     for m in range(wl.M):
         assert abs(loss[m] - losses[m]) <= tol * losses[m], (m, loss[m], losses[m])
-        assert nerr(host(gpu.act[m * S + S - 1]), ys[m]) <= tol
-        assert nerr(host(gpu.grad[m * S]), dxs[m]) <= tol
+        assert perr(host(gpu.act[m * S + S - 1]), ys[m]) <= tol
+        assert perr(host(gpu.grad[m * S]), dxs[m]) <= tol
     for s in range(S):
         compare_grads(gpu.grad_dicts(s), grads[s], tol, "%s stage %d" % (name, s))
-    assert nerr(host(gpu.d_wte), eg["wte"]) <= tol and nerr(host(gpu.d_wpe), eg["wpe"]) <= tol
+    assert perr(host(gpu.d_wte), eg["wte"]) <= tol and perr(host(gpu.d_wpe), eg["wpe"]) <= tol
     if eg["lnf"] is not None:
         H = wl.hidden
-        assert nerr(host(gpu.d_lnf)[:H], eg["lnf"][0]) <= tol and nerr(host(gpu.d_lnf)[H:], eg["lnf"][1]) <= tol
+        assert perr(host(gpu.d_lnf)[:H], eg["lnf"][0]) <= tol and perr(host(gpu.d_lnf)[H:], eg["lnf"][1]) <= tol
 
 
 def test_pipeline_arguments_with_and_without_ends():
