@@ -70,7 +70,7 @@ def oracle_ends(wl, tied=True):
 def oracle_rank(wl, rank, tasks, ends=None):
     """The oracle's execution of the same list on the same seeded inputs."""
     from oracle import executor as OE
-    params = [synth.chunk_params(wl, c) for c in range(2 * wl.W)]
+    params = [synth.chunk_params(wl, c) for c in range(hn.chunks_per_rank(wl.W))]
     vl = (lambda m: synth.valid_lengths(wl, m)) if wl.valid_len_range is not None else None
     lst = [(int(t["kind"]), int(t["mb"]), int(t["chunk"]), int(t["stage"])) for t in tasks]
     return OE.run_rank(lst, wl.P, wl.W, rank, oracle_cfg(wl), params,
