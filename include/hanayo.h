@@ -550,9 +550,10 @@ enum {
  * The forward linears use (a_t, b_t) = (0, 1), the input gradients (0, 0), the
  * weight gradients (1, 1) with HANAYO_EPI_ACCUM_F32.
  * colsum (device fp32 [N], may be NULL; needs b_t = 1 and ldb = N): colsum[n] += sum over k of B[k][n],
- * the bias gradient that belongs to a weight-gradient GEMM; the bf16 MFMA kernels fold it into the
- * GEMM (fp32 atomics, so the summation order is not fixed), the others run a column-sum pass using
- * colsum_scratch (device, at least 64 * N floats).
+ * the bias gradient that belongs to a weight-gradient GEMM; the tiled bf16 MFMA kernels fold it into the
+ * GEMM (the workgroups of the first tile row sum the B tiles they load anyway), the others run a
+ * column-sum pass using colsum_scratch (device, at least 64 * N floats).  No atomics either way: the
+ * sums are added in a fixed order and repeat bit for bit.
  */
 int hanayo_op_gemm(int dtype, const void* A, const void* B, void* C, int M, int N, int K, int lda, int ldb, int ldc,
                    int a_t, int b_t, int epilogue, const void* bias, const void* aux, void* aux_out, float* colsum,

@@ -274,15 +274,15 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
       for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
   };
 
-  // Column sums of B (bias gradient): the K tiles are dealt round-robin to the workgroups of a
-  // column of the grid, each thread adds 4 columns x (32 / kColRowGroups) rows of a tile it owns.
+  // Column sums of B (bias gradient): the workgroup of tile row 0 sums every K tile of its tile column from
+  // the B tiles that pass through LDS anyway (each thread adds 4 columns x (BK / kColRowGroups) rows per
+  // tile).  One workgroup per column and a fixed order of additions: the sums are the same bits every run.
   constexpr int kColGroups = BN / 4, kColRowGroups = NW * 64 / kColGroups, kColRows = BK / kColRowGroups;
   float csum[4] = {0.f, 0.f, 0.f, 0.f};
-  int colsum_next = p.colsum ? tile_m : 0x7fffffff;  // next K tile this workgroup sums
+  const bool sums_columns = B_T && p.colsum && tile_m == 0;
   auto colsum_tile = [&](int kt) {
     if constexpr (B_T) {
-      if (kt == colsum_next) {
-        colsum_next += tiles_m;
+      if (sums_columns) {
         const char* b_lds = smem + (kt % NSTAGE) * STAGE_BYTES + OpA::kBytes;
         const int c = (threadIdx.x % kColGroups) * 4, rg = threadIdx.x / kColGroups;
 #pragma unroll
@@ -490,7 +490,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   }
 
   if constexpr (B_T) {
-    if (p.colsum) {  // combine the row groups through LDS (the ring is idle now), one atomic per column
+    if (sums_columns) {  // combine the row groups through LDS (the ring is idle now); this workgroup alone owns the columns
       __syncthreads();
       float* red = reinterpret_cast<float*>(smem);
       const int c = (threadIdx.x % kColGroups) * 4, rg = threadIdx.x / kColGroups;
@@ -501,7 +501,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
         float t = 0.f;
 #pragma unroll
         for (int g = 0; g < kColRowGroups; ++g) t += red[g * BN + threadIdx.x];
-        atomicAdd(p.colsum + n0 + threadIdx.x, t);
+        p.colsum[n0 + threadIdx.x] += t;
       }
     }
   }

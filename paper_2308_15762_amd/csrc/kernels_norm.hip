@@ -202,19 +202,30 @@ __global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict_
   }
 }
 
-// out[c] += sum_r partial[r][c] for c in [0, n): a thread owns one column of a slab of 8 partial
-// rows and adds its sum with one atomic, so the reduction is spread over (n / 256) x (rows / 8)
-// workgroups instead of running down the rows in a few.  Columns >= split go to out1[c - split].
-// (fp32 atomics: the order in which the slabs are added is not fixed.)
-constexpr int kFinalizeRows = 8;
+// out[c] += sum_r partial[r][c] for c in [0, n), without atomics and in a fixed order: a workgroup owns 32
+// columns; its 8 row groups each run down every 8th partial row (32 lanes x 4 bytes = one 128-byte line per
+// row), the 8 group sums are added in order through LDS, and one thread per column adds the total to `out`.
+// Columns >= split go to out1[c - split].  The same bits every run.
+constexpr int kFinalizeCols = 32, kFinalizeGroups = 8;
 __global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n,
                                                        float* __restrict__ out0, float* __restrict__ out1, int split) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= n) return;
-  const int r0 = blockIdx.y * kFinalizeRows, r1 = min(rows, r0 + kFinalizeRows);
+  __shared__ float red[kFinalizeGroups][kFinalizeCols];
+  const int cl = threadIdx.x % kFinalizeCols, rg = threadIdx.x / kFinalizeCols;
+  const int c = blockIdx.x * kFinalizeCols + cl;
   float t = 0.f;
-  for (int r = r0; r < r1; ++r) t += partial[(size_t)r * ld + c];
-  atomicAdd(c < split ? out0 + c : out1 + (c - split), t);
+  if (c < n) {
+#pragma unroll 8
+    for (int r = rg; r < rows; r += kFinalizeGroups) t += partial[(size_t)r * ld + c];
+  }
+  red[rg][cl] = t;
+  __syncthreads();
+  if (rg == 0 && c < n) {
+    float total = 0.f;
+#pragma unroll
+    for (int g = 0; g < kFinalizeGroups; ++g) total += red[g][cl];
+    float* dst = c < split ? out0 + c : out1 + (c - split);
+    *dst += total;
+  }
 }
 
 // ------------------------------------------------------------------ column sums
@@ -281,8 +292,8 @@ int ln_backward_t(const void* dout, const void* x, const void* gamma, const floa
 #undef LAUNCH
   int rc = check_launch("ln_backward");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((2 * H + 255) / 256, (blocks + kFinalizeRows - 1) / kFinalizeRows), dim3(256), 0,
-                     stream, partial, blocks, 2 * H, 2 * H, dgamma, dbeta, H);
+  hipLaunchKernelGGL(finalize_kernel, dim3((2 * H + kFinalizeCols - 1) / kFinalizeCols), dim3(256), 0, stream, partial, blocks,
+                     2 * H, 2 * H, dgamma, dbeta, H);
   return check_launch("ln_backward finalize");
 }
 
@@ -295,8 +306,8 @@ int colsum_t(const void* in, int T_, int N, float* out, float* partial, hipStrea
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, stream, (const T*)in, T_, N, partial);
   int rc = check_launch("colsum");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((N + 255) / 256, (gy + kFinalizeRows - 1) / kFinalizeRows), dim3(256), 0, stream,
-                     partial, gy, N, N, out, out, N);
+  hipLaunchKernelGGL(finalize_kernel, dim3((N + kFinalizeCols - 1) / kFinalizeCols), dim3(256), 0, stream, partial, gy, N, N,
+                     out, out, N);
   return check_launch("colsum finalize");
 }
 

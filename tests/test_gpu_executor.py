@@ -89,6 +89,22 @@ def test_second_run_after_zeroing_grads_is_identical_enough():
         assert perr(b.cpu().numpy(), a.cpu().numpy()) <= 1e-5
 
 
+@pytest.mark.parametrize("lanes", [1, 4])
+def test_gradients_repeat_bit_for_bit(lanes):
+    """No kernel of the path adds with atomics (weight gradients start from the sums so far, bias gradients and
+    LayerNorm parameter gradients are reduced in a fixed order): two runs give identical bits everywhere."""
+    wl, rank = CASES["gpt_1024_sched_small"]
+    gpu = GpuRank(wl, rank, lanes=lanes)
+    snaps = []
+    for _ in range(2):
+        gpu.zero_grads()
+        gpu.run()
+        torch.cuda.synchronize()
+        snaps.append([g.clone() for g in gpu.grads] + [t.clone() for t in gpu.grad_out])
+    for a, b in zip(*snaps):
+        assert torch.equal(a, b)
+
+
 @pytest.mark.parametrize("name", ["gpt_1024_sched_small", "wave4_sched_small_rank3"])
 def test_lanes_do_not_change_results(name):
     """Boundary outputs are bit-identical whatever the lane count; gradients differ only by the
