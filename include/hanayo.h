@@ -597,7 +597,8 @@ int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
    the shape is a whole number of tiles; 7 / 8 / 9 = 256x256 (8 wavefronts) / 256x128 / 128x128 with two stages
    of 64-wide K tiles instead of four of 32 (K a multiple of 64); 3 = register-staged kernel only.
    HANAYO_EINVAL outside -1..9.
-   Process-wide, not thread-safe. */
+   The setting belongs to the calling thread: it changes what this thread's later hanayo_op_gemm*, hanayo_chunk_*
+   and executor calls dispatch, and nothing for other threads. */
 int hanayo_op_gemm_config(int config);
 
 /* out = LN(x) over the last dimension; stats[t] = (mean, rstd) as two floats;

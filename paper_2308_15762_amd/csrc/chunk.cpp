@@ -89,7 +89,7 @@ k::GemmArgs bwd_params_gemm(const Shape& sh, const void* x, const void* dy, floa
 namespace k {
 
 namespace {
-int g_gemm_config = -1;
+thread_local int g_gemm_config = -1;  // measurement knob: of the calling thread only
 thread_local double g_gemm_sharing = 0.0;
 }
 void set_gemm_config(int config) { g_gemm_config = config; }
@@ -98,7 +98,8 @@ void set_gemm_sharing(double share) { g_gemm_sharing = share < 0.0 ? 0.0 : (shar
 
 // Tile choice for the direct-to-LDS kernels by a cost model fitted to timings on MI355X: a launch
 // runs ceil(tiles / 256 CUs) rounds; a round costs one K tile's time per 32 columns of K (0.84 us for
-// 256 x 256 with 8 wavefronts, 0.52 us for 256 x 128, 0.295 us for 128 x 128 with two workgroups
+// 256 x 256 with 8 wavefronts, 0.59 us for 256 x 128 (one wavefront per SIMD; measured on a chip in its
+// sustained clock state with operands that do not stay in the Infinity Cache), 0.295 us for 128 x 128 with two workgroups
 // sharing a CU) plus an epilogue, and the launch a fixed start-up (pipeline fill grows with the
 // tile).  Large tiles reuse operands better; small ones waste less of the last round, which matters
 // less the more the chip is shared with other streams' kernels (set_gemm_sharing).  Returns -1 if no
@@ -111,7 +112,7 @@ int choose_dma_config(const GemmArgs* gs, int count) {
   }
   if (g_gemm_config != -1) return -1;
   static const struct { int config; double per_ktile, epilogue, start; } kTiles[] = {
-      {6, 0.79, 3.0, 7.0}, {2, 0.49, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
+      {6, 0.79, 3.0, 7.0}, {2, 0.59, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
   int best = -1;
   double best_cost = 0.0;
   for (const auto& t : kTiles) {

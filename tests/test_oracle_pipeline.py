@@ -199,3 +199,30 @@ def test_pipeline_with_ends_equals_monolithic(P, W, M):
     assert np.allclose(out["ends_grads"]["wte"], eg["wte"], rtol=1e-12, atol=1e-15)
     assert np.array_equal(out["ends_grads"]["wpe"], eg["wpe"])
     assert np.array_equal(out["ends_grads"]["lnf"][0], eg["lnf"][0])
+
+
+def test_rounding_error_grows_like_the_square_root_of_the_depth():
+    """Where the whole-pipeline GPU tests get their tolerance from.  A tensor that has passed through d blocks
+    whose stored outputs are rounded to bf16 carries d independent roundings of relative size 2^-9; through the
+    residual stream they add in quadrature.  Emulated in the oracle (every block's output rounded to bf16, against
+    the same model unrounded, float64): the normalised error at depth 32 is sqrt(8) times the error at depth 4
+    within a factor 1.6, far from the factor 8 of errors that add up linearly, and stays below the stated bf16
+    tolerance scaled by sqrt(depth / 4), the rule of tests/test_gpu_pipeline.py."""
+    import numpy as np
+    from oracle import block as OB
+    from paper_2308_15762_amd import synth
+    wl = synth.WORKLOADS["gpt_1024_bf16"].scaled(hidden=64, heads=2, ffn=256, seq=32, mb=2, n_blocks=1)
+    cfg = OB.BlockCfg(wl.hidden, wl.heads, wl.ffn, norm=wl.norm, causal=wl.causal)
+    x = synth.model_input(wl, 0)
+    exact, rounded = np.asarray(x, dtype=np.float64), np.asarray(x, dtype=np.float64)
+    err = {}
+    for depth in range(1, 33):
+        params = synth.stage_params(wl, depth - 1)
+        exact, _ = OB.chunk_forward(params, exact, cfg)
+        rounded, _ = OB.chunk_forward(params, rounded, cfg)
+        rounded = synth.bf16_round(rounded.astype(np.float32)).astype(np.float64)
+        err[depth] = float(np.abs(rounded - exact).max() / np.abs(exact).max())
+    growth = err[32] / err[4]
+    assert 8 ** 0.5 / 1.6 <= growth <= 8 ** 0.5 * 1.6, growth
+    for depth in (4, 8, 16, 32):
+        assert err[depth] <= 2e-2 * (depth / 4.0) ** 0.5
