@@ -595,8 +595,9 @@ int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
    kernel with 256x256 / 128x128 (8-deep load ring) / 256x128 / 128x128 (4-deep ring, two workgroups per
    CU) / 128x128 (8 wavefronts that split a K tile's MFMA steps) / 256x256 (8 wavefronts) tiles wherever
    the shape is a whole number of tiles; 7 / 8 / 9 = 256x256 (8 wavefronts) / 256x128 / 128x128 with two stages
-   of 64-wide K tiles instead of four of 32 (K a multiple of 64); 3 = register-staged kernel only.
-   HANAYO_EINVAL outside -1..9.
+   of 64-wide K tiles instead of four of 32 (K a multiple of 64); 10 / 11 = 256x128 / 128x128 with three such
+   stages; 3 = register-staged kernel only.
+   HANAYO_EINVAL outside -1..11.
    The setting belongs to the calling thread: it changes what this thread's later hanayo_op_gemm*, hanayo_chunk_*
    and executor calls dispatch, and nothing for other threads. */
 int hanayo_op_gemm_config(int config);

@@ -98,8 +98,8 @@ void set_gemm_sharing(double share) { g_gemm_sharing = share < 0.0 ? 0.0 : (shar
 
 // Tile choice for the direct-to-LDS kernels by a cost model fitted to timings on MI355X: a launch
 // runs ceil(tiles / 256 CUs) rounds; a round costs one K tile's time per 32 columns of K (0.84 us for
-// 256 x 256 with 8 wavefronts, 0.59 us for 256 x 128 (one wavefront per SIMD; measured on a chip in its
-// sustained clock state with operands that do not stay in the Infinity Cache), 0.295 us for 128 x 128 with two workgroups
+// 256 x 256 with 8 wavefronts, 0.53 us for 256 x 128 (one wavefront per SIMD, three-stage ring; measured on a chip in
+// its sustained clock state with operands that do not stay in the Infinity Cache), 0.295 us for 128 x 128 with two workgroups
 // sharing a CU) plus an epilogue, and the launch a fixed start-up (pipeline fill grows with the
 // tile).  Large tiles reuse operands better; small ones waste less of the last round, which matters
 // less the more the chip is shared with other streams' kernels (set_gemm_sharing).  Returns -1 if no
@@ -112,7 +112,7 @@ int choose_dma_config(const GemmArgs* gs, int count) {
   }
   if (g_gemm_config != -1) return -1;
   static const struct { int config; double per_ktile, epilogue, start; } kTiles[] = {
-      {6, 0.79, 3.0, 7.0}, {2, 0.59, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
+      {6, 0.79, 3.0, 7.0}, {2, 0.53, 2.0, 4.5}, {4, 0.295, 2.3, 3.3}};
   int best = -1;
   double best_cost = 0.0;
   for (const auto& t : kTiles) {
@@ -134,19 +134,20 @@ int choose_dma_config(const GemmArgs* gs, int count) {
     const double cost = t.start + rounds * ((ktiles / tiles) * t.per_ktile + t.epilogue);
     if (best < 0 || cost < best_cost) best = t.config, best_cost = cost;
   }
-  // The same tile with 64-wide K tiles (half the barriers per unit of work) where K allows it.  For the 128 x 128
-  // tile only where a CU holds two workgroups at a time (more than 256 tiles, or a chip shared with other lanes):
-  // measured alone on the chip, 2048 x 2560 x 2560 takes 35 us instead of 44, but 4096 x 1024 x 4096, one
-  // workgroup per CU, 42 instead of 38.
+  // The same tile with 64-wide K tiles (half the barriers per unit of work) where K allows it.  The 256 x 128 tile
+  // and, for a launch of at most one tile per CU alone on the chip, the 128 x 128 tile take a ring of three such
+  // stages: with one wavefront per SIMD nothing else covers a load that is late, and one more tile of look-ahead
+  // is worth 11 - 21 % on the 2048 x 4096 outputs with K = 4096 .. 16384 (270 us instead of 338 for the input gradient
+  // of FC1 at H = 4096) and 4 - 6 % on the 4096 x 1024 outputs.  The 128 x 128 tile with two stages only where a CU
+  // holds two workgroups at a time (more than 256 tiles, or a chip shared with other lanes): measured alone on the
+  // chip, 2048 x 2560 x 2560 takes 35 us instead of 44, but 4096 x 1024 x 4096, one workgroup per CU, 42 instead of 38.
   if (best == 6 || best == 2 || best == 4) {
-    const int wide_config = best == 6 ? 7 : best == 2 ? 8 : 9;
-    bool wide = true;
     long tiles = 0;
-    for (int i = 0; i < count; ++i) {
-      wide = wide && gemm_dma_supported(gs[i], wide_config);
-      tiles += (long)(gs[i].M / 128) * (gs[i].N / 128);
-    }
-    if (best == 4 && tiles <= 256 && g_gemm_sharing <= 0.0) wide = false;
+    for (int i = 0; i < count; ++i) tiles += (long)(gs[i].M / 128) * (gs[i].N / 128);
+    const bool one_per_cu = best == 4 && tiles <= 256 && g_gemm_sharing <= 0.0;
+    const int wide_config = best == 6 ? 7 : best == 2 ? 10 : one_per_cu ? 11 : 9;
+    bool wide = true;
+    for (int i = 0; i < count; ++i) wide = wide && gemm_dma_supported(gs[i], wide_config);
     if (wide) best = wide_config;
   }
   return best;

@@ -84,12 +84,13 @@ bool gemm_mfma_supported(const GemmArgs& g);
 int gemm_mfma(const GemmArgs& g, hipStream_t stream);  // bf16 only
 // Direct-to-LDS multi-stage kernel for tile-aligned shapes; config 0 = 256x256, 1 = 128x128 (8-deep ring),
 // 2 = 256x128, 4 = 128x128 (4-deep ring), 5 = 128x128 with 8 wavefronts, 6 = 256x256 with 8 wavefronts,
-// 7 / 8 / 9 = 256x256 (8 wavefronts) / 256x128 / 128x128 with two stages of 64-wide K tiles (K a multiple of 64).
+// 7 / 8 / 9 = 256x256 (8 wavefronts) / 256x128 / 128x128 with two stages of 64-wide K tiles (K a multiple of 64),
+// 10 / 11 = 256x128 / 128x128 with three such stages.
 bool gemm_dma_supported(const GemmArgs& g, int config);
 void gemm_dma_tile(int config, int& bm, int& bn);
 int gemm_dma(const GemmArgs& g, int config, hipStream_t stream);
 int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream);
-// -1 = automatic choice; 0, 1, 2, 4 .. 9 = force that direct-to-LDS configuration where it applies; 3 = staged kernel only
+// -1 = automatic choice; 0, 1, 2, 4 .. 11 = force that direct-to-LDS configuration where it applies; 3 = staged kernel only
 void set_gemm_config(int config);
 // How much of the chip the calling thread's GEMM launches share with kernels of other streams: 0 = a launch
 // runs alone (choose the tile for the shortest launch), 1 = idle CUs are always taken by other work (choose

@@ -163,13 +163,14 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     if (j < grp.count && (int)blockIdx.x >= grp.first[j]) gi = j;
   const DmaGemm p = grp.prob[gi];
   const int wg = (int)blockIdx.x - grp.first[gi];  // tile number within the problem
-  constexpr bool FDEEP = MODE >= 1;
+  constexpr bool FDEEP = MODE == 1 || MODE == 2;
+  constexpr bool WIDE = NSTAGE == 2 || MODE == 3;  // 64-wide K tiles (MODE 3: in a ring of NSTAGE >= 2 stages)
   constexpr int NSP = WGM * WGN;                 // wavefronts that tile the output
   constexpr int NW = NSP * (MODE == 2 ? 2 : 1);  // wavefronts in the workgroup
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   // A ring of two stages holds 64-wide K tiles (the same bytes in flight as four stages of 32, half as many
   // barriers and waits per unit of work, whole 128-byte lines per row of a contraction-contiguous operand).
-  constexpr int BK = NSTAGE == 2 ? 64 : 32;
+  constexpr int BK = WIDE ? 64 : 32;
   constexpr int KS = BK / 16;  // MFMA steps per K tile
   using OpA = Operand<BM, A_T, NW, BK>;
   using OpB = Operand<BN, B_T, NW, BK>;
@@ -177,6 +178,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   constexpr int LOADS = OpA::kPerWave + OpB::kPerWave;  // per thread per tile
   static_assert((NSTAGE - 1) * LOADS <= 63, "vmcnt range");
   static_assert(NSTAGE >= 3 || (NSTAGE == 2 && MODE == 0), "two stages: the 64-wide pipeline of MODE 0 only");
+  static_assert(MODE != 3 || NSTAGE >= 2, "the 64-wide pipeline needs at least two stages");
 
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // LDS byte address of the ring (address-space-3 offset, what M0 takes)
@@ -297,16 +299,18 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     }
   };
 
-  if constexpr (NSTAGE == 2) {
-    // Two 64-wide stages.  Per K tile (KS = 4 MFMA steps):
+  if constexpr (WIDE) {
+    // NSTAGE 64-wide stages (two, or three where the tile leaves room: one more tile of look-ahead for launches
+    // that have a single wavefront per SIMD and nothing else to cover a late load).  Per K tile (KS = 4 MFMA steps):
     //   steps 0 .. KS-2 of tile kt    | LDS reads: the following step of tile kt
     //   every fragment of tile kt is in registers; wait until tile kt+1 has landed; barrier (everyone is there)
-    //   start the loads of tile kt+2 into the buffer tile kt occupied
+    //   start the loads of tile kt+NSTAGE into the buffer tile kt occupied
     //   step KS-1 of tile kt          | LDS reads: step 0 of tile kt+1
-    issue();
-    if (nk > 1) issue();
+#pragma unroll
+    for (int t = 0; t < NSTAGE; ++t)
+      if (t < nk) issue();
     bf16x8 fa[2][TM], fb[2][TN];
-    wait_tiles<LOADS>(min(1, nk - 1));
+    wait_tiles<LOADS>(min(NSTAGE - 1, nk - 1));
     __syncthreads();
     colsum_tile(0);
     read_a(0, 0, fa[0]);
@@ -322,9 +326,14 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
       }
       // the buffer of tile kt is overwritten right after the barrier: its last fragments must have arrived
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      wait_vmcnt<0>();
-      __syncthreads();
-      if (kt + 2 < nk) issue();
+      if (kt + NSTAGE < nk) {  // steady state: tiles kt+2 .. kt+NSTAGE-1 may still be in flight
+        wait_vmcnt<(NSTAGE - 2) * LOADS>();
+        __syncthreads();
+        issue();
+      } else {
+        wait_tiles<LOADS>(min(NSTAGE - 2, nk - 2 - kt));
+        __syncthreads();
+      }
       colsum_tile(kt + 1);
       __builtin_amdgcn_sched_barrier(0);
       read_a(kt + 1, 0, fa[0]);
@@ -644,7 +653,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
 template <int BM, int BN, int WGM, int WGN, int NSTAGE, int MODE, bool A_T, bool B_T, int EPI>
 int launch(DmaGemmGroup& grp, hipStream_t stream) {
   constexpr int NW = WGM * WGN * (MODE == 2 ? 2 : 1);
-  constexpr int BK = NSTAGE == 2 ? 64 : 32;  // as in the kernel
+  constexpr int BK = (NSTAGE == 2 || MODE == 3) ? 64 : 32;  // as in the kernel
   using OpA = Operand<BM, A_T, NW, BK>;
   using OpB = Operand<BN, B_T, NW, BK>;
   constexpr size_t lds = (size_t)NSTAGE * (OpA::kBytes + OpB::kBytes);
@@ -697,10 +706,12 @@ int launch_layout(const GemmArgs& g, DmaGemmGroup& grp, hipStream_t stream) {
 // 4 = 128 x 128 with a 4-deep ring (two workgroups fit a CU), 5 = as 4 with 8 wavefronts that split
 // the MFMA steps of a K tile, 6 = 256 x 256 with 8 wavefronts (2 x 4, 128 x 64 each: two per SIMD
 // that cover each other's stalls), 7, 8 and 9 = the tiles of 6, 2 and 4 with a ring of two 64-wide K tiles
-// instead of four 32-wide ones (same bytes in flight, one barrier per 64 of K).  The others use 4 wavefronts.
+// instead of four 32-wide ones (same bytes in flight, one barrier per 64 of K); 10 and 11 = the tiles of 2 and 4 with
+// three 64-wide stages (one workgroup per CU: for launches whose single wavefront per SIMD has nothing else to cover
+// a late load).  The others use 4 wavefronts.
 void gemm_dma_tile(int config, int& bm, int& bn) {
-  bm = (config == 1 || config == 4 || config == 5 || config == 9) ? 128 : 256;
-  bn = (config == 0 || config == 6 || config == 7) ? 256 : 128;  // 2 and 8: 256 x 128
+  bm = (config == 1 || config == 4 || config == 5 || config == 9 || config == 11) ? 128 : 256;
+  bn = (config == 0 || config == 6 || config == 7) ? 256 : 128;  // 2, 8 and 10: 256 x 128
 }
 
 bool gemm_dma_supported(const GemmArgs& g, int config) {
@@ -742,6 +753,8 @@ int gemm_dma_group(const GemmArgs* gs, int count, int config, hipStream_t stream
     case 7: return launch_layout<256, 256, 2, 4, 2, 0>(g, grp, stream);  // as 6 with two stages of 64-wide K tiles
     case 8: return launch_layout<256, 128, 2, 2, 2, 0>(g, grp, stream);  // as 2 with two stages of 64-wide K tiles
     case 9: return launch_layout<128, 128, 2, 2, 2, 0>(g, grp, stream);  // 128 x 128 likewise (two workgroups per CU)
+    case 10: return launch_layout<256, 128, 2, 2, 3, 3>(g, grp, stream);  // as 8 with three stages (144 KiB): one more tile of look-ahead
+    case 11: return launch_layout<128, 128, 2, 2, 3, 3>(g, grp, stream);  // 128 x 128, three 64-wide stages (96 KiB, one workgroup per CU)
     default: return launch_layout<256, 128, 2, 2, 4, 0>(g, grp, stream);
   }
 }

@@ -66,7 +66,7 @@ int hanayo_op_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
 }
 
 int hanayo_op_gemm_config(int config) {
-  if (config < -1 || config > 9) return set_error(HANAYO_EINVAL, "op_gemm_config: config must be -1..9");
+  if (config < -1 || config > 11) return set_error(HANAYO_EINVAL, "op_gemm_config: config must be -1..11");
   k::set_gemm_config(config);
   return HANAYO_OK;
 }

@@ -46,7 +46,7 @@ def gemm_config(request):
 
 
 # every bf16 MFMA kernel variant on shapes that are whole numbers of its tile
-@pytest.mark.parametrize("gemm_config", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9], indirect=True)
+@pytest.mark.parametrize("gemm_config", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11], indirect=True)
 @pytest.mark.parametrize("layout", list(LAYOUTS))
 @pytest.mark.parametrize("shape", [(512, 768, 256), (256, 256, 32), (1024, 512, 96), (512, 512, 192), (256, 512, 64)])
 def test_gemm_kernel_variants(gemm_config, layout, shape):
