@@ -1,8 +1,9 @@
 // LayerNorm forward / backward, column sums (bias gradients) and the partial-sum
 // finaliser.  All of them stream [T][H]-shaped tensors once and are bound by HBM
-// bandwidth: one wavefront owns a whole row, lanes read 8-element vectors so
-// that a wavefront touches 1 KiB (bf16) of contiguous memory per load, row
-// statistics are wavefront butterfly reductions, and per-column sums live in
+// bandwidth: lanes read 8-element vectors so that a wavefront touches 1 KiB (bf16)
+// of contiguous memory per load, row statistics are wavefront butterfly
+// reductions (forward: one wavefront owns a whole row; backward: the wavefronts
+// that share a row exchange two sums through LDS), and per-column sums live in
 // registers across the rows a wavefront visits.
 #include <atomic>
 
@@ -18,8 +19,11 @@ constexpr int kRowsPerBlock = 4;  // wavefronts per 256-thread block
 constexpr int kLnBwdMaxBlocks = 256;  // workgroups of the LN backward = partial rows of gamma/beta sums it writes
 
 // ------------------------------------------------------------------ LN forward
-// NV = vectors of 8 per lane kept in registers (H <= 64 * 8 * NV).
-template <typename T, int NV>
+// NV = vectors of 8 per lane kept in registers (H <= 64 * 8 * NV).  FULL: H == 512 * NV exactly, so no lane's
+// vector falls outside the row: the column guards vanish at compile time and a row's loads are one straight run
+// of instructions (a guarded load sits in a branch of its own, and the waits the compiler places at the joins
+// serialise the loads of a row).
+template <typename T, int NV, bool FULL>
 __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ out,
                                                      float2* __restrict__ stats, T* __restrict__ copy_out, int rows,
@@ -33,7 +37,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 64 + lane) * 8;
-    if (c < H) {
+    if (FULL || c < H) {
       load8(xr + c, v[i]);
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += v[i][j];
@@ -44,7 +48,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 64 + lane) * 8;
-    if (c < H) {
+    if (FULL || c < H) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const float dlt = v[i][j] - mean;
@@ -57,7 +61,7 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 64 + lane) * 8;
-    if (c < H) {
+    if (FULL || c < H) {
       if (copy_out) store8(copy_out + (size_t)row * H + c, v[i]);
       float g[8], b[8], o[8];
       load8(gamma + c, g);
@@ -70,144 +74,145 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
 }
 
 // ------------------------------------------------------------------ LN backward
-// Workgroup = 8 wavefronts; each wavefront walks rows two at a time (both rows' loads are
-// issued before either is reduced, which doubles the bytes in flight), its lanes keep the
-// column sums of dout*xhat and dout for their columns in registers.  The eight wavefronts are
-// combined through LDS (upper four into lower four, then the four into one partial row).
-// U = rows in flight per wavefront (2 where the registers allow), WAVES = wavefronts per workgroup
-// (8, or 4 for the widest rows whose register arrays need the larger per-wavefront budget).
-template <typename T, int NV, int U, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ x,
-                                                     const T* __restrict__ gamma, const float2* __restrict__ stats,
-                                                     const T* __restrict__ addend, T* __restrict__ dz,
-                                                     float* __restrict__ partial, int rows, int H) {
-  extern __shared__ float red[];  // [4][H]
-  constexpr int kBwdWaves = WAVES;
+// Eight consecutive elements in storage form: what a load that is still in flight occupies (for bf16 a
+// quarter of the registers of eight floats).
+template <typename T>
+struct Raw8;
+template <>
+struct Raw8<bf16> {
+  bf16x8 v;
+  __device__ __forceinline__ void load(const bf16* p) { v = *reinterpret_cast<const bf16x8*>(p); }
+  __device__ __forceinline__ float get(int j) const { return (float)v[j]; }
+};
+template <>
+struct Raw8<float> {
+  f32x4 v[2];
+  __device__ __forceinline__ void load(const float* p) {
+    v[0] = *reinterpret_cast<const f32x4*>(p);
+    v[1] = *reinterpret_cast<const f32x4*>(p + 4);
+  }
+  __device__ __forceinline__ float get(int j) const { return v[j >> 2][j & 3]; }
+};
+
+// A row is shared by RS wavefronts: lane l of part p owns vector p of the row's 512-element groups (8 columns
+// from (p * 64 + l) * 8), so a lane keeps 8 columns of x, dout, gamma and of the two column sums whatever the
+// width of the row, and the registers left over go to the NEXT row: every wavefront fetches its slice of the
+// row after (storage form) before it reduces the current one, so loads, arithmetic and stores of neighbouring
+// rows overlap.  (One wavefront per row holds the whole row and both column sums in registers: at 4096
+// columns that is one wavefront per SIMD and nothing in flight while it computes.)  A workgroup of RS * RG
+// wavefronts walks RG rows at a time.  The two row sums cross the RS parts through LDS (double-buffered slots:
+// one barrier per row); the parts are added in a fixed order and every part computes the same totals.  The
+// gamma / beta column sums stay in registers across the rows a wavefront walks; at the end the RG row groups
+// are added in order through LDS and the workgroup writes one partial row [gamma sums | beta sums].
+// FULL: H == 512 * RS, no column guard.
+template <typename T, int RS, int RG, bool FULL>
+__global__ __launch_bounds__(RS * RG * 64) void ln_bwd_kernel(const T* __restrict__ dout, const T* __restrict__ x,
+                                                              const T* __restrict__ gamma, const float2* __restrict__ stats,
+                                                              const T* __restrict__ addend, T* __restrict__ dz,
+                                                              float* __restrict__ partial, int rows, int H) {
+  extern __shared__ float red[];                 // [RG][2 * H] for the column sums; before that the row-sum exchange
+  float2* xch = reinterpret_cast<float2*>(red);  // [2][RG][RS]
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
-  float acc_g[NV][8], acc_b[NV][8], gm[NV][8];
+  const int rg = wave / RS, part = wave % RS;
+  const int col = (part * 64 + lane) * 8;
+  const bool inside = FULL || col < H;
+  float acc_g[8], acc_b[8], gm[8];
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    const int c = (i * 64 + lane) * 8;
+  for (int j = 0; j < 8; ++j) acc_g[j] = acc_b[j] = gm[j] = 0.f;
+  if (inside) load8(gamma + col, gm);
+  Raw8<T> nx, ndy, nadd;
+  float2 nst = make_float2(0.f, 0.f);
+  auto fetch = [&](int row) {
+    if (row < rows && inside) {
+      nst = stats[row];
+      const size_t at = (size_t)row * H + col;
+      nx.load(x + at);
+      ndy.load(dout + at);
+      if (addend) nadd.load(addend + at);
+    }
+  };
+  const int step = gridDim.x * RG;
+  fetch(blockIdx.x * RG + rg);
+  int it = 0;
+  for (int first = blockIdx.x * RG; first < rows; first += step, ++it) {  // the same trip count for every wavefront
+    const int row = first + rg;
+    const bool valid = row < rows && inside;
+    const float2 st = nst;
+    float xh[8], dy[8];
+    const Raw8<T> add = nadd;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc_g[i][j] = acc_b[i][j] = gm[i][j] = 0.f;
-    if (c < H) load8(gamma + c, gm[i]);
-  }
-  const int stride = gridDim.x * kBwdWaves;
-  for (int row0 = blockIdx.x * kBwdWaves + wave; row0 < rows; row0 += U * stride) {
-    const int row1 = row0 + stride;
-    const bool has1 = U == 2 && row1 < rows;
-    float xh[U][NV][8], dy[U][NV][8];
-    bf16x8 add_raw[U][NV];    // residual addend in storage form, fetched with the other loads
-    f32x4 add_f32[U][NV][2];  // (fp32 storage)
-    float2 st[U];
-    st[0] = stats[row0];
-    if (U == 2) st[U - 1] = has1 ? stats[row1] : make_float2(0.f, 0.f);
+    for (int j = 0; j < 8; ++j) {
+      xh[j] = valid ? (nx.get(j) - st.x) * st.y : 0.f;
+      dy[j] = valid ? ndy.get(j) : 0.f;
+    }
+    fetch(row + step);
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const size_t base = (size_t)(u ? row1 : row0) * H;
+    for (int j = 0; j < 8; ++j) {
+      acc_g[j] += dy[j] * xh[j];
+      acc_b[j] += dy[j];
+      const float dxh = dy[j] * gm[j];
+      s1 += dxh;
+      s2 += dxh * xh[j];
+    }
+    s1 = wave_sum(s1);
+    s2 = wave_sum(s2);
+    if (RS > 1) {
+      float2* slot = xch + ((it & 1) * RG + rg) * RS;
+      if (lane == 0) slot[part] = make_float2(s1, s2);
+      __syncthreads();
+      s1 = s2 = 0.f;
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 8;
-        if (c < H && (u == 0 || has1)) {
-          load8(x + base + c, xh[u][i]);
-          load8(dout + base + c, dy[u][i]);
-          if (addend) {
-            if constexpr (sizeof(T) == 2) {
-              add_raw[u][i] = *reinterpret_cast<const bf16x8*>(addend + base + c);
-            } else {
-              add_f32[u][i][0] = *reinterpret_cast<const f32x4*>(addend + base + c);
-              add_f32[u][i][1] = *reinterpret_cast<const f32x4*>(addend + base + c + 4);
-            }
-          }
-        }
+      for (int p = 0; p < RS; ++p) {
+        const float2 t = slot[p];
+        s1 += t.x;
+        s2 += t.y;
       }
     }
+    if (valid) {
+      const float c1 = s1 / (float)H, c2 = s2 / (float)H;
+      float o[8];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (u == 1 && !has1) break;
-      const size_t base = (size_t)(u ? row1 : row0) * H;
-      float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 8;
-        if (c < H) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            xh[u][i][j] = (xh[u][i][j] - st[u].x) * st[u].y;
-            acc_g[i][j] += dy[u][i][j] * xh[u][i][j];
-            acc_b[i][j] += dy[u][i][j];
-            const float dxh = dy[u][i][j] * gm[i][j];
-            s1 += dxh;
-            s2 += dxh * xh[u][i][j];
-          }
-        }
+      for (int j = 0; j < 8; ++j) {
+        o[j] = (dy[j] * gm[j] - c1 - xh[j] * c2) * st.y;
+        if (addend) o[j] += add.get(j);
       }
-      const float c1 = wave_sum(s1) / (float)H;
-      const float c2 = wave_sum(s2) / (float)H;
-#pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 8;
-        if (c < H) {
-          float o[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) o[j] = (dy[u][i][j] * gm[i][j] - c1 - xh[u][i][j] * c2) * st[u].y;
-          if (addend) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              if constexpr (sizeof(T) == 2) o[j] += (float)add_raw[u][i][j];
-              else o[j] += add_f32[u][i][j >> 2][j & 3];
-            }
-          }
-          store8(dz + base + c, o);
-        }
-      }
+      store8(dz + (size_t)row * H + col, o);
     }
   }
-  // combine: pass 0 = gamma sums, pass 1 = beta sums
-  for (int pass = 0; pass < 2; ++pass) {
-    if (WAVES == 8 && wave >= 4) {
+  __syncthreads();  // the exchange slots are done with; the same memory now takes the column sums
+  if (inside) {
+    f32x4 v[4];
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 8;
-        if (c < H) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) red[(wave - 4) * H + c + j] = pass == 0 ? acc_g[i][j] : acc_b[i][j];
-        }
-      }
+    for (int j = 0; j < 4; ++j) {
+      v[0][j] = acc_g[j];
+      v[1][j] = acc_g[4 + j];
+      v[2][j] = acc_b[j];
+      v[3][j] = acc_b[4 + j];
     }
-    if (WAVES == 8) __syncthreads();
-    if (wave < 4) {
+    float* mine = red + (size_t)rg * 2 * H + col;
+    *reinterpret_cast<f32x4*>(mine) = v[0];
+    *reinterpret_cast<f32x4*>(mine + 4) = v[1];
+    *reinterpret_cast<f32x4*>(mine + H) = v[2];
+    *reinterpret_cast<f32x4*>(mine + H + 4) = v[3];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < 2 * H; c += RS * RG * 64) {
+    float t = 0.f;
 #pragma unroll
-      for (int i = 0; i < NV; ++i) {
-        const int c = (i * 64 + lane) * 8;
-        if (c < H) {
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            float v = pass == 0 ? acc_g[i][j] : acc_b[i][j];
-            if (WAVES == 8) v += red[wave * H + c + j];
-            red[wave * H + c + j] = v;
-          }
-        }
-      }
-    }
-    __syncthreads();
-    for (int c = threadIdx.x; c < H; c += blockDim.x) {
-      float t = 0.f;
-#pragma unroll
-      for (int w = 0; w < 4; ++w) t += red[w * H + c];
-      partial[(size_t)blockIdx.x * 2 * H + pass * H + c] = t;
-    }
-    __syncthreads();
+    for (int g = 0; g < RG; ++g) t += red[g * 2 * H + c];
+    partial[(size_t)blockIdx.x * 2 * H + c] = t;
   }
 }
 
 // out[c] += sum_r partial[r][c] for c in [0, n), without atomics and in a fixed order: a workgroup owns 32
-// columns; its 8 row groups each run down every 8th partial row (32 lanes x 4 bytes = one 128-byte line per
-// row), the 8 group sums are added in order through LDS, and one thread per column adds the total to `out`.
+// columns; its 32 row groups each run down every 32nd partial row (32 lanes x 4 bytes = one 128-byte line per
+// row; with 256 partial rows that is 8 loads per thread, all in flight at once), the group sums are added in
+// order through LDS, and one thread per column adds the total to `out`.
 // Columns >= split go to out1[c - split].  The same bits every run.
-constexpr int kFinalizeCols = 32, kFinalizeGroups = 8;
-__global__ __launch_bounds__(256) void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n,
+constexpr int kFinalizeCols = 32, kFinalizeGroups = 32;
+__global__ __launch_bounds__(kFinalizeCols * kFinalizeGroups) void finalize_kernel(const float* __restrict__ partial, int rows, int ld, int n,
                                                        float* __restrict__ out0, float* __restrict__ out1, int split) {
   __shared__ float red[kFinalizeGroups][kFinalizeCols];
   const int cl = threadIdx.x % kFinalizeCols, rg = threadIdx.x / kFinalizeCols;
@@ -263,38 +268,67 @@ int ln_forward_t(const void* x, const void* gamma, const void* beta, void* out, 
                  int H, float eps, hipStream_t stream) {
   const dim3 grid((T_ + kRowsPerBlock - 1) / kRowsPerBlock), block(256);
   const int nv = (H + 511) / 512;
-#define LAUNCH(NV)                                                                                                 \
-  hipLaunchKernelGGL((ln_fwd_kernel<T, NV>), grid, block, 0, stream, (const T*)x, (const T*)gamma, (const T*)beta, \
+#define LAUNCH(NV, FULL)                                                                                              \
+  hipLaunchKernelGGL((ln_fwd_kernel<T, NV, FULL>), grid, block, 0, stream, (const T*)x, (const T*)gamma, (const T*)beta, \
                      (T*)out, stats, (T*)copy_out, T_, H, eps)
-  if (nv <= 1) LAUNCH(1);
-  else if (nv <= 2) LAUNCH(2);
-  else if (nv <= 4) LAUNCH(4);
-  else LAUNCH(8);
+  if (H % 512 == 0) {  // every vector of every lane is inside the row
+    switch (nv) {
+      case 1: LAUNCH(1, true); break;
+      case 2: LAUNCH(2, true); break;
+      case 3: LAUNCH(3, true); break;
+      case 4: LAUNCH(4, true); break;
+      case 5: LAUNCH(5, true); break;
+      case 6: LAUNCH(6, true); break;
+      case 7: LAUNCH(7, true); break;
+      default: LAUNCH(8, true); break;
+    }
+  } else if (nv <= 1) LAUNCH(1, false);
+  else if (nv <= 2) LAUNCH(2, false);
+  else if (nv <= 4) LAUNCH(4, false);
+  else LAUNCH(8, false);
 #undef LAUNCH
   return check_launch("ln_forward");
+}
+
+int launch_finalize(const float* partial, int rows, int ld, int n, float* out0, float* out1, int split, hipStream_t stream,
+                    const char* what) {
+  hipLaunchKernelGGL(finalize_kernel, dim3((n + kFinalizeCols - 1) / kFinalizeCols), dim3(kFinalizeCols * kFinalizeGroups), 0,
+                     stream, partial, rows, ld, n, out0, out1, split);
+  return check_launch(what);
 }
 
 template <typename T>
 int ln_backward_t(const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend, void* dz,
                   float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
-  const int nv = (H + 511) / 512;
-  const int waves = nv <= 4 ? 8 : 4;
-  int blocks = (T_ + waves - 1) / waves;
-  if (blocks > kLnBwdMaxBlocks) blocks = kLnBwdMaxBlocks;  // a wavefront then walks several rows
-  const size_t lds = (size_t)4 * H * sizeof(float);
-#define LAUNCH(NV, U, WAVES)                                                                                   \
-  hipLaunchKernelGGL((ln_bwd_kernel<T, NV, U, WAVES>), dim3(blocks), dim3(WAVES * 64), lds, stream, (const T*)dout, \
-                     (const T*)x, (const T*)gamma, stats, (const T*)addend, (T*)dz, partial, T_, H)
-  if (nv <= 1) LAUNCH(1, 2, 8);
-  else if (nv <= 2) LAUNCH(2, 2, 8);
-  else if (nv <= 4) LAUNCH(4, 1, 8);
-  else LAUNCH(8, 1, 4);
+  const int nv = (H + 511) / 512;  // wavefronts that share a row; 16 wavefronts (15 or 14 where nv does not divide 16)
+  const int rg = 16 / nv;          // per workgroup walk rg rows at a time
+  int blocks = (T_ + rg - 1) / rg;
+  if (blocks > kLnBwdMaxBlocks) blocks = kLnBwdMaxBlocks;  // a workgroup then walks several groups of rows
+  size_t lds = (size_t)rg * 2 * H * sizeof(float);         // at most 16 / nv * 2 * 512 nv * 4 = 64 KiB
+  if (lds < 1024) lds = 1024;                              // the row-sum exchange slots
+#define LAUNCH(RS, RG)                                                                                                \
+  do {                                                                                                                \
+    if (H == 512 * RS)                                                                                                \
+      hipLaunchKernelGGL((ln_bwd_kernel<T, RS, RG, true>), dim3(blocks), dim3(RS * RG * 64), lds, stream, (const T*)dout, \
+                         (const T*)x, (const T*)gamma, stats, (const T*)addend, (T*)dz, partial, T_, H);              \
+    else                                                                                                              \
+      hipLaunchKernelGGL((ln_bwd_kernel<T, RS, RG, false>), dim3(blocks), dim3(RS * RG * 64), lds, stream, (const T*)dout, \
+                         (const T*)x, (const T*)gamma, stats, (const T*)addend, (T*)dz, partial, T_, H);              \
+  } while (0)
+  switch (nv) {
+    case 1: LAUNCH(1, 16); break;
+    case 2: LAUNCH(2, 8); break;
+    case 3: LAUNCH(3, 5); break;
+    case 4: LAUNCH(4, 4); break;
+    case 5: LAUNCH(5, 3); break;
+    case 6: LAUNCH(6, 2); break;
+    case 7: LAUNCH(7, 2); break;
+    default: LAUNCH(8, 2); break;
+  }
 #undef LAUNCH
   int rc = check_launch("ln_backward");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((2 * H + kFinalizeCols - 1) / kFinalizeCols), dim3(256), 0, stream, partial, blocks,
-                     2 * H, 2 * H, dgamma, dbeta, H);
-  return check_launch("ln_backward finalize");
+  return launch_finalize(partial, blocks, 2 * H, 2 * H, dgamma, dbeta, H, stream, "ln_backward finalize");
 }
 
 template <typename T>
@@ -306,9 +340,7 @@ int colsum_t(const void* in, int T_, int N, float* out, float* partial, hipStrea
   hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, stream, (const T*)in, T_, N, partial);
   int rc = check_launch("colsum");
   if (rc) return rc;
-  hipLaunchKernelGGL(finalize_kernel, dim3((N + kFinalizeCols - 1) / kFinalizeCols), dim3(256), 0, stream, partial, gy, N, N,
-                     out, out, N);
-  return check_launch("colsum finalize");
+  return launch_finalize(partial, gy, N, N, out, out, N, stream, "colsum finalize");
 }
 
 }  // namespace

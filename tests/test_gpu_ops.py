@@ -131,7 +131,10 @@ def run_gemm_case(dtype, layout, shape):
 
 
 @pytest.mark.parametrize("dtype", ["bf16", "fp32"])
-@pytest.mark.parametrize("rows,H", [(64, 256), (300, 1024), (37, 2560), (130, 4096), (1030, 512), (5, 72)])
+@pytest.mark.parametrize("rows,H", [(64, 256), (300, 1024), (37, 2560), (130, 4096), (1030, 512), (5, 72),
+                                    # wide rows: several trips of a workgroup's row loop with a ragged last one,
+                                    # every width class above 2048, a width that is no multiple of 512, one row
+                                    (2100, 4096), (1601, 2560), (700, 3072), (530, 3584), (41, 2600), (1, 4096)])
 def test_layernorm_forward_backward(dtype, rows, H):
     rng = np.random.default_rng(rows * 7 + H)
     x = rnd(rng, (rows, H), dtype, 2.0) + (0.5 if dtype == "fp32" else 0.0)
