@@ -18,6 +18,26 @@ namespace {
 constexpr int kRowsPerBlock = 4;  // wavefronts per 256-thread block
 constexpr int kLnBwdMaxBlocks = 256;  // workgroups of the LN backward = partial rows of gamma/beta sums it writes
 
+// Eight consecutive elements in storage form: what a load that is still in flight occupies (for bf16 a
+// quarter of the registers of eight floats).
+template <typename T>
+struct Raw8;
+template <>
+struct Raw8<bf16> {
+  bf16x8 v;
+  __device__ __forceinline__ void load(const bf16* p) { v = *reinterpret_cast<const bf16x8*>(p); }
+  __device__ __forceinline__ float get(int j) const { return (float)v[j]; }
+};
+template <>
+struct Raw8<float> {
+  f32x4 v[2];
+  __device__ __forceinline__ void load(const float* p) {
+    v[0] = *reinterpret_cast<const f32x4*>(p);
+    v[1] = *reinterpret_cast<const f32x4*>(p + 4);
+  }
+  __device__ __forceinline__ float get(int j) const { return v[j >> 2][j & 3]; }
+};
+
 // ------------------------------------------------------------------ LN forward
 // NV = vectors of 8 per lane kept in registers (H <= 64 * 8 * NV).  FULL: H == 512 * NV exactly, so no lane's
 // vector falls outside the row: the column guards vanish at compile time and a row's loads are one straight run
@@ -33,12 +53,25 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
   if (row >= rows) return;
   const T* xr = x + (size_t)row * H;
   float v[NV][8];
+  Raw8<T> g[NV], b[NV];  // fetched with the row (storage form), so that the last step waits for nothing
   float sum = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = (i * 64 + lane) * 8;
+    if (FULL || c < H) load8(xr + c, v[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 8;
     if (FULL || c < H) {
-      load8(xr + c, v[i]);
+      g[i].load(gamma + c);
+      b[i].load(beta + c);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = (i * 64 + lane) * 8;
+    if (FULL || c < H) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) sum += v[i][j];
     }
@@ -63,37 +96,15 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const T* __restrict__ x, co
     const int c = (i * 64 + lane) * 8;
     if (FULL || c < H) {
       if (copy_out) store8(copy_out + (size_t)row * H + c, v[i]);
-      float g[8], b[8], o[8];
-      load8(gamma + c, g);
-      load8(beta + c, b);
+      float o[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * g[j] + b[j];
+      for (int j = 0; j < 8; ++j) o[j] = (v[i][j] - mean) * rstd * g[i].get(j) + b[i].get(j);
       store8(out + (size_t)row * H + c, o);
     }
   }
 }
 
 // ------------------------------------------------------------------ LN backward
-// Eight consecutive elements in storage form: what a load that is still in flight occupies (for bf16 a
-// quarter of the registers of eight floats).
-template <typename T>
-struct Raw8;
-template <>
-struct Raw8<bf16> {
-  bf16x8 v;
-  __device__ __forceinline__ void load(const bf16* p) { v = *reinterpret_cast<const bf16x8*>(p); }
-  __device__ __forceinline__ float get(int j) const { return (float)v[j]; }
-};
-template <>
-struct Raw8<float> {
-  f32x4 v[2];
-  __device__ __forceinline__ void load(const float* p) {
-    v[0] = *reinterpret_cast<const f32x4*>(p);
-    v[1] = *reinterpret_cast<const f32x4*>(p + 4);
-  }
-  __device__ __forceinline__ float get(int j) const { return v[j >> 2][j & 3]; }
-};
-
 // A row is shared by RS wavefronts: lane l of part p owns vector p of the row's 512-element groups (8 columns
 // from (p * 64 + l) * 8), so a lane keeps 8 columns of x, dout, gamma and of the two column sums whatever the
 // width of the row, and the registers left over go to the NEXT row: every wavefront fetches its slice of the
