@@ -611,7 +611,7 @@ __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
 // sets alternate roles; tile t+1 must have landed when step t starts, hence NST >= 3 buffers and
 // the loads of tile t+NST-1 issued at step t.  Arithmetic is that of attn_fwd_dma_kernel.
 template <int DP, int NST>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_pipe_kernel(AttnDev p) {
+__device__ __forceinline__ void attn_fwd_pipe_body(const AttnDev& p) {
   using Tile = SwTile<DP>;
   static_assert(NST >= 3, "tile t+1 is read while tile t+NST-1 is loaded");
   constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
@@ -750,6 +750,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
     if (half == 0) p.lse[((size_t)n * p.heads + h) * p.s + q] = (m * c2 + log2f(lsum)) * kLn2;
   }
+}
+
+// Head dim 64: capped at 256 registers so that two workgroups share a CU.  Head dim 128: the output
+// accumulators and two score sets need more, one workgroup per CU.
+template <int DP, int NST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_pipe_kernel(AttnDev p) {
+  attn_fwd_pipe_body<DP, NST>(p);
+}
+template <int DP, int NST>
+__global__ __launch_bounds__(256) void attn_fwd_pipe_wide_kernel(AttnDev p) {
+  attn_fwd_pipe_body<DP, NST>(p);
 }
 
 template <int DP, int NST, int D = DP>
@@ -1284,8 +1295,12 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
       hipLaunchKernelGGL((attn_fwd_pipe_kernel<64, 4>), grid, block, lds, stream, p);
     } else {  // head dims 80 and 96 use the 128-wide LDS rows, partly filled
       constexpr size_t lds = 2 * 2 * SwTile<128>::kBytes;
-      if (a.d == 128) hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2>), grid, block, lds, stream, p);
-      else if (a.d == 96) hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 96>), grid, block, lds, stream, p);
+      if (a.d == 128) {  // pipelined over the key tiles like head dim 64, three stages of K and V (96 KiB)
+        constexpr size_t lds3 = 3 * 2 * SwTile<128>::kBytes;
+        const int rc = raise_lds(attn_fwd_pipe_wide_kernel<128, 3>, lds3);
+        if (rc) return rc;
+        hipLaunchKernelGGL((attn_fwd_pipe_wide_kernel<128, 3>), grid, block, lds3, stream, p);
+      } else if (a.d == 96) hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 96>), grid, block, lds, stream, p);
       else hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 80>), grid, block, lds, stream, p);
     }
     return check_launch("attn_fwd_dma");
