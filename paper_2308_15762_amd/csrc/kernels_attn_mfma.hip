@@ -610,11 +610,11 @@ __global__ __launch_bounds__(256) void attn_fwd_dma_kernel(AttnDev p) {
 // the longest query tile's chain of key tiles sets the kernel's duration).  Two score registers
 // sets alternate roles; tile t+1 must have landed when step t starts, hence NST >= 3 buffers and
 // the loads of tile t+NST-1 issued at step t.  Arithmetic is that of attn_fwd_dma_kernel.
-template <int DP, int NST>
+template <int DP, int NST, int D = DP>
 __device__ __forceinline__ void attn_fwd_pipe_body(const AttnDev& p) {
   using Tile = SwTile<DP>;
   static_assert(NST >= 3, "tile t+1 is read while tile t+NST-1 is loaded");
-  constexpr int BKV = 64, KS = DP / 16, DT = DP / 32;
+  constexpr int BKV = 64, KS = D / 16, DT = (D + 31) / 32;  // D = head dim in memory, DP = LDS row layout
   constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const unsigned lds0 = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)smem);
@@ -632,8 +632,8 @@ __device__ __forceinline__ void attn_fwd_pipe_body(const AttnDev& p) {
 
   auto issue = [&](int t) {
     const unsigned st = lds0 + (unsigned)(t % NST) * STAGE;
-    Tile::issue(base + H, ld3, t * BKV, p.s, st, wave, lane);
-    Tile::issue(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
+    Tile::template issue<D>(base + H, ld3, t * BKV, p.s, st, wave, lane);
+    Tile::template issue<D>(base + 2 * H, ld3, t * BKV, p.s, st + Tile::kBytes, wave, lane);
   };
 #pragma unroll
   for (int t = 0; t < NST - 1; ++t)
@@ -743,6 +743,7 @@ __device__ __forceinline__ void attn_fwd_pipe_body(const AttnDev& p) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int col = 32 * dt + 8 * g + 4 * half;
+        if (D % 32 != 0 && col >= D) continue;  // the last column tile of a head dim like 80 is partly padding
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16)(o[dt][4 * g + e] * inv);
@@ -758,9 +759,9 @@ template <int DP, int NST>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_pipe_kernel(AttnDev p) {
   attn_fwd_pipe_body<DP, NST>(p);
 }
-template <int DP, int NST>
+template <int DP, int NST, int D = DP>
 __global__ __launch_bounds__(256) void attn_fwd_pipe_wide_kernel(AttnDev p) {
-  attn_fwd_pipe_body<DP, NST>(p);
+  attn_fwd_pipe_body<DP, NST, D>(p);
 }
 
 template <int DP, int NST, int D = DP>
@@ -1293,15 +1294,25 @@ int attn_forward_mfma(const AttnArgs& a, hipStream_t stream) {
     if (a.d == 64) {
       constexpr size_t lds = 4 * 2 * SwTile<64>::kBytes;
       hipLaunchKernelGGL((attn_fwd_pipe_kernel<64, 4>), grid, block, lds, stream, p);
-    } else {  // head dims 80 and 96 use the 128-wide LDS rows, partly filled
+    } else if (a.d == 80) {
+      // one tile at a time, two stages, in the 128-wide LDS rows partly filled: 231 registers and 64 KiB, so two
+      // workgroups share a CU.  (The pipelined body is no faster here alone, 39.2 against 39.8 us at s = 1024,
+      // 64 (sequence, head) pairs, and with its 128 KiB and one workgroup per CU it leaves less room for the
+      // kernels of the executor's other lanes: 573.5 against 570.6 ms per step of the eight-chunk workload.)
       constexpr size_t lds = 2 * 2 * SwTile<128>::kBytes;
-      if (a.d == 128) {  // pipelined over the key tiles like head dim 64, three stages of K and V (96 KiB)
-        constexpr size_t lds3 = 3 * 2 * SwTile<128>::kBytes;
-        const int rc = raise_lds(attn_fwd_pipe_wide_kernel<128, 3>, lds3);
-        if (rc) return rc;
-        hipLaunchKernelGGL((attn_fwd_pipe_wide_kernel<128, 3>), grid, block, lds3, stream, p);
-      } else if (a.d == 96) hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 96>), grid, block, lds, stream, p);
-      else hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 80>), grid, block, lds, stream, p);
+      hipLaunchKernelGGL((attn_fwd_dma_kernel<128, 2, 80>), grid, block, lds, stream, p);
+    } else {  // the pipelined body without the register cap (one workgroup per CU), four stages of K and V
+              // (128 KiB); head dim 96 in the 128-wide LDS rows, partly filled
+      constexpr size_t lds = 4 * 2 * SwTile<128>::kBytes;
+#define LAUNCH_FWD(...)                                                                        \
+  do {                                                                                         \
+    const int rc = raise_lds(attn_fwd_pipe_wide_kernel<__VA_ARGS__>, lds);                     \
+    if (rc) return rc;                                                                         \
+    hipLaunchKernelGGL((attn_fwd_pipe_wide_kernel<__VA_ARGS__>), grid, block, lds, stream, p); \
+  } while (0)
+      if (a.d == 128) LAUNCH_FWD(128, 4);
+      else LAUNCH_FWD(128, 4, 96);
+#undef LAUNCH_FWD
     }
     return check_launch("attn_fwd_dma");
   }
