@@ -6,6 +6,8 @@
 #include <cstdio>
 #include <cstring>
 
+#include <vector>
+
 #include "kernels.h"
 
 namespace hanayo {
@@ -249,6 +251,19 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
   char* ws = static_cast<char*>(workspace);
   const int T = sh.T, H = sh.H, F = sh.F;
   float* partial = reinterpret_cast<float*>(ws + WL.partial);
+  // Every LayerNorm backward leaves its partial gamma/beta sums in a slot of its own; one launch after the
+  // last block adds them all to the gradients.
+  std::vector<k::FinalizeJob> ln_jobs;
+  ln_jobs.reserve(2 * (size_t)sh.nb);
+  auto ln_slot = [&]() { return reinterpret_cast<float*>(ws + WL.ln_partial + ln_jobs.size() * WL.ln_slot_bytes); };
+  auto ln_bwd = [&](const void* dout, const void* x, const void* gamma, const void* stats, const void* addend, void* dz,
+                    float* dgamma, float* dbeta) {
+    k::FinalizeJob job;
+    const int rc = k::ln_backward_deferred(sh.dtype, dout, x, gamma, reinterpret_cast<const float2*>(stats), addend, dz,
+                                           dgamma, dbeta, ln_slot(), T, H, st, &job);
+    if (rc == HANAYO_OK) ln_jobs.push_back(job);
+    return rc;
+  };
   const void* dy_blk = dy;
   for (int blk = sh.nb - 1; blk >= 0; --blk) {
     // The four weight-gradient GEMMs of a block wait until its end and go out as one group: every
@@ -270,8 +285,8 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
       dw[1] = bwd_params_gemm(sh, sb + L.ln_b, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_act, p.w[P_W1], ws + WL.d_h0, H, F, k::EPI_NONE, nullptr, st));
       // dx1 = dy + LN2'(d_h0)
-      TRY(k::ln_backward(sh.dtype, ws + WL.d_h0, sb + L.x1, p.w[P_LN2G], reinterpret_cast<const float2*>(sb + L.stats2),
-                         dy_blk, ws + WL.d_h1, p.g[P_LN2G], p.g[P_LN2B], partial, T, H, st));
+      TRY(ln_bwd(ws + WL.d_h0, sb + L.x1, p.w[P_LN2G], sb + L.stats2,
+                 dy_blk, ws + WL.d_h1, p.g[P_LN2G], p.g[P_LN2B]));
       // x1 = x + Wo ctx
       dw[2] = bwd_params_gemm(sh, sb + L.ctx, ws + WL.d_h1, p.g[P_WO], p.g[P_BO], H, H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_h1, p.w[P_WO], ws + WL.d_h0, H, H, k::EPI_NONE, nullptr, st));
@@ -280,20 +295,20 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
       dw[3] = bwd_params_gemm(sh, sb + L.ln_a, ws + WL.d_qkv, p.g[P_WQKV], p.g[P_BQKV], H, 3 * H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_qkv, p.w[P_WQKV], ws + WL.d_h2, H, 3 * H, k::EPI_NONE, nullptr, st));
       // dx = dx1 + LN1'(d_h2)
-      TRY(k::ln_backward(sh.dtype, ws + WL.d_h2, sb + L.x, p.w[P_LN1G], reinterpret_cast<const float2*>(sb + L.stats1),
-                         ws + WL.d_h1, dx_blk, p.g[P_LN1G], p.g[P_LN1B], partial, T, H, st));
+      TRY(ln_bwd(ws + WL.d_h2, sb + L.x, p.w[P_LN1G], sb + L.stats1,
+                 ws + WL.d_h1, dx_blk, p.g[P_LN1G], p.g[P_LN1B]));
     } else {
       // y = LN2(f), f = x1 + W2 GELU(W1 x1)
-      TRY(k::ln_backward(sh.dtype, dy_blk, sb + L.ln_b, p.w[P_LN2G], reinterpret_cast<const float2*>(sb + L.stats2),
-                         nullptr, ws + WL.d_h0, p.g[P_LN2G], p.g[P_LN2B], partial, T, H, st));
+      TRY(ln_bwd(dy_blk, sb + L.ln_b, p.w[P_LN2G], sb + L.stats2,
+                 nullptr, ws + WL.d_h0, p.g[P_LN2G], p.g[P_LN2B]));
       dw[0] = bwd_params_gemm(sh, sb + L.act, ws + WL.d_h0, p.g[P_W2], p.g[P_B2], F, H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_h0, p.w[P_W2], ws + WL.d_act, F, H, k::EPI_MUL_DGELU, sb + L.hpre, st));
       dw[1] = bwd_params_gemm(sh, sb + L.x1, ws + WL.d_act, p.g[P_W1], p.g[P_B1], H, F, partial);
       // dx1 = df + d_act W1^T
       TRY(linear_bwd_input(sh, ws + WL.d_act, p.w[P_W1], ws + WL.d_h1, H, F, k::EPI_ADD, ws + WL.d_h0, st));
       // x1 = LN1(a), a = x + Wo ctx
-      TRY(k::ln_backward(sh.dtype, ws + WL.d_h1, sb + L.ln_a, p.w[P_LN1G], reinterpret_cast<const float2*>(sb + L.stats1),
-                         nullptr, ws + WL.d_h2, p.g[P_LN1G], p.g[P_LN1B], partial, T, H, st));
+      TRY(ln_bwd(ws + WL.d_h1, sb + L.ln_a, p.w[P_LN1G], sb + L.stats1,
+                 nullptr, ws + WL.d_h2, p.g[P_LN1G], p.g[P_LN1B]));
       dw[2] = bwd_params_gemm(sh, sb + L.ctx, ws + WL.d_h2, p.g[P_WO], p.g[P_BO], H, H, partial);
       TRY(linear_bwd_input(sh, ws + WL.d_h2, p.w[P_WO], ws + WL.d_h3, H, H, k::EPI_NONE, nullptr, st));
       at.dctx = ws + WL.d_h3;  // d_h0 still feeds the W2 gradient
@@ -305,7 +320,7 @@ int chunk_backward(const Shape& sh, const void* weights, float* grads, const voi
     TRY(k::gemm_group(sh.dtype, dw, 4, st));
     dy_blk = dx_blk;
   }
-  return HANAYO_OK;
+  return k::finalize_group(ln_jobs.data(), (int)ln_jobs.size(), st);
 }
 
 int device_ok() { return check_device(); }

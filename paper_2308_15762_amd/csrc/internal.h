@@ -76,9 +76,12 @@ struct WorkLayout {
   size_t d_pong;   // [T][H]
   size_t delta;    // [b][heads][s] float, rowsum(dC * C)
   size_t partial;  // [rows][2H] float, LayerNorm gamma/beta partial sums; also bias-grad partials
+  size_t ln_partial, ln_slot_bytes;  // 2 * nb slots of [kLnPartialRows][2H] float: the partial gamma/beta sums of each
+                                     // LayerNorm of the chunk, kept until one launch adds them all up
   size_t bytes;
 };
 WorkLayout work_layout(const Shape& sh);
 constexpr int kMaxPartialRows = 512;
+constexpr int kLnPartialRows = 256;  // partial rows one LayerNorm backward writes (one per workgroup, one workgroup per CU)
 
 }  // namespace hanayo

@@ -18,6 +18,22 @@ int ln_forward(int dtype, const void* x, const void* gamma, const void* beta, vo
 // `partial` is scratch of at least kMaxPartialRows * 2H floats.
 int ln_backward(int dtype, const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend,
                 void* dz, float* dgamma, float* dbeta, float* partial, int T, int H, hipStream_t stream);
+// The same with the last step left to the caller: dz is written, the gamma/beta sums stay as partial rows in
+// `partial` (kLnPartialRows * 2H floats, untouched until finalize_group has run) and *job says how to add them up.
+// finalize_group runs any number of such jobs, eight to a launch: one launch for all the LayerNorms of a chunk's
+// backward pass instead of one each.
+constexpr int kMaxFinalizeJobs = 8;
+struct FinalizeJob {
+  const float* partial;  // [rows][ld]
+  int rows, ld, n;       // columns c < n: (c < split ? out0[c] : out1[c - split]) += sum over rows of partial[r][c]
+  float* out0;
+  float* out1;
+  int split;
+};
+int ln_backward_deferred(int dtype, const void* dout, const void* x, const void* gamma, const float2* stats,
+                         const void* addend, void* dz, float* dgamma, float* dbeta, float* partial, int T, int H,
+                         hipStream_t stream, FinalizeJob* job);
+int finalize_group(const FinalizeJob* jobs, int count, hipStream_t stream);
 // out[n] += sum_t in[t][n]
 int colsum_add(int dtype, const void* in, int T, int N, float* out, float* partial, hipStream_t stream);
 

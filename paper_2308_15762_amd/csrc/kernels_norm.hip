@@ -16,7 +16,7 @@ namespace k {
 namespace {
 
 constexpr int kRowsPerBlock = 4;  // wavefronts per 256-thread block
-constexpr int kLnBwdMaxBlocks = 256;  // workgroups of the LN backward = partial rows of gamma/beta sums it writes
+constexpr int kLnBwdMaxBlocks = kLnPartialRows;  // workgroups of the LN backward = partial rows of gamma/beta sums it writes
 
 // Eight consecutive elements in storage form: what a load that is still in flight occupies (for bf16 a
 // quarter of the registers of eight floats).
@@ -244,6 +244,33 @@ __global__ __launch_bounds__(kFinalizeCols * kFinalizeGroups) void finalize_kern
   }
 }
 
+// Several finaliser jobs in one launch (blockIdx.y = job): the gamma/beta sums of all the LayerNorms of a
+// chunk's backward pass, whose partial rows wait in slots of their own until the pass is over.
+struct FinalizeJobs {
+  FinalizeJob job[kMaxFinalizeJobs];
+};
+__global__ __launch_bounds__(kFinalizeCols * kFinalizeGroups) void finalize_group_kernel(FinalizeJobs jobs) {
+  const FinalizeJob j = jobs.job[blockIdx.y];
+  if ((int)blockIdx.x * kFinalizeCols >= j.n) return;  // uniform over the workgroup: jobs may differ in width
+  __shared__ float red[kFinalizeGroups][kFinalizeCols];
+  const int cl = threadIdx.x % kFinalizeCols, rg = threadIdx.x / kFinalizeCols;
+  const int c = blockIdx.x * kFinalizeCols + cl;
+  float t = 0.f;
+  if (c < j.n) {
+#pragma unroll 8
+    for (int r = rg; r < j.rows; r += kFinalizeGroups) t += j.partial[(size_t)r * j.ld + c];
+  }
+  red[rg][cl] = t;
+  __syncthreads();
+  if (rg == 0 && c < j.n) {
+    float total = 0.f;
+#pragma unroll
+    for (int g = 0; g < kFinalizeGroups; ++g) total += red[g][cl];
+    float* dst = c < j.split ? j.out0 + c : j.out1 + (c - j.split);
+    *dst += total;
+  }
+}
+
 // ------------------------------------------------------------------ column sums
 // Block = 8 row groups x 32 lanes, each lane owning 8 consecutive columns.
 template <typename T>
@@ -310,7 +337,7 @@ int launch_finalize(const float* partial, int rows, int ld, int n, float* out0, 
 
 template <typename T>
 int ln_backward_t(const void* dout, const void* x, const void* gamma, const float2* stats, const void* addend, void* dz,
-                  float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
+                  float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream, FinalizeJob* later) {
   const int nv = (H + 511) / 512;  // wavefronts that share a row; 16 wavefronts (15 or 14 where nv does not divide 16)
   const int rg = 16 / nv;          // per workgroup walk rg rows at a time
   int blocks = (T_ + rg - 1) / rg;
@@ -339,6 +366,10 @@ int ln_backward_t(const void* dout, const void* x, const void* gamma, const floa
 #undef LAUNCH
   int rc = check_launch("ln_backward");
   if (rc) return rc;
+  if (later) {  // the caller sums the partial rows later, with others (finalize_group)
+    *later = FinalizeJob{partial, blocks, 2 * H, 2 * H, dgamma, dbeta, H};
+    return HANAYO_OK;
+  }
   return launch_finalize(partial, blocks, 2 * H, 2 * H, dgamma, dbeta, H, stream, "ln_backward finalize");
 }
 
@@ -373,8 +404,36 @@ int ln_backward(int dtype, const void* dout, const void* x, const void* gamma, c
                 void* dz, float* dgamma, float* dbeta, float* partial, int T_, int H, hipStream_t stream) {
   if (T_ < 1 || H < 8 || H % 8 || H > 4096) return set_error(HANAYO_EUNSUPPORTED, "ln_backward: H=%d (need multiple of 8, <= 4096)", H);
   return dtype == HANAYO_BF16
-             ? ln_backward_t<bf16>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream)
-             : ln_backward_t<float>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream);
+             ? ln_backward_t<bf16>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream, nullptr)
+             : ln_backward_t<float>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream, nullptr);
+}
+
+int ln_backward_deferred(int dtype, const void* dout, const void* x, const void* gamma, const float2* stats,
+                         const void* addend, void* dz, float* dgamma, float* dbeta, float* partial, int T_, int H,
+                         hipStream_t stream, FinalizeJob* job) {
+  if (T_ < 1 || H < 8 || H % 8 || H > 4096) return set_error(HANAYO_EUNSUPPORTED, "ln_backward: H=%d (need multiple of 8, <= 4096)", H);
+  if (!job) return set_error(HANAYO_EINVAL, "ln_backward_deferred: no job to fill in");
+  return dtype == HANAYO_BF16
+             ? ln_backward_t<bf16>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream, job)
+             : ln_backward_t<float>(dout, x, gamma, stats, addend, dz, dgamma, dbeta, partial, T_, H, stream, job);
+}
+
+int finalize_group(const FinalizeJob* jobs, int count, hipStream_t stream) {
+  for (int first = 0; first < count; first += kMaxFinalizeJobs) {
+    const int n = count - first < kMaxFinalizeJobs ? count - first : kMaxFinalizeJobs;
+    FinalizeJobs batch{};
+    int widest = 0;
+    for (int i = 0; i < n; ++i) {
+      batch.job[i] = jobs[first + i];
+      if (batch.job[i].n > widest) widest = batch.job[i].n;
+    }
+    if (widest < 1) continue;
+    hipLaunchKernelGGL(finalize_group_kernel, dim3((widest + kFinalizeCols - 1) / kFinalizeCols, n),
+                       dim3(kFinalizeCols * kFinalizeGroups), 0, stream, batch);
+    const int rc = check_launch("finalize_group");
+    if (rc) return rc;
+  }
+  return HANAYO_OK;
 }
 
 int colsum_add(int dtype, const void* in, int T_, int N, float* out, float* partial, hipStream_t stream) {

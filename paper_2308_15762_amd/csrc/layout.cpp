@@ -108,6 +108,8 @@ WorkLayout work_layout(const Shape& sh) {
   L.d_pong = take(th);
   L.delta = take(align_up((size_t)sh.b * sh.heads * sh.s * 4, 256));
   L.partial = take(align_up((size_t)kMaxPartialRows * 2 * sh.H * 4, 256));
+  L.ln_slot_bytes = align_up((size_t)kLnPartialRows * 2 * sh.H * 4, 256);
+  L.ln_partial = take(2 * (size_t)sh.nb * L.ln_slot_bytes);
   L.bytes = at;
   return L;
 }
