@@ -913,13 +913,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
 
   const size_t stat = ((size_t)n * p.heads + h) * p.s + q;
   const float my_lse2 = q < p.s ? p.lse[stat] * kLog2e : 0.f;
-  const float my_delta = q < p.s ? p.delta[stat] : 0.f;
   bf16x8 qf[KS], cf[KS];
+  // delta = rowsum(dC * C) of this lane's query row: each half wavefront holds half of the row's
+  // columns.  Written out for the dK/dV kernel, which runs after this one.
+  float my_delta = 0.f;
 #pragma unroll
   for (int kk = 0; kk < KS; ++kk) {
     qf[kk] = frag_global(base + (size_t)q * ld3, q < p.s, kk, lane, p.d);
     cf[kk] = frag_global(p.dctx + ((size_t)n * p.s + q) * H + h * p.d, q < p.s, kk, lane, p.d);
+    const bf16x8 of = frag_global(p.ctx + ((size_t)n * p.s + q) * H + h * p.d, q < p.s, kk, lane, p.d);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) my_delta += (float)cf[kk][e] * (float)of[e];
   }
+  my_delta += __shfl_xor(my_delta, 32, 64);
+  if (q < p.s && half == 0) p.delta[stat] = my_delta;
   f32x16 dq[DT];
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt) dq[dt] = zero16();
@@ -1335,17 +1342,15 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL((attn_bwd_dkv_pipe_kernel<64, 4>), grid, block, lds_dkv, stream, p);
     return check_launch("attn_bwd_pipe");
   }
-  rc = attn_delta(HANAYO_BF16, a, stream);
-  if (rc) return rc;
-  if (dma_ok(a)) {
+  if (dma_ok(a)) {  // likewise: dQ first (it writes delta), then dK/dV
     {
       constexpr size_t lds_dkv = 2 * (2 * SwTile<128>::kBytes + 512), lds_dq = 2 * 2 * SwTile<128>::kBytes;
 #define LAUNCH_BWD(...)                                                                              \
   do {                                                                                               \
     rc = raise_lds(attn_bwd_dkv_dma_kernel<__VA_ARGS__>, lds_dkv);                                   \
     if (rc) return rc;                                                                               \
-    hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<__VA_ARGS__>), grid, block, lds_dkv, stream, p);     \
     hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<__VA_ARGS__>), grid, block, lds_dq, stream, p);       \
+    hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<__VA_ARGS__>), grid, block, lds_dkv, stream, p);     \
   } while (0)
       if (a.d == 128) LAUNCH_BWD(128, 2);
       else if (a.d == 96) LAUNCH_BWD(128, 2, 96);
@@ -1354,6 +1359,8 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
     }
     return check_launch("attn_bwd_dma");
   }
+  rc = attn_delta(HANAYO_BF16, a, stream);
+  if (rc) return rc;
   if (a.d <= 64) {
     hipLaunchKernelGGL((attn_bwd_dkv_kernel<64>), grid, block, 0, stream, p);
     hipLaunchKernelGGL((attn_bwd_dq_kernel<64>), grid, block, 0, stream, p);
