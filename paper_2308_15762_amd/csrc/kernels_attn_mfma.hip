@@ -765,7 +765,7 @@ __global__ __launch_bounds__(256) void attn_fwd_pipe_wide_kernel(AttnDev p) {
 }
 
 template <int DP, int NST, int D = DP>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
+__device__ __forceinline__ void attn_bwd_dkv_dma_body(const AttnDev& p) {
   using Tile = SwTile<DP>;
   constexpr int BQ = 64, KS = D / 16, DT = (D + 31) / 32;  // D = head dim in memory, DP = LDS row layout
   constexpr int STAGE = 2 * Tile::kBytes + 512;  // Q tile, dC tile, 64 lse, 64 delta
@@ -884,7 +884,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
 }
 
 template <int DP, int NST, int D = DP>
-__global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
+__global__ __launch_bounds__(256) void attn_bwd_dkv_dma_kernel(AttnDev p) {
+  attn_bwd_dkv_dma_body<DP, NST, D>(p);
+}
+// The same under a cap of 256 registers, so that two workgroups share a CU.
+template <int DP, int NST, int D = DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dkv_dma2_kernel(AttnDev p) {
+  attn_bwd_dkv_dma_body<DP, NST, D>(p);
+}
+
+template <int DP, int NST, int D = DP>
+__device__ __forceinline__ void attn_bwd_dq_dma_body(const AttnDev& p) {
   using Tile = SwTile<DP>;
   constexpr int BKV = 64, KS = D / 16, DT = (D + 31) / 32;  // D = head dim in memory, DP = LDS row layout
   constexpr int STAGE = 2 * Tile::kBytes, LOADS = 2 * Tile::kPerWave;
@@ -980,6 +990,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
         *reinterpret_cast<bf16x4*>(out + col) = v;
       }
   }
+}
+
+template <int DP, int NST, int D = DP>
+__global__ __launch_bounds__(256) void attn_bwd_dq_dma_kernel(AttnDev p) {
+  attn_bwd_dq_dma_body<DP, NST, D>(p);
+}
+template <int DP, int NST, int D = DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_bwd_dq_dma2_kernel(AttnDev p) {
+  attn_bwd_dq_dma_body<DP, NST, D>(p);
 }
 
 // dK / dV, software-pipelined in half tiles of 32 queries like attn_bwd_dq_pipe_kernel: the score
@@ -1352,10 +1371,21 @@ int attn_backward_mfma(const AttnArgs& a, hipStream_t stream) {
     hipLaunchKernelGGL((attn_bwd_dq_dma_kernel<__VA_ARGS__>), grid, block, lds_dq, stream, p);       \
     hipLaunchKernelGGL((attn_bwd_dkv_dma_kernel<__VA_ARGS__>), grid, block, lds_dkv, stream, p);     \
   } while (0)
+      // Head dims 80 and 96 fit 256 registers (218 - 255, nothing spilled), so two workgroups share a CU: 118 -> 103 us
+      // at d = 80, s = 1024, 64 (sequence, head) pairs.  Head dim 128 does not (72 - 92 bytes of scratch per lane and
+      // 230 -> 315 us under the cap) and runs one workgroup per CU.
+#define LAUNCH_BWD2(...)                                                                             \
+  do {                                                                                               \
+    rc = raise_lds(attn_bwd_dkv_dma2_kernel<__VA_ARGS__>, lds_dkv);                                  \
+    if (rc) return rc;                                                                               \
+    hipLaunchKernelGGL((attn_bwd_dq_dma2_kernel<__VA_ARGS__>), grid, block, lds_dq, stream, p);      \
+    hipLaunchKernelGGL((attn_bwd_dkv_dma2_kernel<__VA_ARGS__>), grid, block, lds_dkv, stream, p);    \
+  } while (0)
       if (a.d == 128) LAUNCH_BWD(128, 2);
-      else if (a.d == 96) LAUNCH_BWD(128, 2, 96);
-      else LAUNCH_BWD(128, 2, 80);
+      else if (a.d == 96) LAUNCH_BWD2(128, 2, 96);
+      else LAUNCH_BWD2(128, 2, 80);
 #undef LAUNCH_BWD
+#undef LAUNCH_BWD2
     }
     return check_launch("attn_bwd_dma");
   }
