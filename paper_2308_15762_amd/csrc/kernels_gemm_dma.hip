@@ -222,15 +222,21 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
   unsigned stage_next = 0;  // buffer index the next issued tile goes to
   const unsigned wave_lds_a = lds0 + wave * OpA::kPerWave * 1024;
   const unsigned wave_lds_b = lds0 + OpA::kBytes + wave * OpB::kPerWave * 1024;
-  auto issue = [&]() {
+  // the i-th of the LOADS direct loads of the next tile (i is a compile-time constant at every call)
+  auto issue_part = [&](int i) {
     const unsigned st = stage_next * STAGE_BYTES;
-#pragma unroll
-    for (int i = 0; i < OpA::kPerWave; ++i) dma16(a_next, voff_a[i], wave_lds_a + st + i * 1024);
-#pragma unroll
-    for (int i = 0; i < OpB::kPerWave; ++i) dma16(b_next, voff_b[i], wave_lds_b + st + i * 1024);
+    if (i < OpA::kPerWave) dma16(a_next, voff_a[i], wave_lds_a + st + i * 1024);
+    else dma16(b_next, voff_b[i - OpA::kPerWave], wave_lds_b + st + (i - OpA::kPerWave) * 1024);
+  };
+  auto issue_done = [&]() {
     a_next += a_step;
     b_next += b_step;
     stage_next = stage_next + 1 == NSTAGE ? 0 : stage_next + 1;
+  };
+  auto issue = [&]() {
+#pragma unroll
+    for (int i = 0; i < LOADS; ++i) issue_part(i);
+    issue_done();
   };
 
   f32x16 acc[TM][TN];
@@ -315,7 +321,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     colsum_tile(0);
     read_a(0, 0, fa[0]);
     read_b(0, 0, fb[0]);
-    for (int kt = 0; kt + 1 < nk; ++kt) {
+    auto steps_before_barrier = [&](int kt) {
 #pragma unroll
       for (int st = 0; st + 1 < KS; ++st) {
         read_a(kt, st + 1, fa[(st + 1) & 1]);
@@ -326,14 +332,40 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
       }
       // the buffer of tile kt is overwritten right after the barrier: its last fragments must have arrived
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      if (kt + NSTAGE < nk) {  // steady state: tiles kt+2 .. kt+NSTAGE-1 may still be in flight
-        wait_vmcnt<(NSTAGE - 2) * LOADS>();
-        __syncthreads();
-        issue();
-      } else {
-        wait_tiles<LOADS>(min(NSTAGE - 2, nk - 2 - kt));
-        __syncthreads();
-      }
+    };
+    int kt = 0;
+    // Steady state: tiles kt+2 .. kt+NSTAGE-1 may still be in flight at the barrier, and tile kt+NSTAGE is started
+    // after it.  Every wavefront of the workgroup leaves the barrier in the same phase, so whatever stands between
+    // the barrier and the next MFMA is time the matrix pipe idles on all four SIMDs at once.  The last step's
+    // fragments are in registers: its MFMAs start at once, and the tile's direct loads and the first fragment
+    // reads of tile kt+1 go out between them.
+    for (; kt + NSTAGE < nk; ++kt) {
+      steps_before_barrier(kt);
+      wait_vmcnt<(NSTAGE - 2) * LOADS>();
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      read_a(kt + 1, 0, fa[0]);
+      read_b(kt + 1, 0, fb[0]);
+      constexpr int kMf = TM * TN, kPer = (LOADS + kMf - 1) / kMf;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[(KS - 1) & 1][j], fa[(KS - 1) & 1][i], acc[i][j], 0, 0, 0);
+#pragma unroll
+          for (int u = 0; u < kPer; ++u)
+            if ((i * TN + j) * kPer + u < LOADS) issue_part((i * TN + j) * kPer + u);
+        }
+      issue_done();
+      interleave();
+      __builtin_amdgcn_sched_barrier(0);
+      colsum_tile(kt + 1);
+    }
+    // The last tiles: nothing left to start.
+    for (; kt + 1 < nk; ++kt) {
+      steps_before_barrier(kt);
+      wait_tiles<LOADS>(min(NSTAGE - 2, nk - 2 - kt));
+      __syncthreads();
       colsum_tile(kt + 1);
       __builtin_amdgcn_sched_barrier(0);
       read_a(kt + 1, 0, fa[0]);
