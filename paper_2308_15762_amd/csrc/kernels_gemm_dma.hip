@@ -344,21 +344,31 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
       wait_vmcnt<(NSTAGE - 2) * LOADS>();
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
-      read_a(kt + 1, 0, fa[0]);
-      read_b(kt + 1, 0, fb[0]);
-      constexpr int kMf = TM * TN, kPer = (LOADS + kMf - 1) / kMf;
+      constexpr int kMf = TM * TN, kPer = (LOADS + kMf - 1) / kMf, kFr = (TM + TN + kMf - 1) / kMf;
+      const char* a_nx = smem + ((kt + 1) % NSTAGE) * STAGE_BYTES;
+      const char* b_nx = a_nx + OpA::kBytes;
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
+          const int m = i * TN + j;  // one slot per MFMA: its share of the fragment reads and of the direct loads
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[(KS - 1) & 1][j], fa[(KS - 1) & 1][i], acc[i][j], 0, 0, 0);
 #pragma unroll
+          for (int u = 0; u < kFr; ++u) {
+            const int f = m * kFr + u;
+            if (f < TM)
+              fa[0][f] = A_T ? frag_t<OpA::kSlotsPerRow>(a_nx, wm * WM + f * 32, 0, lane)
+                             : frag_k<OpA::kSlotsPerRow>(a_nx, wm * WM + f * 32, 0, lane);
+            else if (f < TM + TN)
+              fb[0][f - TM] = B_T ? frag_t<OpB::kSlotsPerRow>(b_nx, wn * WN + (f - TM) * 32, 0, lane)
+                                  : frag_k<OpB::kSlotsPerRow>(b_nx, wn * WN + (f - TM) * 32, 0, lane);
+          }
+#pragma unroll
           for (int u = 0; u < kPer; ++u)
-            if ((i * TN + j) * kPer + u < LOADS) issue_part((i * TN + j) * kPer + u);
+            if (m * kPer + u < LOADS) issue_part(m * kPer + u);
+          __builtin_amdgcn_sched_barrier(0);
         }
       issue_done();
-      interleave();
-      __builtin_amdgcn_sched_barrier(0);
       colsum_tile(kt + 1);
     }
     // The last tiles: nothing left to start.
