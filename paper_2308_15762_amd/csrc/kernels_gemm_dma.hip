@@ -337,8 +337,10 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     // Steady state: tiles kt+2 .. kt+NSTAGE-1 may still be in flight at the barrier, and tile kt+NSTAGE is started
     // after it.  Every wavefront of the workgroup leaves the barrier in the same phase, so whatever stands between
     // the barrier and the next MFMA is time the matrix pipe idles on all four SIMDs at once.  The last step's
-    // fragments are in registers: its MFMAs start at once, and the tile's direct loads and the first fragment
-    // reads of tile kt+1 go out between them.
+    // fragments are in registers: its MFMAs start at once, and behind each of them goes its share of the tile's
+    // direct loads and of the first fragment reads of tile kt+1, one or two instructions, held there by
+    // scheduling barriers.  (Left to the scheduler the loads, each with its M0 set-up, go out in runs of four
+    // between two MFMAs; both wavefronts of a SIMD do that at the same moment and the pipe idles meanwhile.)
     for (; kt + NSTAGE < nk; ++kt) {
       steps_before_barrier(kt);
       wait_vmcnt<(NSTAGE - 2) * LOADS>();
