@@ -321,9 +321,45 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
     colsum_tile(0);
     read_a(0, 0, fa[0]);
     read_b(0, 0, fb[0]);
+    // A tile's direct loads go out one behind each MFMA: the first kFirst in the step after the barrier, the rest
+    // (a 4-wavefront tile has more loads per wavefront than MFMAs per step) in step 0 of the next tile; `pending`
+    // says that this rest is still to be issued.
+    // (Only with three stages: with two, the rest would have less than a tile's time to land.)
+    constexpr int kMf = TM * TN, kFirst = (LOADS < kMf || NSTAGE < 3) ? LOADS : kMf, kRest = LOADS - kFirst;
+    constexpr int kPer = (kFirst + kMf - 1) / kMf;
+    static_assert(kRest <= kMf, "at most two steps' worth of loads per tile");
+    bool pending = false;
     auto steps_before_barrier = [&](int kt) {
+      {  // step 0, one slot per MFMA: behind it, its share of step 1's fragment reads and of the pending loads
+        const char* a_cur = smem + (kt % NSTAGE) * STAGE_BYTES;
+        const char* b_cur = a_cur + OpA::kBytes;
+        constexpr int kFr = (TM + TN + kMf - 1) / kMf;
 #pragma unroll
-      for (int st = 0; st + 1 < KS; ++st) {
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const int m = i * TN + j;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[0][j], fa[0][i], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < kFr; ++u) {
+              const int f = m * kFr + u;
+              if (f < TM)
+                fa[1][f] = A_T ? frag_t<OpA::kSlotsPerRow>(a_cur, wm * WM + f * 32, 1, lane)
+                               : frag_k<OpA::kSlotsPerRow>(a_cur, wm * WM + f * 32, 1, lane);
+              else if (f < TM + TN)
+                fb[1][f - TM] = B_T ? frag_t<OpB::kSlotsPerRow>(b_cur, wn * WN + (f - TM) * 32, 1, lane)
+                                    : frag_k<OpB::kSlotsPerRow>(b_cur, wn * WN + (f - TM) * 32, 1, lane);
+            }
+            if (m < kRest && pending) issue_part(kFirst + m);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        if (kRest > 0 && pending) {
+          issue_done();
+          pending = false;
+        }
+      }
+#pragma unroll
+      for (int st = 1; st + 1 < KS; ++st) {
         read_a(kt, st + 1, fa[(st + 1) & 1]);
         read_b(kt, st + 1, fb[(st + 1) & 1]);
         mfma_step(fa[st & 1], fb[st & 1]);
@@ -346,7 +382,7 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
       wait_vmcnt<(NSTAGE - 2) * LOADS>();
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
-      constexpr int kMf = TM * TN, kPer = (LOADS + kMf - 1) / kMf, kFr = (TM + TN + kMf - 1) / kMf;
+      constexpr int kFr = (TM + TN + kMf - 1) / kMf;
       const char* a_nx = smem + ((kt + 1) % NSTAGE) * STAGE_BYTES;
       const char* b_nx = a_nx + OpA::kBytes;
 #pragma unroll
@@ -367,10 +403,11 @@ __global__ __launch_bounds__(WGM* WGN*(MODE == 2 ? 2 : 1) * 64) void gemm_dma_ke
           }
 #pragma unroll
           for (int u = 0; u < kPer; ++u)
-            if (m * kPer + u < LOADS) issue_part(m * kPer + u);
+            if (m * kPer + u < kFirst) issue_part(m * kPer + u);
           __builtin_amdgcn_sched_barrier(0);
         }
-      issue_done();
+      if (kRest > 0) pending = true;  // the rest goes out in step 0 of tile kt+1, which advances the loader's state
+      else issue_done();
       colsum_tile(kt + 1);
     }
     // The last tiles: nothing left to start.
