@@ -61,6 +61,11 @@ def test_sizes_and_param_layout():
             off += cnt
     assert hn.hanayo_stash_bytes(d) % 256 == 0 and hn.hanayo_stash_bytes(d) >= 2 * 256 * (8 * H + 2 * F) * 2
     assert hn.hanayo_workspace_bytes(d) > 0
+    # the workspace holds one slot of 256 partial rows [gamma sums | beta sums] per LayerNorm of the chunk (two per
+    # block): they wait there until one launch adds them all to the gradients; nothing else in it depends on the
+    # number of blocks
+    d3 = hn.make_desc(3, 256, 4, 1024, 128, 2, hn.PRE_LN, hn.MASK_CAUSAL, hn.BF16)
+    assert hn.hanayo_workspace_bytes(d3) - hn.hanayo_workspace_bytes(d) == 2 * 256 * 2 * H * 4
     for bad in [hn.make_desc(1, 250, 4, 1024, 128, 2, 0, 1, 1), hn.make_desc(1, 256, 3, 1024, 128, 2, 0, 1, 1),
                 hn.make_desc(0, 256, 4, 1024, 128, 2, 0, 1, 1), hn.make_desc(1, 256, 4, 1024, 128, 2, 2, 1, 1),
                 hn.make_desc(1, 8192, 64, 1024, 128, 2, 0, 1, 1)]:
